@@ -1,0 +1,117 @@
+"""TEST INFRASTRUCTURE -- not part of the product path.
+
+ctypes front end of the float64 CPU oracle in ``tfno_oracle.c`` (the plain
+definition of the TurboFNO spectral convolution, Sec. 2.1 / 3.1 / 3.3 of the
+paper).  Only tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It imports nothing from the HIP package
+and the HIP package imports nothing from here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tfno_oracle.c")
+_LIB = os.path.join(_HERE, "libtfno_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (fp64, OpenMP over batch elements)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c_int, c_void = ctypes.c_int, ctypes.c_void_p
+        for name in ("oracle_spectral_conv1d", "oracle_spectral_conv2d"):
+            fn = getattr(lib, name)
+            fn.restype = c_int
+            fn.argtypes = [c_void, c_void, c_void] + [c_int] * 6
+        lib.oracle_forward_spectrum1d.restype = c_int
+        lib.oracle_forward_spectrum1d.argtypes = [c_void, c_void, c_int, c_int]
+        for name in ("oracle_fft_c128", "oracle_fft_radix2_c128", "oracle_dft_direct_c128"):
+            fn = getattr(lib, name)
+            fn.restype = None
+            fn.argtypes = [c_void, c_void, c_int, c_int]
+        _lib = lib
+    return _lib
+
+
+def _c64(a: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.complex64:
+        raise TypeError("oracle inputs are complex64 (the fp32 bits the GPU also reads)")
+    return a
+
+
+def spectral_conv1d(x: np.ndarray, W: np.ndarray, K: int, threads: int = 0):
+    """y[B,C_out,N] (complex128) for x[B,C_in,N], W[C_in,C_out] (complex64).
+
+    Returns (y, threads_used)."""
+    x, W = _c64(x), _c64(W)
+    B, C_in, N = x.shape
+    C_in2, C_out = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N), dtype=np.complex128)
+    used = _load().oracle_spectral_conv1d(x.ctypes.data, W.ctypes.data, y.ctypes.data,
+                                          B, C_in, C_out, N, K, threads)
+    if used < 0:
+        raise ValueError("oracle_spectral_conv1d: bad arguments")
+    return y, used
+
+
+def spectral_conv2d(x: np.ndarray, W: np.ndarray, K: int, threads: int = 0):
+    """y[B,C_out,N,N] (complex128) for x[B,C_in,N,N], W[C_in,C_out] (complex64)."""
+    x, W = _c64(x), _c64(W)
+    B, C_in, N, N2 = x.shape
+    assert N == N2
+    C_in2, C_out = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N, N), dtype=np.complex128)
+    used = _load().oracle_spectral_conv2d(x.ctypes.data, W.ctypes.data, y.ctypes.data,
+                                          B, C_in, C_out, N, K, threads)
+    if used < 0:
+        raise ValueError("oracle_spectral_conv2d: bad arguments")
+    return y, used
+
+
+def forward_spectrum1d(x: np.ndarray) -> np.ndarray:
+    """Untruncated, unscaled forward spectra of x[C,N] (complex64) -> complex128."""
+    x = _c64(x)
+    C, N = x.shape
+    out = np.empty((C, N), dtype=np.complex128)
+    if _load().oracle_forward_spectrum1d(x.ctypes.data, out.ctypes.data, C, N) != 0:
+        raise ValueError("oracle_forward_spectrum1d: bad arguments")
+    return out
+
+
+def _xform(name: str, v: np.ndarray, sign: int) -> np.ndarray:
+    v = np.ascontiguousarray(v, dtype=np.complex128)
+    out = np.empty_like(v)
+    getattr(_load(), name)(v.ctypes.data, out.ctypes.data, v.shape[0], sign)
+    return out
+
+
+def fft(v, sign=-1):
+    """The transform the oracle uses (direct for N<=32 or non power of two, radix-2 else)."""
+    return _xform("oracle_fft_c128", v, sign)
+
+
+def fft_radix2(v, sign=-1):
+    return _xform("oracle_fft_radix2_c128", v, sign)
+
+
+def dft_direct(v, sign=-1):
+    return _xform("oracle_dft_direct_c128", v, sign)

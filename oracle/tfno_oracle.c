@@ -1,0 +1,280 @@
+/*
+ * TEST INFRASTRUCTURE -- NOT PART OF THE PRODUCT PATH.
+ *
+ * Float64 CPU oracle for the FNO Fourier-layer spectral convolution of
+ * TurboFNO (arxiv 2504.11681).  Only tests, the smoke check and the
+ * benchmark's cpu_baseline leg may link or call this file.  It shares no
+ * code, header, table or constant with the HIP library.
+ *
+ * What it computes is the plain definition of the operator (Sec. 2.1: forward
+ * FFT, truncation to the low modes, complex linear layer over the hidden
+ * dimension, zero padding back to full length, inverse FFT; Sec. 3.1 fixes the
+ * GEMM shape M = batch x modes, N = OutputDim, K = HiddenDim, i.e. ONE weight
+ * matrix shared by every mode; Sec. 3.3 fixes which bins survive: the first
+ * K of N along each transformed axis).  Fusion, pruning, built-in truncation
+ * and built-in padding (Sec. 3.3, Sec. 4) only skip or reorder exact
+ * arithmetic, so the definition itself is the oracle:
+ *
+ *   Xh[b,c,k] = sum_n  x[b,c,n] exp(-2 pi i k n / N)            k = 0..K-1
+ *   Yh[b,o,k] = sum_c  Xh[b,c,k] W[c,o]
+ *   y [b,o,n] = (1/N) sum_{k<K} Yh[b,o,k] exp(+2 pi i k n / N)   n = 0..N-1
+ *
+ * and in 2-D the same with (n1,n2), (k1,k2) in [0,K)x[0,K), scale 1/N^2.
+ *
+ * Readings taken where the paper is silent: forward exponent negative, inverse
+ * positive and scaled by 1/N per axis (the cuFFT/PyTorch convention the paper
+ * benchmarks against, Sec. 5); no conjugation of W; W is [C_in, C_out]
+ * row-major; tensors are [B, C, N] / [B, C, N, N] row-major interleaved
+ * (re, im).
+ *
+ * No blocking, no pruning, no fusion: a full N-point transform is taken and
+ * bins are then discarded / zero-filled.  Transform: direct O(N^2) DFT for
+ * N <= 32 or N not a power of two, textbook recursive radix-2
+ * decimation-in-time otherwise.  Contraction: naive triple loop.
+ */
+#include <complex.h>
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef double complex cplx;
+
+static const double TWO_PI = 6.283185307179586476925286766559;
+
+/* out[k] = sum_n in[n] exp(sign * 2 pi i k n / N), strided input/output. */
+void oracle_dft_direct(const cplx *in, long istride, cplx *out, long ostride, int N, int sign)
+{
+    for (int k = 0; k < N; ++k) {
+        cplx acc = 0.0;
+        for (int n = 0; n < N; ++n) {
+            /* reduce k*n mod N before forming the angle: keeps the argument small */
+            long kn = ((long)k * (long)n) % N;
+            double ang = sign * TWO_PI * (double)kn / (double)N;
+            acc += in[n * istride] * (cos(ang) + I * sin(ang));
+        }
+        out[k * ostride] = acc;
+    }
+}
+
+/* Recursive radix-2 decimation in time.  N power of two.  tmp: N scratch. */
+static void fft_rec(const cplx *in, long istride, cplx *out, int N, int sign, cplx *tmp)
+{
+    if (N == 1) { out[0] = in[0]; return; }
+    int h = N / 2;
+    /* even samples -> out[0..h), odd samples -> out[h..N), each transformed */
+    fft_rec(in,           2 * istride, tmp,     h, sign, out);
+    fft_rec(in + istride, 2 * istride, tmp + h, h, sign, out + h);
+    for (int k = 0; k < h; ++k) {
+        double ang = sign * TWO_PI * (double)k / (double)N;
+        cplx w = cos(ang) + I * sin(ang);
+        cplx e = tmp[k], o = w * tmp[h + k];
+        out[k]     = e + o;
+        out[k + h] = e - o;
+    }
+}
+
+static int is_pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
+
+/* Full N-point transform of a strided sequence into a contiguous buffer.
+ * out and scratch hold N elements each; no scaling. */
+void oracle_fft(const cplx *in, long istride, cplx *out, int N, int sign, cplx *scratch)
+{
+    if (N <= 32 || !is_pow2(N))
+        oracle_dft_direct(in, istride, out, 1, N, sign);
+    else
+        fft_rec(in, istride, out, N, sign, scratch);
+}
+
+/* Same, forcing the radix-2 path (N power of two); for the pin tests. */
+void oracle_fft_radix2(const cplx *in, long istride, cplx *out, int N, int sign, cplx *scratch)
+{
+    fft_rec(in, istride, out, N, sign, scratch);
+}
+
+/* ------------------------------------------------------------------ 1-D -- */
+
+/* One batch element.  x: [C_in, N] c64 (float pairs).  W: [C_in, C_out] c64.
+ * y: [C_out, N] complex double.  Xh_full (optional, may be NULL): [C_in, N]
+ * untruncated forward spectra, for the Parseval pin. */
+static void conv1d_one(const float *x, const float *W, cplx *y, cplx *Xh_full,
+                       int C_in, int C_out, int N, int K)
+{
+    cplx *sig = malloc(sizeof(cplx) * N);
+    cplx *spec = malloc(sizeof(cplx) * N);
+    cplx *scr = malloc(sizeof(cplx) * N);
+    cplx *Xh = malloc(sizeof(cplx) * (size_t)C_in * K);   /* truncated */
+    cplx *Yh = malloc(sizeof(cplx) * (size_t)C_out * K);
+
+    /* forward transform of every input channel, keep bins 0..K-1 (Sec. 3.3) */
+    for (int c = 0; c < C_in; ++c) {
+        for (int n = 0; n < N; ++n)
+            sig[n] = (double)x[2 * ((size_t)c * N + n)] + I * (double)x[2 * ((size_t)c * N + n) + 1];
+        oracle_fft(sig, 1, spec, N, -1, scr);
+        if (Xh_full) memcpy(Xh_full + (size_t)c * N, spec, sizeof(cplx) * N);
+        for (int k = 0; k < K; ++k) Xh[(size_t)c * K + k] = spec[k];
+    }
+    /* complex linear layer over the hidden dimension, same W for every mode (Sec. 3.1) */
+    for (int o = 0; o < C_out; ++o)
+        for (int k = 0; k < K; ++k) {
+            cplx acc = 0.0;
+            for (int c = 0; c < C_in; ++c) {
+                cplx w = (double)W[2 * ((size_t)c * C_out + o)] + I * (double)W[2 * ((size_t)c * C_out + o) + 1];
+                acc += Xh[(size_t)c * K + k] * w;
+            }
+            Yh[(size_t)o * K + k] = acc;
+        }
+    /* zero-pad to N, inverse transform, scale 1/N */
+    for (int o = 0; o < C_out; ++o) {
+        for (int k = 0; k < N; ++k) spec[k] = (k < K) ? Yh[(size_t)o * K + k] : 0.0;
+        oracle_fft(spec, 1, sig, N, +1, scr);
+        for (int n = 0; n < N; ++n) y[(size_t)o * N + n] = sig[n] / (double)N;
+    }
+    free(sig); free(spec); free(scr); free(Xh); free(Yh);
+}
+
+/* x: [B, C_in, N] c64;  W: [C_in, C_out] c64;  y: [B, C_out, N] complex128.
+ * Batch elements are independent and are spread over `threads` host threads.
+ * Returns the number of threads actually used, or -1 on bad arguments. */
+int oracle_spectral_conv1d(const float *x, const float *W, double *y,
+                           int B, int C_in, int C_out, int N, int K, int threads)
+{
+    if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N <= 0 || K <= 0 || K > N) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+        #pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < B; ++b)
+            conv1d_one(x + 2 * (size_t)b * C_in * N, W, (cplx *)y + (size_t)b * C_out * N, NULL,
+                       C_in, C_out, N, K);
+    }
+#else
+    (void)threads;
+    for (int b = 0; b < B; ++b)
+        conv1d_one(x + 2 * (size_t)b * C_in * N, W, (cplx *)y + (size_t)b * C_out * N, NULL,
+                   C_in, C_out, N, K);
+#endif
+    return used;
+}
+
+/* Untruncated forward spectra of one [C, N] block (no scaling): Xh[c,k], k < N. */
+int oracle_forward_spectrum1d(const float *x, double *Xh, int C, int N)
+{
+    if (!x || !Xh || C <= 0 || N <= 0) return -1;
+    cplx *sig = malloc(sizeof(cplx) * N), *scr = malloc(sizeof(cplx) * N);
+    for (int c = 0; c < C; ++c) {
+        for (int n = 0; n < N; ++n)
+            sig[n] = (double)x[2 * ((size_t)c * N + n)] + I * (double)x[2 * ((size_t)c * N + n) + 1];
+        oracle_fft(sig, 1, (cplx *)Xh + (size_t)c * N, N, -1, scr);
+    }
+    free(sig); free(scr);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ 2-D -- */
+
+/* In-place full 2-D transform of an N x N row-major image (no scaling):
+ * every row along the last axis, then every column along the first. */
+static void fft2_inplace(cplx *img, int N, int sign, cplx *line, cplx *scr)
+{
+    for (int r = 0; r < N; ++r) {
+        oracle_fft(img + (size_t)r * N, 1, line, N, sign, scr);
+        memcpy(img + (size_t)r * N, line, sizeof(cplx) * N);
+    }
+    for (int c = 0; c < N; ++c) {
+        oracle_fft(img + c, N, line, N, sign, scr);
+        for (int r = 0; r < N; ++r) img[(size_t)r * N + c] = line[r];
+    }
+}
+
+/* One batch element.  x: [C_in, N, N] c64;  y: [C_out, N, N] complex double. */
+static void conv2d_one(const float *x, const float *W, cplx *y,
+                       int C_in, int C_out, int N, int K)
+{
+    size_t NN = (size_t)N * N, KK = (size_t)K * K;
+    cplx *img = malloc(sizeof(cplx) * NN);
+    cplx *line = malloc(sizeof(cplx) * N), *scr = malloc(sizeof(cplx) * N);
+    cplx *Xh = malloc(sizeof(cplx) * C_in * KK);
+    cplx *Yh = malloc(sizeof(cplx) * C_out * KK);
+
+    for (int c = 0; c < C_in; ++c) {
+        const float *xc = x + 2 * (size_t)c * NN;
+        for (size_t i = 0; i < NN; ++i) img[i] = (double)xc[2 * i] + I * (double)xc[2 * i + 1];
+        fft2_inplace(img, N, -1, line, scr);
+        /* keep the single low corner [0,K) x [0,K) */
+        for (int k1 = 0; k1 < K; ++k1)
+            for (int k2 = 0; k2 < K; ++k2)
+                Xh[c * KK + (size_t)k1 * K + k2] = img[(size_t)k1 * N + k2];
+    }
+    for (int o = 0; o < C_out; ++o)
+        for (size_t m = 0; m < KK; ++m) {
+            cplx acc = 0.0;
+            for (int c = 0; c < C_in; ++c) {
+                cplx w = (double)W[2 * ((size_t)c * C_out + o)] + I * (double)W[2 * ((size_t)c * C_out + o) + 1];
+                acc += Xh[c * KK + m] * w;
+            }
+            Yh[o * KK + m] = acc;
+        }
+    double scale = 1.0 / ((double)N * (double)N);
+    for (int o = 0; o < C_out; ++o) {
+        for (size_t i = 0; i < NN; ++i) img[i] = 0.0;
+        for (int k1 = 0; k1 < K; ++k1)
+            for (int k2 = 0; k2 < K; ++k2)
+                img[(size_t)k1 * N + k2] = Yh[o * KK + (size_t)k1 * K + k2];
+        fft2_inplace(img, N, +1, line, scr);
+        cplx *yo = y + (size_t)o * NN;
+        for (size_t i = 0; i < NN; ++i) yo[i] = img[i] * scale;
+    }
+    free(img); free(line); free(scr); free(Xh); free(Yh);
+}
+
+/* x: [B, C_in, N, N] c64;  W: [C_in, C_out] c64;  y: [B, C_out, N, N] complex128. */
+int oracle_spectral_conv2d(const float *x, const float *W, double *y,
+                           int B, int C_in, int C_out, int N, int K, int threads)
+{
+    if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N <= 0 || K <= 0 || K > N) return -1;
+    int used = 1;
+    size_t NN = (size_t)N * N;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+        #pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < B; ++b)
+            conv2d_one(x + 2 * (size_t)b * C_in * NN, W, (cplx *)y + (size_t)b * C_out * NN,
+                       C_in, C_out, N, K);
+    }
+#else
+    (void)threads;
+    for (int b = 0; b < B; ++b)
+        conv2d_one(x + 2 * (size_t)b * C_in * NN, W, (cplx *)y + (size_t)b * C_out * NN,
+                   C_in, C_out, N, K);
+#endif
+    return used;
+}
+
+/* Thin complex128 entry points for the pin tests (buffers interleaved doubles). */
+void oracle_fft_c128(const double *in, double *out, int N, int sign)
+{
+    cplx *scr = malloc(sizeof(cplx) * (N > 0 ? N : 1));
+    oracle_fft((const cplx *)in, 1, (cplx *)out, N, sign, scr);
+    free(scr);
+}
+void oracle_fft_radix2_c128(const double *in, double *out, int N, int sign)
+{
+    cplx *scr = malloc(sizeof(cplx) * (N > 0 ? N : 1));
+    oracle_fft_radix2((const cplx *)in, 1, (cplx *)out, N, sign, scr);
+    free(scr);
+}
+void oracle_dft_direct_c128(const double *in, double *out, int N, int sign)
+{
+    oracle_dft_direct((const cplx *)in, 1, (cplx *)out, 1, N, sign);
+}

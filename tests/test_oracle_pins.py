@@ -1,0 +1,267 @@
+"""Pins for the float64 oracle: none of them re-types the oracle's own formula.
+
+They check it against brute force, closed forms, invariants and NumPy's FFT
+(library special case), chosen so that a dropped term, a wrong sign or index, a
+transposed W or a wrong normalisation fails at least one of them.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2504_11681_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng(1234)
+
+
+def crandn(*shape):
+    return (rng.standard_normal(shape) + 1j * rng.standard_normal(shape)).astype(np.complex64)
+
+
+# ---------------------------------------------------------------- transform --
+
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 16, 32, 64, 128, 1024])
+@pytest.mark.parametrize("sign", [-1, +1])
+def test_radix2_equals_brute_force(oracle_mod, N, sign):
+    v = crandn(N).astype(np.complex128)
+    a = oracle_mod.fft_radix2(v, sign)
+    b = oracle_mod.dft_direct(v, sign)
+    assert np.max(np.abs(a - b)) <= 1e-12 * max(1.0, N) * np.max(np.abs(b))
+
+
+@pytest.mark.parametrize("N", [3, 5, 12, 32, 64, 256])
+def test_transform_matches_numpy_fft(oracle_mod, N):
+    v = crandn(N).astype(np.complex128)
+    assert np.allclose(oracle_mod.fft(v, -1), np.fft.fft(v), rtol=0, atol=1e-11 * N)
+    assert np.allclose(oracle_mod.fft(v, +1), np.fft.ifft(v) * N, rtol=0, atol=1e-11 * N)
+
+
+@pytest.mark.parametrize("N", [8, 64, 256])
+def test_unit_impulse_gives_all_ones(oracle_mod, N):
+    v = np.zeros(N, dtype=np.complex128)
+    v[0] = 1.0
+    assert np.allclose(oracle_mod.fft(v, -1), np.ones(N), atol=1e-14)
+    # shifted impulse: a pure phase ramp with the forward (negative) sign
+    v[:] = 0
+    v[1] = 1.0
+    k = np.arange(N)
+    assert np.allclose(oracle_mod.fft(v, -1), np.exp(-2j * np.pi * k / N), atol=1e-13)
+
+
+def test_parseval_on_untruncated_forward_stage(oracle_mod):
+    x = crandn(5, 128)
+    Xh = oracle_mod.forward_spectrum1d(x)
+    lhs = np.sum(np.abs(x.astype(np.complex128)) ** 2, axis=-1)
+    rhs = np.sum(np.abs(Xh) ** 2, axis=-1) / 128
+    assert np.allclose(lhs, rhs, rtol=1e-13)
+
+
+# ------------------------------------------------------------------- 1-D op --
+
+def dirichlet(N, K):
+    """D(n) = (1/N) sum_{k<K} exp(2 pi i k n / N), closed form."""
+    n = np.arange(N)
+    out = np.empty(N, dtype=np.complex128)
+    out[0] = K / N
+    nz = n[1:]
+    out[1:] = (1 - np.exp(2j * np.pi * K * nz / N)) / (1 - np.exp(2j * np.pi * nz / N)) / N
+    return out
+
+
+@pytest.mark.parametrize("N,K", [(64, 16), (256, 64), (64, 64), (32, 8), (128, 1)])
+def test_impulse_closed_form(oracle_mod, N, K):
+    C_in, C_out, c0 = 3, 4, 1
+    x = np.zeros((2, C_in, N), dtype=np.complex64)
+    x[0, c0, 0] = 1.0
+    x[1, c0, 0] = 2.0 - 1.0j
+    W = crandn(C_in, C_out)
+    y, _ = oracle_mod.spectral_conv1d(x, W, K)
+    D = dirichlet(N, K)
+    for o in range(C_out):
+        assert np.allclose(y[0, o], W[c0, o].astype(np.complex128) * D, atol=1e-13)
+        assert np.allclose(y[1, o], (2.0 - 1.0j) * W[c0, o].astype(np.complex128) * D, atol=1e-13)
+
+
+@pytest.mark.parametrize("N,K", [(64, 16), (256, 64), (1024, 128)])
+def test_single_exponential_selects_low_bins_only(oracle_mod, N, K):
+    """x = exp(2 pi i k0 n/N): passes (times W) iff k0 < K; bins N-K..N-1 are NOT kept."""
+    C_in, C_out, c0 = 2, 3, 0
+    W = crandn(C_in, C_out)
+    n = np.arange(N)
+    for k0 in [0, 1, K - 1, K, K + 1, N // 2, N - K, N - 1]:
+        x = np.zeros((1, C_in, N), dtype=np.complex128)
+        x[0, c0] = np.exp(2j * np.pi * k0 * n / N)
+        x32 = x.astype(np.complex64)
+        y, _ = oracle_mod.spectral_conv1d(x32, W, K)
+        # the fp32-rounded exponential leaks ~1e-7 into other bins
+        if k0 < K:
+            want = W[c0].astype(np.complex128)[:, None] * x32[0, c0].astype(np.complex128)[None, :]
+            assert np.max(np.abs(y[0] - want)) < 5e-6
+        else:
+            assert np.max(np.abs(y[0])) < 5e-6
+
+
+@pytest.mark.parametrize("N", [16, 64, 256])
+def test_round_trip_identity(oracle_mod, N):
+    C = 5
+    x = crandn(3, C, N)
+    W = np.eye(C, dtype=np.complex64)
+    y, _ = oracle_mod.spectral_conv1d(x, W, N)
+    assert np.max(np.abs(y - x)) < 1e-13 * N
+
+
+def test_projection_is_idempotent_and_energy(oracle_mod):
+    N, K, C = 128, 32, 4
+    x = crandn(2, C, N)
+    W = np.eye(C, dtype=np.complex64)
+    y, _ = oracle_mod.spectral_conv1d(x, W, K)
+    y32 = y.astype(np.complex64)
+    y2, _ = oracle_mod.spectral_conv1d(y32, W, K)
+    assert np.max(np.abs(y2 - y32)) < 1e-6          # fp32 rounding of the re-fed input only
+    Xh = oracle_mod.forward_spectrum1d(x[0])
+    assert np.allclose(np.sum(np.abs(y[0]) ** 2, -1), np.sum(np.abs(Xh[:, :K]) ** 2, -1) / N, rtol=1e-12)
+
+
+def test_linearity_in_x_and_W(oracle_mod):
+    N, K, Ci, Co = 64, 16, 6, 5
+    # small integers are exact in fp32, so a*x1 + x2 is representable
+    x1 = (rng.integers(-8, 9, (2, Ci, N)) + 1j * rng.integers(-8, 9, (2, Ci, N))).astype(np.complex64)
+    x2 = (rng.integers(-8, 9, (2, Ci, N)) + 1j * rng.integers(-8, 9, (2, Ci, N))).astype(np.complex64)
+    W1 = (rng.integers(-4, 5, (Ci, Co)) + 1j * rng.integers(-4, 5, (Ci, Co))).astype(np.complex64)
+    W2 = (rng.integers(-4, 5, (Ci, Co)) + 1j * rng.integers(-4, 5, (Ci, Co))).astype(np.complex64)
+    f = lambda x, W: oracle_mod.spectral_conv1d(x, W, K)[0]
+    a = 3 - 2j
+    assert np.allclose(f((a * x1 + x2).astype(np.complex64), W1), a * f(x1, W1) + f(x2, W1), atol=1e-10)
+    assert np.allclose(f(x1, (a * W1 + W2).astype(np.complex64)), a * f(x1, W1) + f(x1, W2), atol=1e-10)
+
+
+def test_commutation_with_channel_mixing(oracle_mod):
+    """W is mode independent, so conv(x, W) = P(x . W) = (P x) . W with P = conv(., I)."""
+    N, K, Ci, Co = 128, 32, 7, 3
+    x = (rng.integers(-8, 9, (2, Ci, N)) + 1j * rng.integers(-8, 9, (2, Ci, N))).astype(np.complex64)
+    W = (rng.integers(-4, 5, (Ci, Co)) + 1j * rng.integers(-4, 5, (Ci, Co))).astype(np.complex64)
+    direct, _ = oracle_mod.spectral_conv1d(x, W, K)
+    mixed_first = np.einsum("bcn,co->bon", x, W).astype(np.complex64)      # exact in fp32 (small ints)
+    a, _ = oracle_mod.spectral_conv1d(mixed_first, np.eye(Co, dtype=np.complex64), K)
+    Px, _ = oracle_mod.spectral_conv1d(x, np.eye(Ci, dtype=np.complex64), K)
+    b = np.einsum("bcn,co->bon", Px, W.astype(np.complex128))
+    assert np.allclose(direct, a, atol=1e-10)
+    assert np.allclose(direct, b, atol=1e-10)
+
+
+def test_W_orientation_and_no_conjugate(oracle_mod):
+    """One-hot W[c0,o0] = i routes channel c0 to output o0, multiplied by +i (not -i), and only there."""
+    N, K, Ci, Co, c0, o0 = 32, 32, 3, 4, 2, 1
+    x = crandn(1, Ci, N)
+    W = np.zeros((Ci, Co), dtype=np.complex64)
+    W[c0, o0] = 1j
+    y, _ = oracle_mod.spectral_conv1d(x, W, K)
+    for o in range(Co):
+        want = 1j * x[0, c0].astype(np.complex128) if o == o0 else 0
+        assert np.max(np.abs(y[0, o] - want)) < 1e-12
+
+
+@pytest.mark.parametrize("cfg", inputs.CONFIGS[:2], ids=lambda c: c.name)
+def test_against_numpy_pipeline_on_benchmark_inputs(oracle_mod, cfg):
+    x, W = inputs.make_workload(cfg)
+    y, _ = oracle_mod.spectral_conv1d(x, W, cfg.K)
+    Xh = np.fft.fft(x.astype(np.complex128), axis=-1)[..., :cfg.K]
+    Yh = np.einsum("bck,co->bok", Xh, W.astype(np.complex128))
+    pad = np.zeros((cfg.B, cfg.C_out, cfg.N), dtype=np.complex128)
+    pad[..., :cfg.K] = Yh
+    ref = np.fft.ifft(pad, axis=-1)
+    assert np.max(np.abs(ref - y)) < 1e-12
+    # E|y|^2 = 4K/N for these distributions (loose statistical sanity)
+    assert abs(np.mean(np.abs(y) ** 2) / (4 * cfg.K / cfg.N) - 1) < 0.2
+
+
+# ------------------------------------------------------------------- 2-D op --
+
+def test_2d_matches_numpy_fft2(oracle_mod):
+    B, Ci, Co, N, K = 2, 3, 4, 64, 16
+    x = crandn(B, Ci, N, N)
+    W = crandn(Ci, Co)
+    y, _ = oracle_mod.spectral_conv2d(x, W, K)
+    Xh = np.fft.fft2(x.astype(np.complex128))[..., :K, :K]
+    Yh = np.einsum("bcxy,co->boxy", Xh, W.astype(np.complex128))
+    pad = np.zeros((B, Co, N, N), dtype=np.complex128)
+    pad[..., :K, :K] = Yh
+    ref = np.fft.ifft2(pad)
+    assert np.max(np.abs(ref - y)) < 1e-12
+
+
+def test_2d_single_exponential_corner_only(oracle_mod):
+    N, K = 32, 8
+    W = crandn(1, 1)
+    n1, n2 = np.meshgrid(np.arange(N), np.arange(N), indexing="ij")
+    for (k1, k2), keep in [((0, 0), True), ((K - 1, K - 1), True), ((3, 5), True), ((K, 0), False),
+                           ((0, K), False), ((N - 1, 0), False), ((0, N - 1), False), ((N - 1, N - 1), False)]:
+        x = np.exp(2j * np.pi * (k1 * n1 + k2 * n2) / N)[None, None].astype(np.complex64)
+        y, _ = oracle_mod.spectral_conv2d(x, W, K)
+        if keep:
+            assert np.max(np.abs(y[0, 0] - W[0, 0].astype(np.complex128) * x[0, 0])) < 5e-6
+        else:
+            assert np.max(np.abs(y)) < 5e-6
+
+
+def test_2d_round_trip_and_separability(oracle_mod):
+    N, C = 32, 3
+    x = crandn(2, C, N, N)
+    I = np.eye(C, dtype=np.complex64)
+    y, _ = oracle_mod.spectral_conv2d(x, I, N)
+    assert np.max(np.abs(y - x)) < 1e-12
+    # P_2d = P_axis1 o P_axis2: apply the 1-D operator along the last axis, then along the first
+    K = 8
+    y2, _ = oracle_mod.spectral_conv2d(x, I, K)
+    rows = x.transpose(0, 2, 1, 3).reshape(2 * N, C, N)                       # [(b,n1), c, n2]
+    p_last, _ = oracle_mod.spectral_conv1d(np.ascontiguousarray(rows), I, K)
+    p_last = p_last.reshape(2, N, C, N).transpose(0, 2, 1, 3)                 # [b, c, n1, n2]
+    F = np.fft.fft(p_last, axis=2)
+    F[:, :, K:, :] = 0
+    both = np.fft.ifft(F, axis=2)
+    assert np.max(np.abs(both - y2)) < 1e-6   # p_last is fed back in fp32
+
+
+def test_2d_transposed_image_gives_transposed_result(oracle_mod):
+    """Axis handling: swapping the two spatial axes of x swaps them in y."""
+    N, K = 32, 8
+    x = crandn(1, 2, N, N)
+    W = crandn(2, 2)
+    y, _ = oracle_mod.spectral_conv2d(x, W, K)
+    yt, _ = oracle_mod.spectral_conv2d(np.ascontiguousarray(x.transpose(0, 1, 3, 2)), W, K)
+    assert np.max(np.abs(yt.transpose(0, 1, 3, 2) - y)) < 1e-12
+
+
+# ------------------------------------------------------ facts the paper prints --
+
+def _needed_ops_radix2(N, kept):
+    """Number of butterfly outputs (one add or subtract each) that the first `kept` bins of an
+    N-point radix-2 decimation-in-time network depend on."""
+    stages = N.bit_length() - 1
+    need = set(range(kept))          # positions needed after the last stage
+    ops = 0
+    for s in range(stages, 0, -1):
+        span = 1 << s                # butterfly group size at this stage
+        half = span >> 1
+        ops += len(need)
+        prev = set()
+        for pos in need:
+            base, j = pos - pos % span, pos % span % half
+            prev.add(base + j)
+            prev.add(base + j + half)
+        need = prev
+    return ops
+
+
+def test_pruned_butterfly_counts_match_paper():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "pruning_op_counts.txt")) if l.strip() and l[0] != "#"]
+    assert rows
+    for N, kept, ops in rows:
+        assert _needed_ops_radix2(int(N), int(kept)) == int(ops)
+
+
+def test_truncated_write_fraction_matches_paper():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "truncation_traffic.txt")) if l.strip() and l[0] != "#"]
+    for N, K, frac in rows:
+        assert 1.0 - int(K) / int(N) == float(frac)
