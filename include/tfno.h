@@ -1,0 +1,118 @@
+/*
+ * tfno.h -- C ABI of the MI355X (gfx950) spectral-convolution library.
+ *
+ * The operator is the Fourier layer of a Fourier Neural Operator as TurboFNO
+ * (arxiv 2504.11681) defines it: forward FFT along the spatial axis or axes,
+ * truncation to the first K frequency bins of every transformed axis, a complex
+ * linear layer over the hidden (channel) dimension that uses ONE weight matrix
+ * for all retained modes, zero padding back to N bins, inverse FFT
+ * (Sec. 2.1 and Fig. 1 for the pipeline and the tensor shapes; Sec. 3.1 for the
+ * GEMM shape M = batch x modes, N = OutputDim, K = HiddenDim; Sec. 3.3 for
+ * which bins are kept and how padding mirrors truncation).
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers to contiguous row-major tensors of
+ *    interleaved complex64 (float re, float im; 8 bytes per element).
+ *      x : [B, C_in,  N]      (1-D)   or   [B, C_in,  N, N]   (2-D)   read only
+ *      W : [C_in, C_out]                                              read only
+ *      y : [B, C_out, N]      (1-D)   or   [B, C_out, N, N]   (2-D)   written
+ *  - Forward transform uses exp(-2 pi i k n / N) and is unscaled; the inverse
+ *    uses exp(+2 pi i k n / N) and is scaled by 1/N per transformed axis.  No
+ *    conjugation of W.  Retained bins are k = 0..K-1 on each transformed axis
+ *    (the low corner [0,K)x[0,K) in 2-D).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls are asynchronous: they enqueue kernels and return; they never
+ *    synchronise and never allocate device memory.
+ *  - Ownership: the caller owns every buffer (including the workspace) and must
+ *    keep it alive and unmodified until the stream has passed the call.
+ *  - y must not overlap x or W (checked on address ranges: TFNO_ERR_ALIAS).
+ *  - Argument errors are detected on the host before anything is launched, so a
+ *    failed call has no effect on y.  B == 0 is a valid empty call (TFNO_OK,
+ *    nothing launched, pointers may be NULL).
+ *  - N must be a power of two, 2 <= N <= 4096; 1 <= K <= N; C_in, C_out >= 1.
+ *  - Thread safety: entry points may be called concurrently from several host
+ *    threads; tfno_set_workspace must not race with calls that use the workspace.
+ */
+#ifndef TFNO_H
+#define TFNO_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TFNO_OK = 0,
+    TFNO_ERR_NULL = 1,        /* a required pointer is NULL                               */
+    TFNO_ERR_SHAPE = 2,       /* a size is out of range (non power-of-two N, K > N, ...)  */
+    TFNO_ERR_UNSUPPORTED = 3, /* valid shape, but this entry point has no kernel for it   */
+    TFNO_ERR_ALIAS = 4,       /* y overlaps x or W                                        */
+    TFNO_ERR_WORKSPACE = 5,   /* workspace missing or smaller than tfno_workspace_bytes() */
+    TFNO_ERR_HIP = 6          /* the HIP runtime reported a launch error                  */
+} tfno_status;
+
+/*
+ * Fused 1-D spectral convolution (the fully fused FFT-CGEMM-iFFT kernel, Sec. 4.3,
+ * with the built-in truncation, zero padding and butterfly pruning of Sec. 3.3):
+ *
+ *   y[b,o,:] = iFFT_N( pad_N( sum_c trunc_K( FFT_N(x[b,c,:]) ) * W[c,o] ) )
+ *
+ * One kernel launch; the spectra never leave the chip.  Needs no workspace.
+ * Supported by the fused kernel: N in {64,128,256,512,1024}, K a multiple of 16
+ * that divides N (K = N allowed).  Other valid shapes: TFNO_ERR_UNSUPPORTED
+ * (use the staged entry point).
+ */
+tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y,
+                                 int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
+ * Fused 2-D spectral convolution (Sec. 3.2/3.3, 2-D pipeline): a truncated
+ * forward FFT along the first spatial axis, the fused 1-D kernel along the last
+ * axis on the K retained rows, and a zero-padded inverse FFT along the first
+ * axis.  Three launches; the two [B, C, K, N] intermediates live in the workspace
+ * set with tfno_set_workspace (tfno_workspace_bytes(2, 0, ...) bytes).
+ * Shape support as for the 1-D fused entry point.
+ */
+tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y,
+                                 int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
+ * Unfused baseline with the structure the paper attributes to the PyTorch Fourier
+ * layer (Sec. 1, Sec. 2.1): full FFT, truncate copy, CGEMM, zero-pad copy, full
+ * inverse FFT, every intermediate in global memory (five launches in 1-D; the 2-D
+ * version transforms both axes with separate launches).  Same contract and same
+ * result as the fused entry points; accepts every valid shape.  Needs
+ * tfno_workspace_bytes(dims, 1, ...) bytes of workspace.
+ */
+tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y,
+                                        int B, int C_in, int C_out, int N, int K, void *stream);
+tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y,
+                                        int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
+ * Workspace (device memory for intermediates) that an entry point needs for a
+ * shape: dims = 1 or 2, staged = 0 (fused entry point) or 1 (staged twin).
+ * Returns 0 when none is needed or the arguments are invalid.
+ */
+size_t tfno_workspace_bytes(int dims, int staged, int B, int C_in, int C_out, int N, int K);
+
+/*
+ * Registers a caller-owned device buffer as the library's workspace for all
+ * later calls (the library never allocates).  dev_ptr = NULL with bytes = 0
+ * clears it.  The buffer must be 256-byte aligned.  Calls that share the
+ * workspace must be ordered on one stream (or otherwise serialised) by the caller.
+ */
+tfno_status tfno_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Static, NUL-terminated description of a status code. */
+const char *tfno_status_string(tfno_status s);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int tfno_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TFNO_H */

@@ -1,0 +1,129 @@
+"""ctypes binding of libtfno.so: argument marshalling only.
+
+Every step of the spectral convolution runs inside the HIP library; PyTorch is used for device
+allocation and streams.  The functions mirror the C ABI in ``include/tfno.h`` name for name.  There is
+no CPU fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtfno.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_ALIAS, ERR_WORKSPACE, ERR_HIP = range(7)
+
+EXPORTS = (
+    "tfno_spectral_conv1d",
+    "tfno_spectral_conv2d",
+    "tfno_spectral_conv1d_staged",
+    "tfno_spectral_conv2d_staged",
+    "tfno_workspace_bytes",
+    "tfno_set_workspace",
+    "tfno_status_string",
+    "tfno_version",
+)
+
+_lib = None
+_workspace = None     # the torch tensor currently registered as workspace (kept alive here)
+
+
+class TfnoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libtfno.so (built in-tree by ``python -m paper_2504_11681_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_11681_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        for name in EXPORTS[:4]:
+            fn = getattr(L, name)
+            fn.restype = ci
+            fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.tfno_workspace_bytes.restype = ctypes.c_size_t
+        L.tfno_workspace_bytes.argtypes = [ci] * 7
+        L.tfno_set_workspace.restype = ci
+        L.tfno_set_workspace.argtypes = [vp, ctypes.c_size_t]
+        L.tfno_status_string.restype = ctypes.c_char_p
+        L.tfno_status_string.argtypes = [ci]
+        L.tfno_version.restype = ci
+        L.tfno_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().tfno_status_string(status).decode()
+
+
+def version() -> int:
+    return lib().tfno_version()
+
+
+def workspace_bytes(dims: int, staged: bool, B: int, C_in: int, C_out: int, N: int, K: int) -> int:
+    return lib().tfno_workspace_bytes(dims, int(staged), B, C_in, C_out, N, K)
+
+
+def set_workspace(tensor) -> None:
+    """Registers a torch device tensor (any dtype) as the library workspace; None clears it."""
+    global _workspace
+    if tensor is None:
+        st = lib().tfno_set_workspace(None, 0)
+    else:
+        st = lib().tfno_set_workspace(tensor.data_ptr(), tensor.numel() * tensor.element_size())
+    if st != OK:
+        raise TfnoError(st, "tfno_set_workspace")
+    _workspace = tensor
+
+
+def ensure_workspace(nbytes: int, device) -> None:
+    """Makes sure a registered workspace of at least nbytes exists (allocates with torch if not)."""
+    import torch
+    if nbytes == 0:
+        return
+    if _workspace is None or _workspace.numel() * _workspace.element_size() < nbytes or _workspace.device != device:
+        set_workspace(torch.empty(nbytes, dtype=torch.uint8, device=device))
+
+
+def _call(name: str, dims: int, staged: bool, x, W, y, K: int, stream):
+    import torch
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if t.dtype != torch.complex64 or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous complex64 device tensor")
+    if x.dim() != 2 + dims or y.dim() != 2 + dims or W.dim() != 2:
+        raise ValueError("x, y must be [B, C, N] (1-D) or [B, C, N, N] (2-D); W must be [C_in, C_out]")
+    B, C_in, N = x.shape[0], x.shape[1], x.shape[2]
+    C_out = W.shape[1]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out) + tuple(x.shape[2:]) or any(s != N for s in x.shape[2:]):
+        raise ValueError("inconsistent tensor shapes")
+    ensure_workspace(workspace_bytes(dims, staged, B, C_in, C_out, N, K), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = getattr(lib(), name)(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, K, stream)
+    if st != OK:
+        raise TfnoError(st, name)
+    return y
+
+
+def spectral_conv1d(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv1d", 1, False, x, W, y, K, stream)
+
+
+def spectral_conv2d(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv2d", 2, False, x, W, y, K, stream)
+
+
+def spectral_conv1d_staged(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv1d_staged", 1, True, x, W, y, K, stream)
+
+
+def spectral_conv2d_staged(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv2d_staged", 2, True, x, W, y, K, stream)

@@ -1,0 +1,207 @@
+// C ABI of libtfno.so: argument checking, workspace registry, shape dispatch.  See include/tfno.h.
+#include "../../include/tfno.h"
+#include "common.h"
+#include "fused1d.h"
+#include "staged.h"
+
+#include <atomic>
+
+using namespace tfno;
+
+namespace {
+
+struct Workspace { void *ptr; size_t bytes; };
+std::atomic<void *> g_ws_ptr{nullptr};
+std::atomic<size_t> g_ws_bytes{0};
+
+bool is_pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
+
+bool overlaps(const void *a, size_t abytes, const void *b, size_t bbytes)
+{
+    uintptr_t a0 = (uintptr_t)a, a1 = a0 + abytes, b0 = (uintptr_t)b, b1 = b0 + bbytes;
+    return a0 < b1 && b0 < a1;
+}
+
+// Everything that can be decided on the host.  *empty is set for a valid call with nothing to do.
+tfno_status validate(int dims, const void *x, const void *W, const void *y, int B, int C_in, int C_out, int N, int K,
+                     bool *empty)
+{
+    *empty = false;
+    if (B < 0 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N) return TFNO_ERR_SHAPE;
+    if (B == 0) { *empty = true; return TFNO_OK; }
+    if (!x || !W || !y) return TFNO_ERR_NULL;
+    const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
+    // element counts must stay below 2^40 (byte offsets then fit comfortably in 64 bits) and the
+    // launch grids below 2^31 workgroups
+    const long double in_elems = (long double)B * C_in * pts, out_elems = (long double)B * C_out * pts;
+    if (in_elems >= 1099511627776.0L || out_elems >= 1099511627776.0L) return TFNO_ERR_SHAPE;
+    if ((long double)B * (C_in > C_out ? C_in : C_out) * (dims == 2 ? N : 1) >= 2147483647.0L) return TFNO_ERR_SHAPE;
+    const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
+    if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    return TFNO_OK;
+}
+
+size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int N, int K)
+{
+    return sizeof(c64) * (size_t)B * K * N * ((size_t)C_in + C_out);
+}
+
+tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W, size_t wb, const void *y, size_t yb,
+                            void **ws)
+{
+    void *p = g_ws_ptr.load();
+    size_t have = g_ws_bytes.load();
+    if (need == 0) { *ws = nullptr; return TFNO_OK; }
+    if (!p || have < need) return TFNO_ERR_WORKSPACE;
+    if (overlaps(p, need, x, xb) || overlaps(p, need, W, wb) || overlaps(p, need, y, yb)) return TFNO_ERR_ALIAS;
+    *ws = p;
+    return TFNO_OK;
+}
+
+tfno_status run(int dims, bool staged, const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                void *stream)
+{
+    bool empty;
+    tfno_status st = validate(dims, x, W, y, B, C_in, C_out, N, K, &empty);
+    if (st != TFNO_OK || empty) return st;
+    if (!staged && !fused1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+
+    const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
+    const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
+    void *ws = nullptr;
+    st = check_workspace(tfno_workspace_bytes(dims, staged ? 1 : 0, B, C_in, C_out, N, K), x, xb, W, wb, y, yb, &ws);
+    if (st != TFNO_OK) return st;
+
+    hipStream_t s = (hipStream_t)stream;
+    const c64 *xc = (const c64 *)x, *Wc = (const c64 *)W;
+    c64 *yc = (c64 *)y;
+    hipError_t e;
+
+    if (staged) {
+        e = staged_conv(dims, xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
+    } else if (dims == 1) {
+        Fused1dArgs a{};
+        a.x = xc; a.W = Wc; a.y = yc; a.C_in = C_in; a.C_out = C_out;
+        a.inner_count = 1;
+        a.x_outer_stride = (long long)C_in * N;  a.x_inner_stride = 0; a.x_chan_stride = N;
+        a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
+        a.scale = 1.0f / (float)N;
+        e = fused1d_launch(N, K, a, B, s);
+    } else {
+        // 2-D pipeline (Sec. 3.2 / 3.3): truncated forward transform along the first axis, fused
+        // kernel along the last axis on the K retained rows, zero-padded inverse along the first axis.
+        c64 *T1 = (c64 *)ws;                                   // [B, C_in,  K, N]
+        c64 *T2 = T1 + (size_t)B * C_in * K * N;               // [B, C_out, K, N]
+        const long long NN = (long long)N * N, KN = (long long)K * N;
+        e = launch_axis_fft(-1, xc, T1, N, (long long)B * C_in * N, N, NN, KN, N, N, K, 1.f, s);
+        if (e == hipSuccess) {
+            Fused1dArgs a{};
+            a.x = T1; a.W = Wc; a.y = T2; a.C_in = C_in; a.C_out = C_out;
+            a.inner_count = K;
+            a.x_outer_stride = (long long)C_in * KN;  a.x_inner_stride = N; a.x_chan_stride = KN;
+            a.y_outer_stride = (long long)C_out * KN; a.y_inner_stride = N; a.y_chan_stride = KN;
+            a.scale = 1.0f / ((float)N * (float)N);
+            e = fused1d_launch(N, K, a, (long long)B * K, s);
+        }
+        if (e == hipSuccess)
+            e = launch_axis_fft(+1, T2, yc, N, (long long)B * C_out * N, N, KN, NN, N, K, N, 1.f, s);
+    }
+    return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
+}
+
+}  // namespace
+
+namespace tfno {
+
+bool fused1d_supported(int N, int K)
+{
+    if (!is_pow2(K)) return false;
+    switch (N) {
+    case 64: return K >= 8 && K <= 64;
+    case 128: return K >= 16 && K <= 128;
+    case 256: return K >= 16 && K <= 256;
+    case 512: return K >= 32 && K <= 256;
+    case 1024: return K >= 32 && K <= 256;
+    default: return false;
+    }
+}
+
+hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    if (!fused1d_supported(N, K)) return hipErrorInvalidValue;
+    switch (N) {
+    case 64: return fused1d_launch_n64(K, a, rows, s);
+    case 128: return fused1d_launch_n128(K, a, rows, s);
+    case 256: return fused1d_launch_n256(K, a, rows, s);
+    case 512: return fused1d_launch_n512(K, a, rows, s);
+    case 1024: return fused1d_launch_n1024(K, a, rows, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tfno
+
+extern "C" {
+
+tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                 void *stream)
+{
+    return run(1, false, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                 void *stream)
+{
+    return run(2, false, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                        int K, void *stream)
+{
+    return run(1, true, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                        int K, void *stream)
+{
+    return run(2, true, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+size_t tfno_workspace_bytes(int dims, int staged, int B, int C_in, int C_out, int N, int K)
+{
+    if ((dims != 1 && dims != 2) || B < 1 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N)
+        return 0;
+    if (staged) return staged_workspace_bytes(dims, B, C_in, C_out, N, K);
+    return dims == 2 ? fused2d_workspace_bytes(B, C_in, C_out, N, K) : 0;
+}
+
+tfno_status tfno_set_workspace(void *dev_ptr, size_t bytes)
+{
+    if (!dev_ptr && bytes != 0) return TFNO_ERR_NULL;
+    if (dev_ptr && bytes == 0) return TFNO_ERR_SHAPE;
+    if (((uintptr_t)dev_ptr & 255u) != 0) return TFNO_ERR_SHAPE;
+    g_ws_bytes.store(0);
+    g_ws_ptr.store(dev_ptr);
+    g_ws_bytes.store(bytes);
+    return TFNO_OK;
+}
+
+const char *tfno_status_string(tfno_status s)
+{
+    switch (s) {
+    case TFNO_OK: return "ok";
+    case TFNO_ERR_NULL: return "a required pointer is NULL";
+    case TFNO_ERR_SHAPE: return "a size argument is out of range";
+    case TFNO_ERR_UNSUPPORTED: return "no fused kernel for this shape (use the staged entry point)";
+    case TFNO_ERR_ALIAS: return "y or the workspace overlaps another buffer";
+    case TFNO_ERR_WORKSPACE: return "workspace missing or too small (see tfno_workspace_bytes)";
+    case TFNO_ERR_HIP: return "the HIP runtime reported an error at launch";
+    default: return "unknown status";
+    }
+}
+
+int tfno_version(void) { return 100; }
+
+}  // extern "C"

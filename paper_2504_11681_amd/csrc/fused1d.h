@@ -1,0 +1,34 @@
+// Host-visible interface of the fused last-axis kernel family.
+#pragma once
+#include "common.h"
+
+namespace tfno {
+
+// One "batch row" bb of the launch is the pair (bb / inner_count, bb % inner_count); its input pencils
+// start at x + outer*x_outer_stride + inner*x_inner_stride + c*x_chan_stride (complex elements) and are
+// contiguous along the transformed axis.  Plain 1-D: inner_count = 1.  Middle stage of the 2-D pipeline:
+// outer = batch element, inner = retained row of the first axis.
+struct Fused1dArgs {
+    const c64 *x;
+    const c64 *W;
+    c64 *y;
+    int C_in, C_out;
+    long long inner_count;
+    long long x_outer_stride, x_inner_stride, x_chan_stride;
+    long long y_outer_stride, y_inner_stride, y_chan_stride;
+    float scale;    // folded into W (1/N for 1-D; the 2-D pipeline passes its full 1/N^2 here)
+};
+
+// Returns true when a fused kernel exists for (N, K).
+bool fused1d_supported(int N, int K);
+// Enqueues the fused kernel; hipErrorInvalidValue when (N, K) is unsupported.
+hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long batch_rows, hipStream_t s);
+
+// Per-N dispatchers, one translation unit each.
+hipError_t fused1d_launch_n64(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_launch_n256(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_launch_n512(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_launch_n1024(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+
+}  // namespace tfno

@@ -1,0 +1,29 @@
+// Fused-kernel instantiations for N = 128 (one translation unit per N so they build in parallel).
+#include "fused1d_kernel.h"
+
+namespace tfno {
+
+hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    switch (K) {
+    case 16:
+        if (a.C_out > 64) return launch_fused1d<128, 16, 4>(a, rows, s);
+        if (a.C_out > 32) return launch_fused1d<128, 16, 2>(a, rows, s);
+        return launch_fused1d<128, 16, 1>(a, rows, s);
+    case 32:
+        if (a.C_out > 64) return launch_fused1d<128, 32, 4>(a, rows, s);
+        if (a.C_out > 32) return launch_fused1d<128, 32, 2>(a, rows, s);
+        return launch_fused1d<128, 32, 1>(a, rows, s);
+    case 64:
+        if (a.C_out > 64) return launch_fused1d<128, 64, 4>(a, rows, s);
+        if (a.C_out > 32) return launch_fused1d<128, 64, 2>(a, rows, s);
+        return launch_fused1d<128, 64, 1>(a, rows, s);
+    case 128:
+        if (a.C_out > 64) return launch_fused1d<128, 128, 4>(a, rows, s);
+        if (a.C_out > 32) return launch_fused1d<128, 128, 2>(a, rows, s);
+        return launch_fused1d<128, 128, 1>(a, rows, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tfno

@@ -1,0 +1,94 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments on the host before any launch (no compute call needs a GPU here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2504_11681_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2504_11681_amd import build
+        build.build(verbose=False)
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tfno.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tfno_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings(L):
+    assert binding.version() >= 100
+    seen = {binding.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and all(seen)
+
+
+FAKE = 0x10000000  # never dereferenced: all of these calls fail validation before any launch
+
+
+def call(L, name, x, W, y, B, Ci, Co, N, K):
+    return getattr(L, name)(x, W, y, B, Ci, Co, N, K, None)
+
+
+@pytest.mark.parametrize("name", binding.EXPORTS[:4])
+def test_argument_errors_are_caught_on_the_host(L, name):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    assert call(L, name, None, W, y, 2, 4, 4, 64, 16) == binding.ERR_NULL
+    assert call(L, name, x, None, y, 2, 4, 4, 64, 16) == binding.ERR_NULL
+    assert call(L, name, x, W, None, 2, 4, 4, 64, 16) == binding.ERR_NULL
+    for bad in [(-1, 4, 4, 64, 16), (2, 0, 4, 64, 16), (2, 4, 0, 64, 16), (2, 4, 4, 48, 16), (2, 4, 4, 64, 0),
+                (2, 4, 4, 64, 65), (2, 4, 4, 1, 1), (2, 4, 4, 8192, 16), (2, 4, 4, -64, 16)]:
+        assert call(L, name, x, W, y, *bad) == binding.ERR_SHAPE, bad
+    # y overlapping x or W
+    assert call(L, name, x, W, x, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
+    assert call(L, name, x, W, x + 8, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
+    assert call(L, name, x, W, W, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
+    # empty batch: valid, nothing to do, pointers may be NULL
+    assert call(L, name, None, None, None, 0, 4, 4, 64, 16) == binding.OK
+
+
+def test_fused_entry_points_report_unsupported_shapes(L):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 2048, 128) == binding.ERR_UNSUPPORTED
+    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 48) == binding.ERR_UNSUPPORTED
+    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 8) == binding.ERR_UNSUPPORTED
+    assert call(L, "tfno_spectral_conv2d", x, W, y, 2, 4, 4, 32, 8) == binding.ERR_UNSUPPORTED
+
+
+def test_workspace_contract(L):
+    assert binding.workspace_bytes(1, False, 4, 16, 16, 64, 16) == 0
+    assert binding.workspace_bytes(1, True, 4, 16, 16, 64, 16) == 8 * 4 * (16 * 64 + 16 * 16 + 16 * 16 + 16 * 64)
+    assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 16) == 8 * 2 * 16 * 64 * (3 + 5)
+    assert binding.workspace_bytes(2, True, 2, 3, 5, 64, 16) == 8 * 2 * (3 * 4096 + 3 * 256 + 5 * 256 + 5 * 4096)
+    assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
+    assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    assert L.tfno_set_workspace(None, 0) == binding.OK
+    # staged needs a workspace: none registered -> error, still no launch
+    assert call(L, "tfno_spectral_conv1d_staged", x, W, y, 2, 4, 4, 64, 16) == binding.ERR_WORKSPACE
+    assert call(L, "tfno_spectral_conv2d", x, W, y, 2, 4, 4, 64, 16) == binding.ERR_WORKSPACE
+    need = binding.workspace_bytes(1, True, 2, 4, 4, 64, 16)
+    ws = FAKE + (3 << 26)
+    assert L.tfno_set_workspace(ws, need - 1) == binding.OK
+    assert call(L, "tfno_spectral_conv1d_staged", x, W, y, 2, 4, 4, 64, 16) == binding.ERR_WORKSPACE
+    assert L.tfno_set_workspace(ws + 4, need) == binding.ERR_SHAPE       # misaligned
+    assert L.tfno_set_workspace(None, 16) == binding.ERR_NULL
+    # workspace overlapping a tensor
+    assert L.tfno_set_workspace(x, need) == binding.OK
+    assert call(L, "tfno_spectral_conv1d_staged", x, W, y, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
+    assert L.tfno_set_workspace(None, 0) == binding.OK

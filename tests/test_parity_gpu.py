@@ -1,0 +1,195 @@
+"""Parity of the HIP path (through the C ABI) against the float64 oracle on the same seeded inputs.
+
+Tolerance (fp32 path vs fp64 oracle): relative L2 error <= 1e-5 and max abs error <= 1e-4 * max|y|.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2504_11681_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+REL_L2, MAX_ABS = 1e-5, 1e-4
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2504_11681_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()   # fails loudly when the HIP library is missing
+    return torch, binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def check(got: np.ndarray, want: np.ndarray, what=""):
+    got = got.astype(np.complex128)
+    err = got - want
+    rel = np.linalg.norm(err.ravel()) / np.linalg.norm(want.ravel())
+    mx = np.max(np.abs(err)) / np.max(np.abs(want))
+    say(f"   {what}: rel_l2={rel:.3e} max_abs/max|y|={mx:.3e}")
+    assert rel <= REL_L2, f"{what}: relative L2 {rel:.3e}"
+    assert mx <= MAX_ABS, f"{what}: max abs {mx:.3e}"
+
+
+def run_gpu(gpu, fn_name, x, W, K):
+    torch, binding = gpu
+    xd = torch.from_numpy(x).cuda()
+    Wd = torch.from_numpy(W).cuda()
+    yd = torch.full((x.shape[0], W.shape[1]) + x.shape[2:], float("nan"), dtype=torch.complex64, device="cuda")
+    getattr(binding, fn_name)(xd, Wd, yd, K)
+    torch.cuda.synchronize()
+    return yd.cpu().numpy()
+
+
+def oracle_fn(oracle_mod, dims):
+    return oracle_mod.spectral_conv1d if dims == 1 else oracle_mod.spectral_conv2d
+
+
+# (B, C_in, C_out, N, K): several tiles, ragged channel counts, every supported N of the fused kernel
+SMALL_1D = [
+    (4, 16, 16, 64, 16),        # benchmark configuration 1
+    (3, 5, 7, 64, 8),
+    (2, 33, 40, 64, 64),        # K = N: no truncation
+    (3, 9, 70, 128, 32),
+    (2, 37, 17, 128, 128),
+    (64, 64, 64, 256, 64),      # benchmark configuration 2
+    (5, 19, 130, 256, 32),
+    (2, 40, 33, 256, 16),
+    (3, 24, 96, 256, 128),
+    (2, 20, 40, 256, 256),
+    (3, 21, 66, 512, 64),
+    (2, 35, 10, 512, 256),
+    (2, 16, 100, 512, 32),
+    (3, 13, 129, 1024, 128),
+    (2, 20, 30, 1024, 32),
+    (2, 9, 64, 1024, 256),
+    (1, 1, 1, 1024, 64),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+@pytest.mark.parametrize("fn", ["spectral_conv1d", "spectral_conv1d_staged"])
+def test_1d_small(gpu, oracle_mod, fn, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] {fn} {shape}")
+    x = inputs.make_x(100 + N + K, B, Ci, (N,))
+    W = inputs.make_W(100 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    got = run_gpu(gpu, fn, x, W, K)
+    check(got, want, fn)
+
+
+STAGED_ONLY_1D = [(2, 3, 4, 2, 1), (2, 3, 4, 4, 3), (3, 6, 5, 32, 5), (2, 4, 4, 2048, 100), (1, 2, 3, 4096, 4096),
+                  (2, 5, 3, 256, 48)]
+
+
+@pytest.mark.parametrize("shape", STAGED_ONLY_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_staged_general_shapes(gpu, oracle_mod, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] staged {shape}")
+    x = inputs.make_x(7, B, Ci, (N,))
+    W = inputs.make_W(7, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    check(run_gpu(gpu, "spectral_conv1d_staged", x, W, K), want, "staged")
+
+
+SMALL_2D = [(2, 3, 5, 64, 16), (1, 8, 8, 64, 8), (2, 5, 33, 128, 32), (1, 4, 3, 256, 64), (1, 2, 2, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", SMALL_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+@pytest.mark.parametrize("fn", ["spectral_conv2d", "spectral_conv2d_staged"])
+def test_2d_small(gpu, oracle_mod, fn, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] {fn} {shape}")
+    x = inputs.make_x(200 + N + K, B, Ci, (N, N))
+    W = inputs.make_W(200 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d(x, W, K)
+    check(run_gpu(gpu, fn, x, W, K), want, fn)
+
+
+def test_2d_staged_general_shape(gpu, oracle_mod):
+    B, Ci, Co, N, K = 2, 3, 2, 32, 5
+    x = inputs.make_x(9, B, Ci, (N, N))
+    W = inputs.make_W(9, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d(x, W, K)
+    check(run_gpu(gpu, "spectral_conv2d_staged", x, W, K), want, "staged2d")
+
+
+def test_round_trip_identity_and_determinism(gpu):
+    """K = N, W = I gives y = x; two runs give bitwise equal output."""
+    torch, binding = gpu
+    N, C = 256, 48
+    x = inputs.make_x(3, 4, C, (N,))
+    W = np.eye(C, dtype=np.complex64)
+    a = run_gpu(gpu, "spectral_conv1d", x, W, N)
+    b = run_gpu(gpu, "spectral_conv1d", x, W, N)
+    assert np.array_equal(a.view(np.float32), b.view(np.float32))
+    check(a, x.astype(np.complex128), "round trip")
+
+
+def test_empty_batch_and_error_paths(gpu):
+    torch, binding = gpu
+    x = torch.zeros((0, 4, 64), dtype=torch.complex64, device="cuda")
+    W = torch.zeros((4, 4), dtype=torch.complex64, device="cuda")
+    y = torch.zeros((0, 4, 64), dtype=torch.complex64, device="cuda")
+    binding.spectral_conv1d(x, W, y, 16)
+    binding.spectral_conv1d_staged(x, W, y, 16)
+    x = torch.zeros((1, 4, 64), dtype=torch.complex64, device="cuda")
+    with pytest.raises(binding.TfnoError) as e:
+        binding.spectral_conv1d(x, W, x, 16)           # y aliases x
+    assert e.value.status == binding.ERR_ALIAS
+    y = torch.zeros((1, 4, 64), dtype=torch.complex64, device="cuda")
+    with pytest.raises(binding.TfnoError) as e:
+        binding.spectral_conv1d(x, W, y, 65)
+    assert e.value.status == binding.ERR_SHAPE
+    torch.cuda.synchronize()
+
+
+# ----------------------------------------------------- full benchmark sizes, sampled batch elements
+
+def full_size_case(gpu, oracle_mod, w, fn_name, sample_b):
+    """Runs the whole workload on the GPU in the launch configuration the benchmark times, and
+    compares complete batch elements `sample_b` with the oracle (which regenerates only those)."""
+    torch, binding = gpu
+    say(f"[case] {fn_name} {w.name} sampled b={sample_b}")
+    Wn = inputs.make_W(w.seed, w.C_in, w.C_out)
+    xd = torch.empty((w.B, w.C_in) + w.spatial, dtype=torch.complex64, device="cuda")
+    for b in range(w.B):
+        xd[b] = torch.from_numpy(inputs.make_x_element(w.seed, b, w.C_in, w.spatial)).cuda()
+    Wd = torch.from_numpy(Wn).cuda()
+    yd = torch.full((w.B, w.C_out) + w.spatial, float("nan"), dtype=torch.complex64, device="cuda")
+    getattr(binding, fn_name)(xd, Wd, yd, w.K)
+    torch.cuda.synchronize()
+    assert not torch.isnan(torch.view_as_real(yd)).any().item(), "some outputs were never written"
+    for b in sample_b:
+        xb = inputs.make_x_element(w.seed, b, w.C_in, w.spatial)[None]
+        want, _ = oracle_fn(oracle_mod, w.dims)(xb, Wn, w.K)
+        check(yd[b].cpu().numpy()[None], want, f"{w.name} b={b}")
+    # E|y|^2 = 4 (K/N)^dims for these input distributions: a property that holds at any size
+    e2 = torch.mean(torch.abs(yd.view(-1)[: 1 << 24]) ** 2).item()
+    assert abs(e2 / (4 * (w.K / w.N) ** w.dims) - 1) < 0.05
+    del xd, yd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("fn", ["spectral_conv1d", "spectral_conv1d_staged"])
+def test_config3_full_size(gpu, oracle_mod, fn):
+    full_size_case(gpu, oracle_mod, inputs.CONFIGS[2], fn, [0, 101, 255])
+
+
+@pytest.mark.parametrize("fn", ["spectral_conv2d", "spectral_conv2d_staged"])
+def test_config4_full_size(gpu, oracle_mod, fn):
+    full_size_case(gpu, oracle_mod, inputs.CONFIGS[3], fn, [0, 31])
+
+
+@pytest.mark.parametrize("w", inputs.sweep_configs(), ids=lambda w: w.name)
+def test_config5_sweep_full_size(gpu, oracle_mod, w):
+    full_size_case(gpu, oracle_mod, w, "spectral_conv1d", [0, 511])
+    full_size_case(gpu, oracle_mod, w, "spectral_conv1d_staged", [257])
