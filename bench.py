@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused spectral convolution on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--no-extras]
+
+A step is one pass of the whole hot path (load, pruned forward FFT, truncation, CGEMM over the hidden
+dimension, zero padding, pruned inverse FFT, store) over one batch of synthetic input that is already
+resident in HBM.  The default workload is the 1-D production shape (B=256, C=128, N=1024, K=128).
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X published dense FP32 matrix rate
+
+
+def pick_config(name: str):
+    from paper_2504_11681_amd import inputs
+    table = {"cfg1": inputs.CONFIGS[0], "cfg2": inputs.CONFIGS[1], "cfg3": inputs.CONFIGS[2], "cfg4": inputs.CONFIGS[3]}
+    for w in inputs.sweep_configs():
+        table[w.name] = w
+    if name not in table:
+        raise SystemExit(f"unknown config {name!r}; choose from {sorted(table)}")
+    return table[name]
+
+
+def device_inputs(w, torch):
+    """Seeded inputs of the workload, generated on the host and moved to HBM before timing starts."""
+    from paper_2504_11681_amd import inputs
+    xd = torch.empty((w.B, w.C_in) + w.spatial, dtype=torch.complex64, device="cuda")
+    for b in range(w.B):
+        xd[b] = torch.from_numpy(inputs.make_x_element(w.seed, b, w.C_in, w.spatial)).cuda()
+    Wd = torch.from_numpy(inputs.make_W(w.seed, w.C_in, w.C_out)).cuda()
+    yd = torch.zeros((w.B, w.C_out) + w.spatial, dtype=torch.complex64, device="cuda")
+    return xd, Wd, yd
+
+
+def time_calls(torch, fn, steps: int, warmup: int):
+    """Returns (wall seconds for `steps` calls, mean per-call device time in seconds from HIP events
+    recorded on the stream the kernels are launched on)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev = sum(a.elapsed_time(b) for a, b in ev) / steps * 1e-3
+    return wall, dev
+
+
+def flops_of(w):
+    """Contraction flops on the retained modes (8 real flops per complex MAC)."""
+    return 8.0 * w.B * (w.K ** w.dims) * w.C_in * w.C_out
+
+
+def measure(w, torch, binding, steps, warmup, staged=False):
+    xd, Wd, yd = device_inputs(w, torch)
+    name = ("spectral_conv%dd" % w.dims) + ("_staged" if staged else "")
+    fn = getattr(binding, name)
+    binding.ensure_workspace(binding.workspace_bytes(w.dims, staged, w.B, w.C_in, w.C_out, w.N, w.K), xd.device)
+    stream = torch.cuda.current_stream().cuda_stream
+    call = lambda: fn(xd, Wd, yd, w.K, stream)
+    wall, dev = time_calls(torch, call, steps, warmup)
+    del xd, Wd, yd
+    torch.cuda.empty_cache()
+    return wall, dev
+
+
+def cpu_baseline(w):
+    """The float64 oracle, as it stands, timed on the host cores over the whole workload (1-D) or
+    over a bounded sample of batch elements (2-D)."""
+    import numpy as np
+    import oracle
+    from paper_2504_11681_amd import inputs
+    oracle.build()
+    nb = w.B if w.dims == 1 else min(w.B, 4)
+    x = np.stack([inputs.make_x_element(w.seed, b, w.C_in, w.spatial) for b in range(nb)])
+    W = inputs.make_W(w.seed, w.C_in, w.C_out)
+    fn = oracle.spectral_conv1d if w.dims == 1 else oracle.spectral_conv2d
+    t0 = time.perf_counter()
+    _, used = fn(x, W, w.K)
+    dt = time.perf_counter() - t0
+    return {"value": (nb / w.B) / dt, "unit": "layers/s", "cores": int(used), "kind": "oracle",
+            "sample": f"{nb} of {w.B} batch elements of {w.name}, float64, {dt:.2f} s wall; "
+                      f"layers/s scaled by {nb}/{w.B}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU (the path shards over the batch axis with no "
+                         "exchange; no multi-GPU code exists). Run with --gpus 1.")
+
+    import torch
+    from paper_2504_11681_amd import binding
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs the MI355X (no CPU fallback exists)")
+    binding.lib()
+
+    w = pick_config(args.config)
+    wall, dev = measure(w, torch, binding, args.steps, args.warmup)
+    ms_per_step = wall / args.steps * 1e3
+    layers_per_s = args.steps / wall
+    alg_bytes = w.compulsory_bytes
+    achieved = alg_bytes / dev / 1e9
+
+    out = {
+        "metric": "fused_spectral_conv_layers_per_s",
+        "value": layers_per_s,
+        "unit": "layers/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "dims": w.dims, "B": w.B, "C_in": w.C_in, "C_out": w.C_out,
+                   "N": w.N, "K": w.K, "seed": w.seed, "entry_point": "tfno_spectral_conv%dd" % w.dims},
+        "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
+        "effective_hbm_frac_of_peak": alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "contraction_TFLOPs": flops_of(w) / dev / 1e12,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "k_fused1d" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
+                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": dev * 1e3},
+    }
+
+    if not args.no_extras:
+        s_steps = max(5, args.steps // 5)
+        swall, sdev = measure(w, torch, binding, s_steps, 2, staged=True)
+        out["staged"] = {"ms_per_step": swall / s_steps * 1e3, "layers_per_s": s_steps / swall,
+                         "variant": "five kernels: full FFT, truncate copy, CGEMM, pad copy, full iFFT",
+                         "fused_speedup": (swall / s_steps) / (wall / args.steps)}
+        if w.name.startswith("cfg3"):
+            w4 = pick_config("cfg4")
+            steps4 = max(5, args.steps // 5)
+            wall4, dev4 = measure(w4, torch, binding, steps4, 2)
+            out["cfg4_2d"] = {"workload": w4.name, "ms_per_step": wall4 / steps4 * 1e3,
+                              "layers_per_s": steps4 / wall4,
+                              "effective_hbm_GBps": w4.compulsory_bytes / (wall4 / steps4) / 1e9,
+                              "effective_hbm_frac_of_peak": w4.compulsory_bytes / (wall4 / steps4) / 1e9 / HBM_PEAK_GBPS}
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    main()
