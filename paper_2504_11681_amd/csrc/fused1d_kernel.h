@@ -57,7 +57,8 @@ struct FusedCfg {
     static constexpr size_t LDS_Z = sizeof(c64) * PPI * ZS;
     static constexpr size_t LDS_XH = sizeof(float) * PPI * 2 * KPAD;
     static constexpr size_t LDS_YH = sizeof(c64) * 32 * YROW;
-    static constexpr size_t LDS_BYTES = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH);
+    static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [p][t]
+    static constexpr size_t LDS_BYTES = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH) + LDS_TW;
     static_assert(K % P == 0 && Q >= 1 && Q <= T && T % Q == 0, "K must be a multiple of P that divides N");
     static_assert(PPI <= 32 && 32 % PPI == 0, "epilogue slabs are 32 outputs");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
@@ -76,6 +77,7 @@ k_fused1d(Fused1dArgs a)
     c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                       // [PPI][ZS]
     float *XH = reinterpret_cast<float *>(lds_raw + C::LDS_Z);        // [PPI][2][KPAD]
     c64 *YH = reinterpret_cast<c64 *>(lds_raw + C::LDS_Z);            // [32][YROW]   (aliases XH)
+    const c64 *TW = reinterpret_cast<const c64 *>(lds_raw + C::LDS_BYTES - C::LDS_TW);   // [P][T]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -86,11 +88,14 @@ k_fused1d(Fused1dArgs a)
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
 
-    // stage-A identity of this thread and its twiddles w_N^(t p) = exp(-2 pi i t p / N)
+    // stage-A identity of this thread; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [p][t]
+    // (consecutive t: conflict-free reads), computed once per workgroup with accurate sincospi
     const int ja = tid / T, t = tid % T;
-    c64 tw[P];
-#pragma unroll
-    for (int p = 0; p < P; ++p) tw[p] = cis2pi(-(float)(t * p), (float)N);
+    {
+        c64 *twr = reinterpret_cast<c64 *>(lds_raw + C::LDS_BYTES - C::LDS_TW);
+        for (int i = tid; i < N; i += NT) twr[i] = cis2pi(-(float)((i / T) * (i % T)), (float)N);
+    }
+    __syncthreads();
 
     // MFMA tile identity of this wave: tiles tile0 .. tile0+TPW-1, all in output slab `ot_w`
     const int tile0 = wave * TPW;
@@ -119,18 +124,29 @@ k_fused1d(Fused1dArgs a)
         }
     };
 
+    load_pencil(0);
     for (int c0 = 0; c0 < a.C_in; c0 += PPI) {
-        load_pencil(c0);
+        // W rows of this iteration's channels: issued first so that their latency hides behind the
+        // transforms.  Lanes 0-31 and 32-63 read the same 32 outputs (the two k-slots of the MFMA).
+        c64 wv[PPI];
+#pragma unroll
+        for (int jc = 0; jc < PPI; ++jc) {
+            wv[jc] = make_float2(0.f, 0.f);
+            if (has_tiles && c0 + jc < a.C_in && o_lane < a.C_out)
+                wv[jc] = a.W[(long long)(c0 + jc) * a.C_out + o_lane];
+        }
         // stage A
         {
             c64 z[P];
             RegFFT<P, -1, 1>::run(v, z);
 #pragma unroll
             for (int p = 0; p < P; ++p) {
-                c64 zz = p == 0 ? z[0] : cmul(z[p], tw[p]);
+                c64 zz = p == 0 ? z[0] : cmul(z[p], TW[p * T + t]);
                 Zl[ja * ZS + p * ZROW + t] = zz;
             }
         }
+        // v is consumed: fetch the next iteration's pencils now, in flight during stage B and the MFMAs
+        if (c0 + PPI < a.C_in) load_pencil(c0 + PPI);
         __syncthreads();
         // stage B
 #pragma unroll
@@ -148,14 +164,12 @@ k_fused1d(Fused1dArgs a)
             }
         }
         __syncthreads();
-        // complex MAC on the matrix cores
+        // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)
         if (has_tiles) {
-            const int nch = min(PPI, a.C_in - c0);
-            for (int jc = 0; jc < nch; ++jc) {
-                c64 w = make_float2(0.f, 0.f);
-                if (o_lane < a.C_out) w = a.W[(long long)(c0 + jc) * a.C_out + o_lane];
-                const float a_re = (hi ? -w.y : w.x) * a.scale;
-                const float a_im = (hi ? w.x : w.y) * a.scale;
+#pragma unroll
+            for (int jc = 0; jc < PPI; ++jc) {
+                const float a_re = (hi ? -wv[jc].y : wv[jc].x) * a.scale;
+                const float a_im = (hi ? wv[jc].x : wv[jc].y) * a.scale;
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
                     const float bx = XH[(jc * 2 + (hi ? 1 : 0)) * KPAD + 32 * (kt0 + i) + (lane & 31)];
@@ -207,7 +221,8 @@ k_fused1d(Fused1dArgs a)
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
                     c64 zz = Zl[ja * ZS + p * ZROW + t];
-                    z[p] = p == 0 ? zz : cmul(zz, make_float2(tw[p].x, -tw[p].y));
+                    c64 w = TW[p * T + t];
+                    z[p] = p == 0 ? zz : cmul(zz, make_float2(w.x, -w.y));
                 }
                 RegFFT<P, +1, 1>::run(z, r);
                 const int o = o_base + 32 * ot + it * PPI + ja;
