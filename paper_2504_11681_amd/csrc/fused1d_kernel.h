@@ -4,26 +4,31 @@
 // workgroup walks the hidden dimension in step with the GEMM k-loop, Sec. 2.3 / 4.1):
 //
 //   workgroup  = one batch row `bb` x one slab of 32*OT output channels, 256 threads (4 waves)
-//   k-loop     : PPI = 256/T input channels per iteration.  N = P * T.
-//     stage A  : thread (pencil j, t) loads x[c0+j][t + T*jj], jj < P (coalesced), P-point DFT in registers,
-//                twiddle by w_N^(t p), writes column-major into LDS            Z[j][p][t]
-//     stage B  : thread (pencil j, column p) reads Z[j][p][0..T), T-point DFT pruned to the Q = K/P outputs
-//                that are retained modes k = p + P q < K (built-in truncation + output pruning, Sec. 3.3),
-//                writes the planar A-operand tile                               XH[j][re|im][k]
+//   k-loop     : PPI = 256/T input channels per iteration, 64/T of them per wave.  N = P * T.
+//     stage A  : thread (pencil slot jw, t) loads x[c][t + T*jj], jj < P (coalesced), P-point DFT in
+//                registers, twiddle by w_N^(t p), writes column-major into the wave's PRIVATE LDS tile
+//                Z[jw][p][t]  -- both transform stages of a pencil run in one wave, so the transpose needs
+//                no workgroup barrier
+//     stage B  : lane (pencil slot j, column p) reads Z[j][p][0..T), T-point DFT pruned to the Q = K/P
+//                outputs that are retained modes k = p + P q < K (built-in truncation + output pruning,
+//                Sec. 3.3), writes the planar operand tile XH[buf][c][re|im][k] (double buffered)
 //     MFMA     : Yh[o][k] += W[c][o] * Xh[c][k] with v_mfma_f32_32x32x2_f32: the two k-slots of one
 //                instruction carry (re, im) of ONE channel, so a complex MAC over 32 outputs x 32 modes is
 //                two MFMAs (real part with A = (W.re, -W.im), imaginary part with A = (W.im, W.re)).
-//                Accumulators stay in registers for the whole k-loop.
-//   epilogue   : per 32-output slab, accumulators -> LDS YH[o][k]; stage B' expands the K retained modes of
-//                column p to T points (built-in zero padding + input pruning, Sec. 3.3), LDS Z, stage A'
-//                applies conj twiddles, P-point inverse DFT, coalesced store of y.  The 1/N scale is folded
-//                into W when it is loaded.
+//                Accumulators stay in registers for the whole k-loop.  The MFMAs of iteration i sit in the
+//                same basic block as the transforms of iteration i+1 so that the matrix cores run under the
+//                VALU work; one workgroup barrier per iteration publishes the next XH buffer.
+//   epilogue   : (a) when a wave owns a whole 32-output slab and P = 32, the accumulator layout already is
+//                the stage-B' input layout (lane = column p, tile = q), so the spectrum goes from registers
+//                straight into the zero-padded, input-pruned inverse transform (Sec. 3.3) with no LDS
+//                handoff and no barrier; (b) otherwise accumulators -> LDS YH[o][k] per slab, then the same
+//                two inverse stages.  Stage A' applies conj twiddles, P-point inverse DFT, coalesced store.
+//                The 1/N scale is folded into W when it is loaded.
 //
 // LDS handoffs (the counterpart of the two swizzles of Sec. 4.1 / 4.2, re-derived for 4-byte banks and
 // 8-byte accesses): Z rows are padded to T+1 complex so that both the write (consecutive t) and the
 // transposed read (consecutive p, stride T+1) touch distinct banks; XH is planar so that an MFMA operand
-// read is 32 consecutive floats per half-wave; YH rows are written 32 consecutive complex at a time straight
-// from the MFMA accumulator layout.
+// read is 32 consecutive floats per half-wave.
 #pragma once
 #include "common.h"
 #include "fft_regs.h"
@@ -45,37 +50,53 @@ struct FusedCfg {
     static constexpr int P = Decomp<N>::P, T = Decomp<N>::T;
     static constexpr int Q = K / P;                 // retained outputs per column of stage B
     static constexpr int NT = 256, NW = 4;
-    static constexpr int PPI = NT / T;              // pencils (channels) per k-loop iteration
-    static constexpr int CPT = P / T;               // stage-B columns per thread
+    static constexpr int PPW = 64 / T;              // pencils per wave per round
+    static constexpr int PPI = NW * PPW;            // pencils (channels) per k-loop iteration
+    static constexpr int CPL = P / T;               // stage-B columns per lane
     static constexpr int KT = (K + 31) / 32;        // 32-mode MFMA tiles
     static constexpr int KPAD = KT * 32;
     static constexpr int TILES = OT * KT;
     static constexpr int TPW = (TILES + NW - 1) / NW;   // 32x32 complex tiles per wave
+    static constexpr bool ALLT = TILES % NW == 0;       // every wave owns exactly TPW tiles
+    static constexpr bool DIRECT = P == 32 && OT == NW && TPW == KT;   // wave w owns output slab w entirely
+    static constexpr int RPA = 32 / T;              // direct epilogue: stage-B' rounds per stage-A' round
     static constexpr int ZROW = T + 1;
     static constexpr int ZS = P * ZROW + (T == 8 ? 8 - (P * ZROW) % 16 + ((P * ZROW) % 16 > 8 ? 16 : 0) : 0);
     static constexpr int YROW = K + 1;
-    static constexpr size_t LDS_Z = sizeof(c64) * PPI * ZS;
-    static constexpr size_t LDS_XH = sizeof(float) * PPI * 2 * KPAD;
-    static constexpr size_t LDS_YH = sizeof(c64) * 32 * YROW;
+    static constexpr int XH_BUF = PPI * 2 * KPAD;   // floats per XH buffer
+    static constexpr size_t LDS_Z = sizeof(c64) * NW * PPW * ZS;
+    static constexpr size_t LDS_XH = sizeof(float) * 2 * XH_BUF;
+    static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * 32 * YROW;
     static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [p][t]
     static constexpr size_t LDS_BYTES = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH) + LDS_TW;
     static_assert(K % P == 0 && Q >= 1 && Q <= T && T % Q == 0, "K must be a multiple of P that divides N");
-    static_assert(PPI <= 32 && 32 % PPI == 0, "epilogue slabs are 32 outputs");
+    static_assert(8 % PPW == 0, "a wave inverts 8 rows of a 32-output slab");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
     static_assert(TPW * 32 <= 128, "accumulators must fit the register file");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one gfx950 CU");
 };
 
-template <int N, int K, int OT>
+// Orders this wave's LDS traffic (all lanes) without a workgroup barrier.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// EVEN: C_in is a multiple of PPI and C_out a multiple of 32, so no load or store needs a mask.
+template <int N, int K, int OT, bool EVEN>
 __global__ void __launch_bounds__(256)
 k_fused1d(Fused1dArgs a)
 {
     using C = FusedCfg<N, K, OT>;
-    constexpr int P = C::P, T = C::T, Q = C::Q, PPI = C::PPI, CPT = C::CPT, KT = C::KT, KPAD = C::KPAD;
-    constexpr int TPW = C::TPW, ZROW = C::ZROW, ZS = C::ZS, YROW = C::YROW, NT = C::NT;
+    constexpr int P = C::P, T = C::T, Q = C::Q, PPW = C::PPW, PPI = C::PPI, CPL = C::CPL, KT = C::KT;
+    constexpr int KPAD = C::KPAD, TPW = C::TPW, ZROW = C::ZROW, ZS = C::ZS, YROW = C::YROW, NT = C::NT;
+    constexpr bool ALLT = C::ALLT;
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                       // [PPI][ZS]
-    float *XH = reinterpret_cast<float *>(lds_raw + C::LDS_Z);        // [PPI][2][KPAD]
+    c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                       // [NW][PPW][ZS]
+    float *XH = reinterpret_cast<float *>(lds_raw + C::LDS_Z);        // [2][PPI][2][KPAD]
     c64 *YH = reinterpret_cast<c64 *>(lds_raw + C::LDS_Z);            // [32][YROW]   (aliases XH)
     const c64 *TW = reinterpret_cast<const c64 *>(lds_raw + C::LDS_BYTES - C::LDS_TW);   // [P][T]
 
@@ -88,9 +109,11 @@ k_fused1d(Fused1dArgs a)
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
 
-    // stage-A identity of this thread; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [p][t]
+    // stage-A identity of this lane; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [p][t]
     // (consecutive t: conflict-free reads), computed once per workgroup with accurate sincospi
-    const int ja = tid / T, t = tid % T;
+    const int jw = lane / T, t = lane % T;
+    const int ja = wave * PPW + jw;
+    c64 *Zw = Zl + wave * (PPW * ZS);
     {
         c64 *twr = reinterpret_cast<c64 *>(lds_raw + C::LDS_BYTES - C::LDS_TW);
         for (int i = tid; i < N; i += NT) twr[i] = cis2pi(-(float)((i / T) * (i % T)), (float)N);
@@ -99,7 +122,7 @@ k_fused1d(Fused1dArgs a)
 
     // MFMA tile identity of this wave: tiles tile0 .. tile0+TPW-1, all in output slab `ot_w`
     const int tile0 = wave * TPW;
-    const bool has_tiles = tile0 < C::TILES;
+    const bool has_tiles = ALLT || tile0 < C::TILES;
     const int ot_w = tile0 / KT, kt0 = tile0 % KT;
     floatx16 acc_re[TPW], acc_im[TPW];
 #pragma unroll
@@ -109,128 +132,194 @@ k_fused1d(Fused1dArgs a)
 
     const int o_lane = o_base + 32 * ot_w + (lane & 31);   // the output channel whose W this lane feeds
     const bool hi = lane >= 32;
+    const int n_it = (a.C_in + PPI - 1) / PPI;
 
-    // ------------------------------------------------------------------ k-loop over input channels
-    c64 v[P];
-    auto load_pencil = [&](int c0) {
+    c64 v[P];       // the pencil slice this lane transforms next
+    c64 wv[PPI];    // W[c][o_lane] for the channels of the iteration whose MFMAs run next
+
+    auto load_pencil = [&](int c0) __attribute__((always_inline)) {
         const int c = c0 + ja;
-        if (c < a.C_in) {
+        if constexpr (EVEN) {
             const c64 *src = xb + (long long)c * a.x_chan_stride + t;
 #pragma unroll
             for (int jj = 0; jj < P; ++jj) v[jj] = src[T * jj];
         } else {
+            const bool ok = c < a.C_in;
+            const c64 *src = xb + (long long)(ok ? c : 0) * a.x_chan_stride + t;
 #pragma unroll
-            for (int jj = 0; jj < P; ++jj) v[jj] = make_float2(0.f, 0.f);
+            for (int jj = 0; jj < P; ++jj) {
+                c64 val = src[T * jj];
+                v[jj] = ok ? val : make_float2(0.f, 0.f);
+            }
         }
     };
-
-    load_pencil(0);
-    for (int c0 = 0; c0 < a.C_in; c0 += PPI) {
-        // W rows of this iteration's channels: issued first so that their latency hides behind the
-        // transforms.  Lanes 0-31 and 32-63 read the same 32 outputs (the two k-slots of the MFMA).
-        c64 wv[PPI];
+    auto load_w = [&](c64 *dst, int c0) __attribute__((always_inline)) {
 #pragma unroll
         for (int jc = 0; jc < PPI; ++jc) {
-            wv[jc] = make_float2(0.f, 0.f);
-            if (has_tiles && c0 + jc < a.C_in && o_lane < a.C_out)
-                wv[jc] = a.W[(long long)(c0 + jc) * a.C_out + o_lane];
+            const int c = c0 + jc;
+            if constexpr (EVEN && ALLT) {
+                dst[jc] = a.W[(long long)c * a.C_out + o_lane];
+            } else {
+                const bool ok = has_tiles && c < a.C_in && o_lane < a.C_out;
+                c64 val = a.W[ok ? (long long)c * a.C_out + o_lane : 0];
+                dst[jc] = ok ? val : make_float2(0.f, 0.f);
+            }
         }
-        // stage A
+    };
+    // forward transform of the pencils in v, truncated to K modes, into XH buffer `buf`
+    auto fft_fwd = [&](int buf) __attribute__((always_inline)) {
         {
             c64 z[P];
             RegFFT<P, -1, 1>::run(v, z);
 #pragma unroll
-            for (int p = 0; p < P; ++p) {
-                c64 zz = p == 0 ? z[0] : cmul(z[p], TW[p * T + t]);
-                Zl[ja * ZS + p * ZROW + t] = zz;
-            }
+            for (int p = 0; p < P; ++p) Zw[jw * ZS + p * ZROW + t] = p == 0 ? z[0] : cmul(z[p], TW[p * T + t]);
         }
-        // v is consumed: fetch the next iteration's pencils now, in flight during stage B and the MFMAs
-        if (c0 + PPI < a.C_in) load_pencil(c0 + PPI);
-        __syncthreads();
-        // stage B
+        wave_sync();
+        float *XHb = XH + buf * C::XH_BUF;
 #pragma unroll
-        for (int cc = 0; cc < CPT; ++cc) {
-            const int item = tid + NT * cc;
+        for (int cc = 0; cc < CPL; ++cc) {
+            const int item = lane + 64 * cc;
             const int j = item / P, p = item % P;
             c64 zt[T], xo[Q];
 #pragma unroll
-            for (int tt = 0; tt < T; ++tt) zt[tt] = Zl[j * ZS + p * ZROW + tt];
+            for (int tt = 0; tt < T; ++tt) zt[tt] = Zw[j * ZS + p * ZROW + tt];
             dft_prune_out<T, Q, -1>(zt, xo);
+            const int jg = wave * PPW + j;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                XH[(j * 2 + 0) * KPAD + p + P * q] = xo[q].x;
-                XH[(j * 2 + 1) * KPAD + p + P * q] = xo[q].y;
+                XHb[(jg * 2 + 0) * KPAD + p + P * q] = xo[q].x;
+                XHb[(jg * 2 + 1) * KPAD + p + P * q] = xo[q].y;
             }
         }
-        __syncthreads();
-        // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)
-        if (has_tiles) {
+        wave_sync();
+    };
+    // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)
+    auto mfma_block = [&](int buf) __attribute__((always_inline)) {
+        const float *XHb = XH + buf * C::XH_BUF;
 #pragma unroll
-            for (int jc = 0; jc < PPI; ++jc) {
-                const float a_re = (hi ? -wv[jc].y : wv[jc].x) * a.scale;
-                const float a_im = (hi ? wv[jc].x : wv[jc].y) * a.scale;
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    const float bx = XH[(jc * 2 + (hi ? 1 : 0)) * KPAD + 32 * (kt0 + i) + (lane & 31)];
-                    acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re, bx, acc_re[i], 0, 0, 0);
-                    acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im, bx, acc_im[i], 0, 0, 0);
-                }
-            }
-        }
-        // the next iteration's barriers order these XH reads before XH is rewritten
-    }
-    __syncthreads();
-
-    // ------------------------------------------------------------------ epilogue: per 32-output slab
-    for (int ot = 0; ot < OT; ++ot) {
-        if (has_tiles && ot == ot_w) {
-            // accumulator layout of the 32x32 MFMA: register r of lane l holds
-            //   row (output)  8*(r/4) + 4*(l/32) + r%4,   column (mode) l%32
+        for (int jc = 0; jc < PPI; ++jc) {
+            const float a_re = (hi ? -wv[jc].y : wv[jc].x) * a.scale;
+            const float a_im = (hi ? wv[jc].x : wv[jc].y) * a.scale;
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const int k = 32 * (kt0 + i) + (lane & 31);
-                if (k < K) {
+                const float bx = XHb[(jc * 2 + (hi ? 1 : 0)) * KPAD + 32 * (kt0 + i) + (lane & 31)];
+                acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re, bx, acc_re[i], 0, 0, 0);
+                acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im, bx, acc_im[i], 0, 0, 0);
+            }
+        }
+    };
+    // one k-loop iteration: MFMAs of block `it` next to the transforms of block it+1
+    auto step = [&](auto do_fft, auto do_load, int it) __attribute__((always_inline)) {
+        constexpr bool DO_FFT = decltype(do_fft)::value, DO_LOAD = decltype(do_load)::value;
+        const int cur = it & 1;
+        c64 wn[PPI];
+        if constexpr (DO_FFT) load_w(wn, (it + 1) * PPI);
+        if constexpr (ALLT) mfma_block(cur);
+        else if (has_tiles) mfma_block(cur);
+        if constexpr (DO_FFT) fft_fwd(cur ^ 1);
+        if constexpr (DO_LOAD) load_pencil((it + 2) * PPI);
+        if constexpr (DO_FFT) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int ol = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                        YH[ol * YROW + k] = make_float2(acc_re[i][r], acc_im[i][r]);
+            for (int jc = 0; jc < PPI; ++jc) wv[jc] = wn[jc];
+            __syncthreads();
+        }
+    };
+
+    // ------------------------------------------------------------------ k-loop over input channels
+    load_pencil(0);
+    load_w(wv, 0);
+    fft_fwd(0);
+    if (n_it > 1) load_pencil(PPI);
+    __syncthreads();
+    {
+        int it = 0;
+        for (; it + 2 < n_it; ++it) step(std::true_type{}, std::true_type{}, it);
+        if (it + 1 < n_it) { step(std::true_type{}, std::false_type{}, it); ++it; }
+        step(std::false_type{}, std::false_type{}, it);
+    }
+
+    // ------------------------------------------------------------------ epilogue
+    // stage A' for the pencil in Z slot jw of this wave: conj twiddle, P-point inverse transform, store
+    auto ifft_store = [&](int o) __attribute__((always_inline)) {
+        c64 z[P], r[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            c64 zz = Zw[jw * ZS + p * ZROW + t];
+            c64 w = TW[p * T + t];
+            z[p] = p == 0 ? zz : cmul(zz, make_float2(w.x, -w.y));
+        }
+        RegFFT<P, +1, 1>::run(z, r);
+        if (EVEN || o < a.C_out) {
+            c64 *dst = yb + (long long)o * a.y_chan_stride + t;
+#pragma unroll
+            for (int jj = 0; jj < P; ++jj) dst[T * jj] = r[jj];
+        }
+    };
+
+    if constexpr (C::DIRECT) {
+        // Wave w owns outputs o_base + 32 w .. +31 for every mode tile.  Register r of lane l of tile q holds
+        // Yh[o][p + 32 q] with p = l%32 and o = 8(r/4) + 4(l/32) + r%4: exactly the Q inputs that lane
+        // (half-wave h = l/32, column p) needs for stage B' of that pencil.
+        constexpr int RPA = C::RPA;
+        const int p = lane & 31, h = lane >> 5;
+        for (int rr = 0; rr < 16; rr += RPA) {
+#pragma unroll
+            for (int sub = 0; sub < RPA; ++sub) {
+                const int r = rr + sub;
+                c64 yin[Q], u[T];
+                static_for<0, 16>([&](auto rc) {
+                    constexpr int R = decltype(rc)::value;
+                    if (r == R) {
+#pragma unroll
+                        for (int q = 0; q < Q; ++q) yin[q] = make_float2(acc_re[q][R], acc_im[q][R]);
+                    }
+                });
+                dft_prune_in<T, Q, +1>(yin, u);
+                const int slot = 2 * sub + h;
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt) Zw[slot * ZS + p * ZROW + tt] = u[tt];
+            }
+            wave_sync();
+            const int r2 = rr + jw / 2;
+            ifft_store(o_base + 32 * wave + 8 * (r2 / 4) + 4 * (jw % 2) + (r2 % 4));
+            wave_sync();
+        }
+    } else {
+        __syncthreads();   // every wave is done reading XH, which YH aliases
+        for (int ot = 0; ot < OT; ++ot) {
+            if (has_tiles && ot == ot_w) {
+                // accumulator layout of the 32x32 MFMA: register r of lane l holds
+                //   row (output)  8*(r/4) + 4*(l/32) + r%4,   column (mode) l%32
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const int k = 32 * (kt0 + i) + (lane & 31);
+                    if (k < K) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int ol = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                            YH[ol * YROW + k] = make_float2(acc_re[i][r], acc_im[i][r]);
+                        }
                     }
                 }
             }
-        }
-        __syncthreads();
-        for (int it = 0; it < 32 / PPI; ++it) {
-            // stage B': zero-padded, input-pruned T-point inverse transform of column p
-#pragma unroll
-            for (int cc = 0; cc < CPT; ++cc) {
-                const int item = tid + NT * cc;
-                const int j = item / P, p = item % P;
-                const int ol = it * PPI + j;
-                c64 yin[Q], u[T];
-#pragma unroll
-                for (int q = 0; q < Q; ++q) yin[q] = YH[ol * YROW + p + P * q];
-                dft_prune_in<T, Q, +1>(yin, u);
-#pragma unroll
-                for (int tt = 0; tt < T; ++tt) Zl[j * ZS + p * ZROW + tt] = u[tt];
-            }
             __syncthreads();
-            // stage A': conj twiddle, P-point inverse transform, store
-            {
-                c64 z[P], r[P];
+            // wave w inverts rows 8w .. 8w+7 of the slab, PPW pencils per round, in its private Z tile
+            for (int rd = 0; rd < 8 / PPW; ++rd) {
 #pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    c64 zz = Zl[ja * ZS + p * ZROW + t];
-                    c64 w = TW[p * T + t];
-                    z[p] = p == 0 ? zz : cmul(zz, make_float2(w.x, -w.y));
-                }
-                RegFFT<P, +1, 1>::run(z, r);
-                const int o = o_base + 32 * ot + it * PPI + ja;
-                if (o < a.C_out) {
-                    c64 *dst = yb + (long long)o * a.y_chan_stride + t;
+                for (int cc = 0; cc < CPL; ++cc) {
+                    const int item = lane + 64 * cc;
+                    const int j = item / P, p = item % P;
+                    const int ol = 8 * wave + rd * PPW + j;
+                    c64 yin[Q], u[T];
 #pragma unroll
-                    for (int jj = 0; jj < P; ++jj) dst[T * jj] = r[jj];
+                    for (int q = 0; q < Q; ++q) yin[q] = YH[ol * YROW + p + P * q];
+                    dft_prune_in<T, Q, +1>(yin, u);
+#pragma unroll
+                    for (int tt = 0; tt < T; ++tt) Zw[j * ZS + p * ZROW + tt] = u[tt];
                 }
+                wave_sync();
+                ifft_store(o_base + 32 * ot + 8 * wave + rd * PPW + jw);
+                wave_sync();
             }
             __syncthreads();
         }
@@ -243,13 +332,19 @@ hipError_t launch_fused1d(const Fused1dArgs &a, long long batch_rows, hipStream_
     using C = FusedCfg<N, K, OT>;
     static bool attr_done = false;   // benign race: every thread sets the same value
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
-    hipLaunchKernelGGL((k_fused1d<N, K, OT>), grid, dim3(256), C::LDS_BYTES, s, a);
+    if (a.C_in % C::PPI == 0 && a.C_out % 32 == 0)
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true>), grid, dim3(256), C::LDS_BYTES, s, a);
+    else
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false>), grid, dim3(256), C::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
