@@ -84,16 +84,21 @@ struct RegFFT<1, DIR, STRIDE> {
     TFNO_HD static void run(const c64 *in, c64 *out) { out[0] = in[0]; }
 };
 
-// out[q] = sum_{t<T} z[t] exp(DIR 2 pi i t q / T),  q < Q,  Q | T.
+// out[q] = sum_{t<T} in(t) exp(DIR 2 pi i t q / T),  q < Q,  Q | T.     in: callable int -> c64
 // t = t1 + S t2 (S = T/Q):  S full Q-point transforms of the decimated input, then a twiddled S-term sum.
-template <int T, int Q, int DIR>
-TFNO_HD void dft_prune_out(const c64 *z, c64 *out)
+// The input is consumed Q values at a time, so a caller that reads it from LDS keeps only one group live.
+template <int T, int Q, int DIR, class In>
+TFNO_HD void dft_prune_out(In &&in, c64 *out)
 {
     constexpr int S = T / Q;
     static_for<0, S>([&](auto t1c) {
         constexpr int t1 = decltype(t1c)::value;
-        c64 F[Q];
-        RegFFT<Q, DIR, S>::run(z + t1, F);
+        c64 g[Q], F[Q];
+        static_for<0, Q>([&](auto t2c) {
+            constexpr int t2 = decltype(t2c)::value;
+            g[t2] = in(std::integral_constant<int, t1 + S * t2>{});
+        });
+        RegFFT<Q, DIR, 1>::run(g, F);
         static_for<0, Q>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
             if constexpr (t1 == 0) out[q] = F[q];
@@ -102,9 +107,10 @@ TFNO_HD void dft_prune_out(const c64 *z, c64 *out)
     });
 }
 
-// out[t] = sum_{q<Q} in[q] exp(DIR 2 pi i t q / T),  t < T.   (the transpose of the network above)
-template <int T, int Q, int DIR>
-TFNO_HD void dft_prune_in(const c64 *in, c64 *out)
+// emit(t, sum_{q<Q} in[q] exp(DIR 2 pi i t q / T)),  t < T.   (the transpose of the network above)
+// emit: callable (integral_constant t, c64); outputs are produced Q at a time.
+template <int T, int Q, int DIR, class Emit>
+TFNO_HD void dft_prune_in(const c64 *in, Emit &&emit)
 {
     constexpr int S = T / Q;
     static_for<0, S>([&](auto t1c) {
@@ -117,7 +123,7 @@ TFNO_HD void dft_prune_in(const c64 *in, c64 *out)
         RegFFT<Q, DIR, 1>::run(g, G);
         static_for<0, Q>([&](auto t2c) {
             constexpr int t2 = decltype(t2c)::value;
-            out[t1 + S * t2] = G[t2];
+            emit(std::integral_constant<int, t1 + S * t2>{}, G[t2]);
         });
     });
 }

@@ -34,6 +34,13 @@
 #include "fft_regs.h"
 #include "fused1d.h"
 
+#ifndef TFNO_STAMP
+#define TFNO_STAMP(i)   // phase-timestamp hooks of the development harness; empty in the library
+#endif
+#ifndef TFNO_STEP_STAMP
+#define TFNO_STEP_STAMP(it, i)
+#endif
+
 namespace tfno {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -67,8 +74,9 @@ struct FusedCfg {
     static constexpr size_t LDS_Z = sizeof(c64) * NW * PPW * ZS;
     static constexpr size_t LDS_XH = sizeof(float) * 2 * XH_BUF;
     static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * 32 * YROW;
-    static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [p][t]
-    static constexpr size_t LDS_BYTES = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH) + LDS_TW;
+    static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [t][p] (static)
+    static constexpr size_t LDS_DYN = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH);   // dynamic part
+    static constexpr size_t LDS_BYTES = LDS_DYN + LDS_TW;
     static_assert(K % P == 0 && Q >= 1 && Q <= T && T % Q == 0, "K must be a multiple of P that divides N");
     static_assert(8 % PPW == 0, "a wave inverts 8 rows of a 32-output slab");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
@@ -98,7 +106,8 @@ k_fused1d(Fused1dArgs a)
     c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                       // [NW][PPW][ZS]
     float *XH = reinterpret_cast<float *>(lds_raw + C::LDS_Z);        // [2][PPI][2][KPAD]
     c64 *YH = reinterpret_cast<c64 *>(lds_raw + C::LDS_Z);            // [32][YROW]   (aliases XH)
-    const c64 *TW = reinterpret_cast<const c64 *>(lds_raw + C::LDS_BYTES - C::LDS_TW);   // [P][T]
+    // the twiddle table is a separate LDS object so that its reads are known not to alias the Z/XH writes
+    __shared__ c64 TW[N];                                             // [T][P]: w_N^(t p)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -109,15 +118,13 @@ k_fused1d(Fused1dArgs a)
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
 
-    // stage-A identity of this lane; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [p][t]
-    // (consecutive t: conflict-free reads), computed once per workgroup with accurate sincospi
+    TFNO_STAMP(0);
+    // stage-A identity of this lane; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [t][p]
+    // (stage-B lanes read consecutive p: conflict-free), computed once per workgroup with accurate sincospi
     const int jw = lane / T, t = lane % T;
     const int ja = wave * PPW + jw;
     c64 *Zw = Zl + wave * (PPW * ZS);
-    {
-        c64 *twr = reinterpret_cast<c64 *>(lds_raw + C::LDS_BYTES - C::LDS_TW);
-        for (int i = tid; i < N; i += NT) twr[i] = cis2pi(-(float)((i / T) * (i % T)), (float)N);
-    }
+    for (int i = tid; i < N; i += NT) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
     __syncthreads();
 
     // MFMA tile identity of this wave: tiles tile0 .. tile0+TPW-1, all in output slab `ot_w`
@@ -166,24 +173,27 @@ k_fused1d(Fused1dArgs a)
             }
         }
     };
-    // forward transform of the pencils in v, truncated to K modes, into XH buffer `buf`
-    auto fft_fwd = [&](int buf) __attribute__((always_inline)) {
-        {
-            c64 z[P];
-            RegFFT<P, -1, 1>::run(v, z);
+    // stage A: P-point transform of the slice in v, written transposed into the wave's Z tile
+    auto stage_a = [&]() __attribute__((always_inline)) {
+        c64 z[P];
+        RegFFT<P, -1, 1>::run(v, z);
 #pragma unroll
-            for (int p = 0; p < P; ++p) Zw[jw * ZS + p * ZROW + t] = p == 0 ? z[0] : cmul(z[p], TW[p * T + t]);
-        }
-        wave_sync();
+        for (int p = 0; p < P; ++p) Zw[jw * ZS + p * ZROW + t] = z[p];
+    };
+    // stage B: twiddle, T-point transform pruned to the Q retained outputs of each column, into XH[buf]
+    auto stage_b = [&](int buf) __attribute__((always_inline)) {
         float *XHb = XH + buf * C::XH_BUF;
 #pragma unroll
         for (int cc = 0; cc < CPL; ++cc) {
             const int item = lane + 64 * cc;
             const int j = item / P, p = item % P;
-            c64 zt[T], xo[Q];
-#pragma unroll
-            for (int tt = 0; tt < T; ++tt) zt[tt] = Zw[j * ZS + p * ZROW + tt];
-            dft_prune_out<T, Q, -1>(zt, xo);
+            const c64 *zcol = Zw + j * ZS + p * ZROW;
+            c64 xo[Q];
+            dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
+                constexpr int tt = decltype(ttc)::value;
+                if constexpr (tt == 0) return zcol[0];
+                else return cmul(zcol[tt], TW[tt * P + p]);
+            }, xo);
             const int jg = wave * PPW + j;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
@@ -191,7 +201,6 @@ k_fused1d(Fused1dArgs a)
                 XHb[(jg * 2 + 1) * KPAD + p + P * q] = xo[q].y;
             }
         }
-        wave_sync();
     };
     // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)
     auto mfma_block = [&](int buf) __attribute__((always_inline)) {
@@ -208,46 +217,85 @@ k_fused1d(Fused1dArgs a)
             }
         }
     };
-    // one k-loop iteration: MFMAs of block `it` next to the transforms of block it+1
-    auto step = [&](auto do_fft, auto do_load, int it) __attribute__((always_inline)) {
-        constexpr bool DO_FFT = decltype(do_fft)::value, DO_LOAD = decltype(do_load)::value;
+    // One k-loop iteration, software pipelined three deep: the MFMAs of block `it` run next to stage B of
+    // block it+1 (from the Z tile written one iteration earlier) and stage A of block it+2, and the loads of
+    // block it+3 are issued as soon as v is free, so they are in flight for a whole iteration.
+    auto step = [&](auto do_b, auto do_a, auto do_load, int it) __attribute__((always_inline)) {
+        constexpr bool DO_B = decltype(do_b)::value, DO_A = decltype(do_a)::value, DO_LOAD = decltype(do_load)::value;
         const int cur = it & 1;
         c64 wn[PPI];
-        if constexpr (DO_FFT) load_w(wn, (it + 1) * PPI);
+        TFNO_STEP_STAMP(it, 0);
+        if constexpr (DO_B) load_w(wn, (it + 1) * PPI);
         if constexpr (ALLT) mfma_block(cur);
         else if (has_tiles) mfma_block(cur);
-        if constexpr (DO_FFT) fft_fwd(cur ^ 1);
-        if constexpr (DO_LOAD) load_pencil((it + 2) * PPI);
-        if constexpr (DO_FFT) {
+        TFNO_STEP_STAMP(it, 1);
+        if constexpr (DO_B) { stage_b(cur ^ 1); wave_sync(); }
+        TFNO_STEP_STAMP(it, 2);
+        if constexpr (DO_A) { stage_a(); wave_sync(); }
+        TFNO_STEP_STAMP(it, 3);
+        if constexpr (DO_LOAD) load_pencil((it + 3) * PPI);
+        TFNO_STEP_STAMP(it, 4);
+        if constexpr (DO_B) {
 #pragma unroll
             for (int jc = 0; jc < PPI; ++jc) wv[jc] = wn[jc];
             __syncthreads();
         }
+        TFNO_STEP_STAMP(it, 5);
     };
+    const std::true_type yes{};
+    const std::false_type no{};
 
     // ------------------------------------------------------------------ k-loop over input channels
     load_pencil(0);
     load_w(wv, 0);
-    fft_fwd(0);
+    stage_a();
+    wave_sync();
     if (n_it > 1) load_pencil(PPI);
+    stage_b(0);
+    wave_sync();
+    if (n_it > 1) {
+        stage_a();
+        wave_sync();
+        if (n_it > 2) load_pencil(2 * PPI);
+    }
     __syncthreads();
+    TFNO_STAMP(1);
     {
         int it = 0;
-        for (; it + 2 < n_it; ++it) step(std::true_type{}, std::true_type{}, it);
-        if (it + 1 < n_it) { step(std::true_type{}, std::false_type{}, it); ++it; }
-        step(std::false_type{}, std::false_type{}, it);
+        for (; it + 3 < n_it; ++it) step(yes, yes, yes, it);
+        const int left = n_it - it;   // 1, 2 or 3
+        if (left == 3) {
+            step(yes, yes, no, it);
+            step(yes, no, no, it + 1);
+            step(no, no, no, it + 2);
+        } else if (left == 2) {
+            step(yes, no, no, it);
+            step(no, no, no, it + 1);
+        } else {
+            step(no, no, no, it);
+        }
     }
 
+    TFNO_STAMP(2);
     // ------------------------------------------------------------------ epilogue
-    // stage A' for the pencil in Z slot jw of this wave: conj twiddle, P-point inverse transform, store
+    // stage B' for Z slot `slot`, column p: zero-padded, input-pruned T-point inverse transform of the Q
+    // retained modes in yin, conj twiddle, written transposed into the wave's Z tile
+    auto stage_b_inv = [&](const c64 *yin, int slot, int p) __attribute__((always_inline)) {
+        c64 *zcol = Zw + slot * ZS + p * ZROW;
+        dft_prune_in<T, Q, +1>(yin, [&](auto ttc, c64 val) __attribute__((always_inline)) {
+            constexpr int tt = decltype(ttc)::value;
+            if constexpr (tt == 0) zcol[0] = val;
+            else {
+                c64 w = TW[tt * P + p];
+                zcol[tt] = cmul(val, make_float2(w.x, -w.y));
+            }
+        });
+    };
+    // stage A' for the pencil in Z slot jw of this wave: P-point inverse transform, store
     auto ifft_store = [&](int o) __attribute__((always_inline)) {
         c64 z[P], r[P];
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            c64 zz = Zw[jw * ZS + p * ZROW + t];
-            c64 w = TW[p * T + t];
-            z[p] = p == 0 ? zz : cmul(zz, make_float2(w.x, -w.y));
-        }
+        for (int p = 0; p < P; ++p) z[p] = Zw[jw * ZS + p * ZROW + t];
         RegFFT<P, +1, 1>::run(z, r);
         if (EVEN || o < a.C_out) {
             c64 *dst = yb + (long long)o * a.y_chan_stride + t;
@@ -266,7 +314,7 @@ k_fused1d(Fused1dArgs a)
 #pragma unroll
             for (int sub = 0; sub < RPA; ++sub) {
                 const int r = rr + sub;
-                c64 yin[Q], u[T];
+                c64 yin[Q];
                 static_for<0, 16>([&](auto rc) {
                     constexpr int R = decltype(rc)::value;
                     if (r == R) {
@@ -274,10 +322,7 @@ k_fused1d(Fused1dArgs a)
                         for (int q = 0; q < Q; ++q) yin[q] = make_float2(acc_re[q][R], acc_im[q][R]);
                     }
                 });
-                dft_prune_in<T, Q, +1>(yin, u);
-                const int slot = 2 * sub + h;
-#pragma unroll
-                for (int tt = 0; tt < T; ++tt) Zw[slot * ZS + p * ZROW + tt] = u[tt];
+                stage_b_inv(yin, 2 * sub + h, p);
             }
             wave_sync();
             const int r2 = rr + jw / 2;
@@ -310,12 +355,10 @@ k_fused1d(Fused1dArgs a)
                     const int item = lane + 64 * cc;
                     const int j = item / P, p = item % P;
                     const int ol = 8 * wave + rd * PPW + j;
-                    c64 yin[Q], u[T];
+                    c64 yin[Q];
 #pragma unroll
                     for (int q = 0; q < Q; ++q) yin[q] = YH[ol * YROW + p + P * q];
-                    dft_prune_in<T, Q, +1>(yin, u);
-#pragma unroll
-                    for (int tt = 0; tt < T; ++tt) Zw[j * ZS + p * ZROW + tt] = u[tt];
+                    stage_b_inv(yin, j, p);
                 }
                 wave_sync();
                 ifft_store(o_base + 32 * ot + 8 * wave + rd * PPW + jw);
@@ -324,6 +367,7 @@ k_fused1d(Fused1dArgs a)
             __syncthreads();
         }
     }
+    TFNO_STAMP(3);
 }
 
 template <int N, int K, int OT>
@@ -333,18 +377,18 @@ hipError_t launch_fused1d(const Fused1dArgs &a, long long batch_rows, hipStream_
     static bool attr_done = false;   // benign race: every thread sets the same value
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
     if (a.C_in % C::PPI == 0 && a.C_out % 32 == 0)
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, true>), grid, dim3(256), C::LDS_BYTES, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true>), grid, dim3(256), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, false>), grid, dim3(256), C::LDS_BYTES, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false>), grid, dim3(256), C::LDS_DYN, s, a);
     return hipGetLastError();
 }
 
