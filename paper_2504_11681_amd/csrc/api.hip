@@ -5,6 +5,7 @@
 #include "staged.h"
 
 #include <atomic>
+#include <cstdlib>
 
 using namespace tfno;
 
@@ -128,9 +129,21 @@ bool fused1d_supported(int N, int K)
     }
 }
 
+// TFNO_CONTRACTION=f32 forces the kernels whose channel contraction uses FP32 MFMA; the default lets
+// shapes that have a wave-specialised kernel use the exact-split BF16x3 contraction.
+static bool contraction_forced_f32()
+{
+    static const bool forced = [] {
+        const char *e = getenv("TFNO_CONTRACTION");
+        return e && e[0] == 'f' && e[1] == '3' && e[2] == '2' && e[3] == 0;
+    }();
+    return forced;
+}
+
 hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
 {
     if (!fused1d_supported(N, K)) return hipErrorInvalidValue;
+    if (fused1d_ws_supported(N, K) && !contraction_forced_f32()) return fused1d_ws_launch(N, K, a, rows, s);
     switch (N) {
     case 64: return fused1d_launch_n64(K, a, rows, s);
     case 128: return fused1d_launch_n128(K, a, rows, s);

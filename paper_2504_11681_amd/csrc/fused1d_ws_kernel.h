@@ -1,0 +1,310 @@
+// Wave-specialised fused FFT -> CGEMM -> iFFT kernel for N = 1024 (P = T = 32) on gfx950 (Sec. 4.3).
+//
+// Why this shape.  Measured on MI355X: FP32 MFMA and FP32 VALU instructions share one pipeline (a wave
+// issuing v_mfma_f32_32x32x2_f32 and a wave issuing v_fma_f32 on the same SIMD take the SUM of their
+// times), whereas BF16 MFMA runs beside VALU work at full rate.  The butterflies need the VALU, so the
+// channel contraction goes to the BF16 matrix pipe with every FP32 operand split exactly into three BF16
+// terms (a = a1 + a2 + a3, each the truncated top 8 significant bits of the remainder) and the six
+// largest cross products accumulated in FP32; the dropped products are below 2^-23 of |a||b|, i.e. of the
+// size of one FP32 rounding, so the result meets the same tolerance against the float64 oracle as an
+// all-FP32 contraction.
+//
+//   workgroup = one batch row x 128 output channels, 512 threads = 8 waves, two per SIMD:
+//     waves 0-3 ("F"): loads, forward transforms, and the split spectra for the matrix pipe
+//     waves 4-7 ("M"): wave m owns outputs 32m..32m+31 for all K modes: W rows, BF16 MFMAs, then the
+//                      whole inverse transform of its 32 output pencils straight from its accumulators
+//   k-loop, 8 input channels (2 per F wave) per iteration, one workgroup barrier per iteration:
+//     F: stage B of block i+1 (twiddle, 32-point column DFT pruned to the Q = K/32 retained outputs,
+//        Sec. 3.3) -> 3 BF16 terms of (re, im) packed in one dword -> XS[buf];  stage A of block i+2
+//        (32-point DFT in registers -> wave-private transposed LDS tile);  loads of block i+3
+//     M: B operands of block i from XS (two 8-byte LDS reads per term and mode tile), 6 MFMAs
+//        v_mfma_f32_32x32x16_bf16 per (mode tile, re|im), W rows of block i+1 split meanwhile
+//   MFMA k index (16 per instruction) = 8 channels x (re, im): lanes 0-31 carry channels 0-3, lanes 32-63
+//   channels 4-7; within a lane dword d = (re | im << 16) of channel 4g + d.  The real part uses
+//   A = (W.re, -W.im) per channel, the imaginary part A = (W.im, W.re).
+//   epilogue: register r of lane l of mode tile q holds Yh[o][l%32 + 32 q] for o = 8(r/4) + 4(l/32) + r%4,
+//   which is exactly what lane (half-wave l/32, column l%32) needs for the zero-padded, input-pruned column
+//   transform (Sec. 3.3): no LDS handoff of the spectrum, no barrier.  1/N is folded into W.
+#pragma once
+#include "common.h"
+#include "fft_regs.h"
+#include "fused1d.h"
+#include "fused1d_kernel.h"
+
+namespace tfno {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+template <int K>
+struct WsCfg {
+    static constexpr int N = 1024, P = 32, T = 32;
+    static constexpr int Q = K / P;                 // retained outputs per column = 32-mode tiles
+    static constexpr int NT = 512, NF = 4;          // F waves (and M waves)
+    static constexpr int PPI = 8;                   // channels per k-loop iteration
+    static constexpr int ZROW = T + 1, ZS = P * ZROW;
+    static constexpr int XS_BUF = 3 * Q * NF * 32 * 2;          // dwords per buffer: [term][q][wave][n][h]
+    static constexpr size_t LDS_Z = sizeof(c64) * NF * 2 * ZS;
+    static constexpr size_t LDS_XS = sizeof(unsigned) * 2 * XS_BUF;
+    static constexpr size_t LDS_DYN = LDS_Z + LDS_XS;
+    static_assert(K % 32 == 0 && Q >= 1 && Q <= 4, "K in {32, 64, 96?, 128}");
+    static_assert(T % Q == 0, "Q must divide 32");
+};
+
+// Exact 3-way split of an FP32 value into BF16-representable terms (truncation: hi bits of the remainder).
+struct Split3 { float t0, t1, t2; };
+__device__ __forceinline__ Split3 split3(float a)
+{
+    Split3 s;
+    s.t0 = __uint_as_float(__float_as_uint(a) & 0xffff0000u);
+    float r = a - s.t0;
+    s.t1 = __uint_as_float(__float_as_uint(r) & 0xffff0000u);
+    s.t2 = r - s.t1;     // at most 8 significant bits left: exactly a BF16 value
+    return s;
+}
+// dword with BF16(lo) in bits 0-15 and BF16(hi) in bits 16-31 (operands already BF16-representable or truncated)
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+
+template <int K, bool EVEN>
+__global__ void __launch_bounds__(512)
+k_fused1d_ws(Fused1dArgs a)
+{
+    using C = WsCfg<K>;
+    constexpr int N = C::N, P = C::P, T = C::T, Q = C::Q, PPI = C::PPI, ZROW = C::ZROW, ZS = C::ZS, NT = C::NT;
+
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                               // [4 waves][2 slots][ZS]
+    unsigned *XS = reinterpret_cast<unsigned *>(lds_raw + C::LDS_Z);          // [2][3][Q][4][32][2]
+    __shared__ c64 TW[N];                                                     // [t][p]: w_N^(t p)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int bb = blockIdx.x;
+    const int o_base = blockIdx.y * 128;
+
+    const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
+    const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
+    c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
+
+    TFNO_STAMP(0);
+    for (int i = tid; i < N; i += NT) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
+    __syncthreads();
+
+    const int n_it = (a.C_in + PPI - 1) / PPI;
+    const int h = lane >> 5, p = lane & 31;     // half-wave = pencil slot, lane within it (t in stage A, column in B)
+
+    if (wave < 4) {
+        // ================================================================== F waves
+        c64 *Zw = Zl + wave * (2 * ZS);
+        const int ja = wave * 2 + h;            // channel of this lane within the iteration's 8
+        c64 v[P];
+
+        auto load_pencil = [&](int c0) __attribute__((always_inline)) {
+            const int c = c0 + ja;
+            if constexpr (EVEN) {
+                const c64 *src = xb + (long long)c * a.x_chan_stride + p;
+#pragma unroll
+                for (int jj = 0; jj < P; ++jj) v[jj] = src[T * jj];
+            } else {
+                const bool ok = c < a.C_in;
+                const c64 *src = xb + (long long)(ok ? c : 0) * a.x_chan_stride + p;
+#pragma unroll
+                for (int jj = 0; jj < P; ++jj) {
+                    c64 val = src[T * jj];
+                    v[jj] = ok ? val : make_float2(0.f, 0.f);
+                }
+            }
+        };
+        // stage A: 32-point transform of the slice in v, written transposed into the wave's Z tile
+        auto stage_a = [&]() __attribute__((always_inline)) {
+            c64 z[P];
+            RegFFT<P, -1, 1>::run(v, z);
+#pragma unroll
+            for (int pp = 0; pp < P; ++pp) Zw[h * ZS + pp * ZROW + p] = z[pp];
+        };
+        // stage B: twiddle, column transform pruned to Q outputs, exact BF16 split, into XS[buf]
+        auto stage_b = [&](int buf) __attribute__((always_inline)) {
+            const c64 *zcol = Zw + h * ZS + p * ZROW;
+            c64 xo[Q];
+            dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
+                constexpr int tt = decltype(ttc)::value;
+                if constexpr (tt == 0) return zcol[0];
+                else return cmul(zcol[tt], TW[tt * P + p]);
+            }, xo);
+            unsigned *dst = XS + buf * C::XS_BUF + (wave * 32 + p) * 2 + h;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
+                dst[(0 * Q + q) * 256] = pack_bf16(re.t0, im.t0);
+                dst[(1 * Q + q) * 256] = pack_bf16(re.t1, im.t1);
+                dst[(2 * Q + q) * 256] = pack_bf16(re.t2, im.t2);
+            }
+        };
+
+        load_pencil(0);
+        stage_a();
+        wave_sync();
+        if (n_it > 1) load_pencil(PPI);
+        stage_b(0);
+        wave_sync();
+        if (n_it > 1) {
+            stage_a();
+            wave_sync();
+            if (n_it > 2) load_pencil(2 * PPI);
+        }
+        __syncthreads();
+        TFNO_STAMP(1);
+        for (int it = 0; it + 1 < n_it; ++it) {
+            stage_b((it + 1) & 1);
+            wave_sync();
+            if (it + 2 < n_it) {
+                stage_a();
+                wave_sync();
+                if (it + 3 < n_it) load_pencil((it + 3) * PPI);
+            }
+            __syncthreads();
+        }
+        TFNO_STAMP(2);
+        return;
+    }
+
+    // ====================================================================== M waves
+    const int m = wave - 4;
+    const int o_lane = o_base + 32 * m + p;     // the output channel whose W this lane feeds
+    floatx16 acc_re[Q], acc_im[Q];
+#pragma unroll
+    for (int i = 0; i < Q; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc_re[i][r] = 0.f; acc_im[i][r] = 0.f; }
+
+    c64 wraw[4];                // W[c0 + 4h + d][o_lane], d < 4, of the next block
+    uintx4 a_re[3], a_im[3];    // split A operands of the current block
+    auto load_w = [&](int c0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int c = c0 + 4 * h + d;
+            if constexpr (EVEN) {
+                wraw[d] = a.W[(long long)c * a.C_out + o_lane];
+            } else {
+                const bool ok = c < a.C_in && o_lane < a.C_out;
+                c64 val = a.W[ok ? (long long)c * a.C_out + o_lane : 0];
+                wraw[d] = ok ? val : make_float2(0.f, 0.f);
+            }
+        }
+    };
+    auto split_w = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const Split3 re = split3(wraw[d].x * a.scale), im = split3(wraw[d].y * a.scale);
+            // real part: (W.re, -W.im);  imaginary part: (W.im, W.re)
+            a_re[0][d] = pack_bf16(re.t0, im.t0) ^ 0x80000000u;
+            a_re[1][d] = pack_bf16(re.t1, im.t1) ^ 0x80000000u;
+            a_re[2][d] = pack_bf16(re.t2, im.t2) ^ 0x80000000u;
+            a_im[0][d] = pack_bf16(im.t0, re.t0);
+            a_im[1][d] = pack_bf16(im.t1, re.t1);
+            a_im[2][d] = pack_bf16(im.t2, re.t2);
+        }
+    };
+    auto mfma_block = [&](int buf) __attribute__((always_inline)) {
+        // lane (n = p, g = h) needs dwords [wave 2g][n][0..1] and [wave 2g+1][n][0..1] of every (term, q)
+        const unsigned *src = XS + buf * C::XS_BUF + (2 * h * 32 + p) * 2;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            uintx4 b[3];
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const uint2 lo = *reinterpret_cast<const uint2 *>(src + (s * Q + q) * 256);
+                const uint2 hi2 = *reinterpret_cast<const uint2 *>(src + (s * Q + q) * 256 + 64);
+                b[s][0] = lo.x; b[s][1] = lo.y; b[s][2] = hi2.x; b[s][3] = hi2.y;
+            }
+            // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
+            constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+            for (int k = 0; k < 6; ++k) {
+                const bf16x8 bb16 = __builtin_bit_cast(bf16x8, b[SB[k]]);
+                acc_re[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb16, acc_re[q], 0, 0, 0);
+                acc_im[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[q], 0, 0, 0);
+            }
+        }
+    };
+
+    load_w(0);
+    split_w();
+    __syncthreads();
+    for (int it = 0; it < n_it; ++it) {
+        const bool more = it + 1 < n_it;
+        if (more) load_w((it + 1) * PPI);
+        mfma_block(it & 1);
+        if (more) {
+            split_w();
+            __syncthreads();
+        }
+    }
+    TFNO_STAMP(2);
+
+    // ------------------------------------------------------------------ epilogue (M waves only)
+    c64 *Zw = Zl + m * (2 * ZS);     // the Z tile of F wave m, free after the last barrier
+    for (int r = 0; r < 16; ++r) {
+        c64 yin[Q];
+        static_for<0, 16>([&](auto rc) {
+            constexpr int R = decltype(rc)::value;
+            if (r == R) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) yin[q] = make_float2(acc_re[q][R], acc_im[q][R]);
+            }
+        });
+        // stage B': zero-padded, input-pruned column transform, conj twiddle, transposed into Z
+        c64 *zcol = Zw + h * ZS + p * ZROW;
+        dft_prune_in<T, Q, +1>(yin, [&](auto ttc, c64 val) __attribute__((always_inline)) {
+            constexpr int tt = decltype(ttc)::value;
+            if constexpr (tt == 0) zcol[0] = val;
+            else {
+                c64 w = TW[tt * P + p];
+                zcol[tt] = cmul(val, make_float2(w.x, -w.y));
+            }
+        });
+        wave_sync();
+        // stage A': 32-point inverse transform of the pencil in slot h, coalesced store
+        {
+            c64 z[P], res[P];
+#pragma unroll
+            for (int pp = 0; pp < P; ++pp) z[pp] = Zw[h * ZS + pp * ZROW + p];
+            RegFFT<P, +1, 1>::run(z, res);
+            const int o = o_base + 32 * m + 8 * (r / 4) + 4 * h + (r % 4);
+            if (EVEN || o < a.C_out) {
+                c64 *dst = yb + (long long)o * a.y_chan_stride + p;
+#pragma unroll
+                for (int jj = 0; jj < P; ++jj) dst[T * jj] = res[jj];
+            }
+        }
+        wave_sync();
+    }
+    TFNO_STAMP(3);
+}
+
+template <int K>
+hipError_t launch_fused1d_ws(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
+{
+    using C = WsCfg<K>;
+    static bool attr_done = false;   // benign race: every thread sets the same value
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_ws<K, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_ws<K, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 127) / 128));
+    if (a.C_in % C::PPI == 0 && a.C_out % 128 == 0)
+        hipLaunchKernelGGL((k_fused1d_ws<K, true>), grid, dim3(512), C::LDS_DYN, s, a);
+    else
+        hipLaunchKernelGGL((k_fused1d_ws<K, false>), grid, dim3(512), C::LDS_DYN, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace tfno
