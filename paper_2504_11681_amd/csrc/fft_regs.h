@@ -84,6 +84,20 @@ struct RegFFT<1, DIR, STRIDE> {
     TFNO_HD static void run(const c64 *in, c64 *out) { out[0] = in[0]; }
 };
 
+// First (decimation-in-frequency) level of an L-point transform: after it the input registers are dead, so a
+// caller can refill them from memory while the two half-size transforms run.
+//   even outputs  X[2k]   = DFT_{L/2}(a)[k],  a[i] = v[i] + v[i + L/2]
+//   odd outputs   X[2k+1] = DFT_{L/2}(b)[k],  b[i] = (v[i] - v[i + L/2]) exp(DIR 2 pi i i / L)
+template <int L, int DIR>
+TFNO_HD void dif_first_level(const c64 *v, c64 *a, c64 *b)
+{
+    static_for<0, L / 2>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        a[i] = cadd(v[i], v[i + L / 2]);
+        b[i] = mul_tw<L, DIR, i>(csub(v[i], v[i + L / 2]));
+    });
+}
+
 // out[q] = sum_{t<T} in(t) exp(DIR 2 pi i t q / T),  q < Q,  Q | T.     in: callable int -> c64
 // t = t1 + S t2 (S = T/Q):  S full Q-point transforms of the decimated input, then a twiddled S-term sum.
 // The input is consumed Q values at a time, so a caller that reads it from LDS keeps only one group live.

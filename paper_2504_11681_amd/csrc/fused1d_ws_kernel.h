@@ -10,26 +10,32 @@
 // all-FP32 contraction.
 //
 //   workgroup = one batch row x 128 output channels, 512 threads = 8 waves, two per SIMD:
-//     waves 0-3 ("F"): loads, forward transforms, and the split spectra for the matrix pipe
-//     waves 4-7 ("M"): wave m owns outputs 32m..32m+31 for all K modes: W rows, BF16 MFMAs, then the
-//                      whole inverse transform of its 32 output pencils straight from its accumulators
-//   k-loop, 8 input channels (2 per F wave) per iteration, one workgroup barrier per iteration:
-//     F: stage B of block i+1 (twiddle, 32-point column DFT pruned to the Q = K/32 retained outputs,
-//        Sec. 3.3) -> 3 BF16 terms of (re, im) packed in one dword -> XS[buf];  stage A of block i+2
-//        (32-point DFT in registers -> wave-private transposed LDS tile);  loads of block i+3
+//     waves 0-3 ("F"): global loads and stores and the 32-point row stage of both transforms
+//     waves 4-7 ("M"): the 32-point column stage of both transforms and the matrix pipe; wave m owns
+//                      outputs 32m..32m+31 for all K modes
+//   k-loop, 8 input channels (2 per F wave) per iteration, one workgroup barrier per iteration,
+//   Z and XS double buffered:
+//     F: stage A of block i+2 (32-point DFT in registers -> transposed LDS tile Z);  loads of block i+3
 //     M: B operands of block i from XS (two 8-byte LDS reads per term and mode tile), 6 MFMAs
-//        v_mfma_f32_32x32x16_bf16 per (mode tile, re|im), W rows of block i+1 split meanwhile
+//        v_mfma_f32_32x32x16_bf16 per (mode tile, re|im);  stage B of block i+1 from Z (twiddle, column
+//        DFT pruned to the Q = K/32 retained outputs, Sec. 3.3) -> 3 BF16 terms of (re, im) packed in
+//        one dword -> XS;  W rows of block i+1 split meanwhile
 //   MFMA k index (16 per instruction) = 8 channels x (re, im): lanes 0-31 carry channels 0-3, lanes 32-63
 //   channels 4-7; within a lane dword d = (re | im << 16) of channel 4g + d.  The real part uses
 //   A = (W.re, -W.im) per channel, the imaginary part A = (W.im, W.re).
 //   epilogue: register r of lane l of mode tile q holds Yh[o][l%32 + 32 q] for o = 8(r/4) + 4(l/32) + r%4,
 //   which is exactly what lane (half-wave l/32, column l%32) needs for the zero-padded, input-pruned column
-//   transform (Sec. 3.3): no LDS handoff of the spectrum, no barrier.  1/N is folded into W.
+//   transform (Sec. 3.3): the spectrum never goes through LDS.  M waves write the expanded columns to Z,
+//   F waves run the 32-point inverse row stage and store, pipelined one round apart.  1/N is folded into W.
 #pragma once
 #include "common.h"
 #include "fft_regs.h"
 #include "fused1d.h"
 #include "fused1d_kernel.h"
+
+#ifndef TFNO_WS_STAMP
+#define TFNO_WS_STAMP(role, it, i)   // development hook, empty in the library
+#endif
 
 namespace tfno {
 
@@ -42,13 +48,16 @@ struct WsCfg {
     static constexpr int Q = K / P;                 // retained outputs per column = 32-mode tiles
     static constexpr int NT = 512, NF = 4;          // F waves (and M waves)
     static constexpr int PPI = 8;                   // channels per k-loop iteration
-    static constexpr int ZROW = T + 1, ZS = P * ZROW;
+    static constexpr int ZS = P * T;                // one pencil tile, rows XOR-swizzled instead of padded
+    static constexpr int Z_BUF = NF * 2 * ZS;       // complex elements per Z buffer
     static constexpr int XS_BUF = 3 * Q * NF * 32 * 2;          // dwords per buffer: [term][q][wave][n][h]
-    static constexpr size_t LDS_Z = sizeof(c64) * NF * 2 * ZS;
+    static constexpr size_t LDS_Z = sizeof(c64) * 2 * Z_BUF;
     static constexpr size_t LDS_XS = sizeof(unsigned) * 2 * XS_BUF;
     static constexpr size_t LDS_DYN = LDS_Z + LDS_XS;
-    static_assert(K % 32 == 0 && Q >= 1 && Q <= 4, "K in {32, 64, 96?, 128}");
+    static constexpr size_t LDS_TW = sizeof(c64) * N;
+    static_assert(K % 32 == 0 && Q >= 1 && Q <= 4, "K in {32, 64, 128}");
     static_assert(T % Q == 0, "Q must divide 32");
+    static_assert(LDS_DYN + LDS_TW <= 160 * 1024, "LDS budget of one gfx950 CU");
 };
 
 // Exact 3-way split of an FP32 value into BF16-representable terms (truncation: hi bits of the remainder).
@@ -73,10 +82,10 @@ __global__ void __launch_bounds__(512)
 k_fused1d_ws(Fused1dArgs a)
 {
     using C = WsCfg<K>;
-    constexpr int N = C::N, P = C::P, T = C::T, Q = C::Q, PPI = C::PPI, ZROW = C::ZROW, ZS = C::ZS, NT = C::NT;
+    constexpr int N = C::N, P = C::P, T = C::T, Q = C::Q, PPI = C::PPI, ZS = C::ZS, NT = C::NT;
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                               // [4 waves][2 slots][ZS]
+    c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                               // [2][4 waves][2 slots][32 rows][32]
     unsigned *XS = reinterpret_cast<unsigned *>(lds_raw + C::LDS_Z);          // [2][3][Q][4][32][2]
     __shared__ c64 TW[N];                                                     // [t][p]: w_N^(t p)
 
@@ -90,15 +99,15 @@ k_fused1d_ws(Fused1dArgs a)
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
 
     TFNO_STAMP(0);
-    for (int i = tid; i < N; i += NT) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
-    __syncthreads();
-
     const int n_it = (a.C_in + PPI - 1) / PPI;
-    const int h = lane >> 5, p = lane & 31;     // half-wave = pencil slot, lane within it (t in stage A, column in B)
+    const int h = lane >> 5, p = lane & 31;     // half-wave = pencil slot; p = t in the row stage, column in the column stage
+    // Z tile element (row pp, position t) of this half-wave's pencil lives at  pp*32 + (t ^ pp):
+    // a row write (lanes = consecutive t) and a column read (lanes = consecutive pp) both hit 32 distinct
+    // 8-byte slots, with no padding.
 
     if (wave < 4) {
-        // ================================================================== F waves
-        c64 *Zw = Zl + wave * (2 * ZS);
+        // ================================================================== F waves: global memory + row stage
+        const int ztile = (wave * 2 + h) * ZS;
         const int ja = wave * 2 + h;            // channel of this lane within the iteration's 8
         c64 v[P];
 
@@ -118,62 +127,65 @@ k_fused1d_ws(Fused1dArgs a)
                 }
             }
         };
-        // stage A: 32-point transform of the slice in v, written transposed into the wave's Z tile
-        auto stage_a = [&]() __attribute__((always_inline)) {
-            c64 z[P];
-            RegFFT<P, -1, 1>::run(v, z);
+        // stage A: 32-point transform of the slice in v, written transposed into Z buffer `zb`.  The first
+        // butterfly level consumes v, so the loads of block `next_c0` (if >= 0) are issued right after it and
+        // stay in flight for a whole iteration while the two 16-point halves run.
+        auto stage_a = [&](int zb, int next_c0) __attribute__((always_inline)) {
+            c64 ea[P / 2], eb[P / 2], za[P / 2], zo[P / 2];
+            dif_first_level<P, -1>(v, ea, eb);
+            // keep the refill right here: the scheduler must not sink these loads below the butterflies
+            __builtin_amdgcn_sched_barrier(0);
+            if (next_c0 >= 0) load_pencil(next_c0);
+            __builtin_amdgcn_sched_barrier(0);
+            RegFFT<P / 2, -1, 1>::run(ea, za);
+            RegFFT<P / 2, -1, 1>::run(eb, zo);
+            c64 *Zt = Zl + zb * C::Z_BUF + ztile;
 #pragma unroll
-            for (int pp = 0; pp < P; ++pp) Zw[h * ZS + pp * ZROW + p] = z[pp];
-        };
-        // stage B: twiddle, column transform pruned to Q outputs, exact BF16 split, into XS[buf]
-        auto stage_b = [&](int buf) __attribute__((always_inline)) {
-            const c64 *zcol = Zw + h * ZS + p * ZROW;
-            c64 xo[Q];
-            dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
-                constexpr int tt = decltype(ttc)::value;
-                if constexpr (tt == 0) return zcol[0];
-                else return cmul(zcol[tt], TW[tt * P + p]);
-            }, xo);
-            unsigned *dst = XS + buf * C::XS_BUF + (wave * 32 + p) * 2 + h;
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
-                dst[(0 * Q + q) * 256] = pack_bf16(re.t0, im.t0);
-                dst[(1 * Q + q) * 256] = pack_bf16(re.t1, im.t1);
-                dst[(2 * Q + q) * 256] = pack_bf16(re.t2, im.t2);
+            for (int k = 0; k < P / 2; ++k) {
+                Zt[(2 * k) * 32 + (p ^ (2 * k))] = za[k];
+                Zt[(2 * k + 1) * 32 + (p ^ (2 * k + 1))] = zo[k];
             }
         };
 
         load_pencil(0);
-        stage_a();
-        wave_sync();
-        if (n_it > 1) load_pencil(PPI);
-        stage_b(0);
-        wave_sync();
-        if (n_it > 1) {
-            stage_a();
-            wave_sync();
-            if (n_it > 2) load_pencil(2 * PPI);
-        }
-        __syncthreads();
+        stage_a(0, n_it > 1 ? PPI : -1);
+        __syncthreads();                                    // P1: Z[0] holds block 0
+        if (n_it > 1) stage_a(1, n_it > 2 ? 2 * PPI : -1);
+        __syncthreads();                                    // P2
         TFNO_STAMP(1);
         for (int it = 0; it + 1 < n_it; ++it) {
-            stage_b((it + 1) & 1);
-            wave_sync();
-            if (it + 2 < n_it) {
-                stage_a();
-                wave_sync();
-                if (it + 3 < n_it) load_pencil((it + 3) * PPI);
-            }
+            TFNO_WS_STAMP(0, it, 0);
+#ifndef TFNO_DBG_NO_F
+            if (it + 2 < n_it) stage_a(it & 1, it + 3 < n_it ? (it + 3) * PPI : -1);
+#endif
+            TFNO_WS_STAMP(0, it, 1);
             __syncthreads();
+            TFNO_WS_STAMP(0, it, 2);
         }
         TFNO_STAMP(2);
+        // epilogue: stage A' of the pencil the M wave (wave + 4) left in Z[r & 1], coalesced store
+        for (int r = 0; r < 16; ++r) {
+            __syncthreads();                                // E_r: Z[r & 1] holds round r
+            const c64 *Zt = Zl + (r & 1) * C::Z_BUF + ztile;
+            c64 z[P], res[P];
+#pragma unroll
+            for (int pp = 0; pp < P; ++pp) z[pp] = Zt[pp * 32 + (p ^ pp)];
+            RegFFT<P, +1, 1>::run(z, res);
+            const int o = o_base + 32 * wave + 8 * (r / 4) + 4 * h + (r % 4);
+            if (EVEN || o < a.C_out) {
+                c64 *dst = yb + (long long)o * a.y_chan_stride + p;
+#pragma unroll
+                for (int jj = 0; jj < P; ++jj) dst[T * jj] = res[jj];
+            }
+        }
+        TFNO_STAMP(3);
         return;
     }
 
-    // ====================================================================== M waves
+    // ====================================================================== M waves: column stage + matrix pipe
     const int m = wave - 4;
     const int o_lane = o_base + 32 * m + p;     // the output channel whose W this lane feeds
+    const int ztile = (m * 2 + h) * ZS + p * 32;            // row p of the tile = column p of the pencil
     floatx16 acc_re[Q], acc_im[Q];
 #pragma unroll
     for (int i = 0; i < Q; ++i)
@@ -208,6 +220,25 @@ k_fused1d_ws(Fused1dArgs a)
             a_im[2][d] = pack_bf16(im.t2, re.t2);
         }
     };
+    // stage B of the pencil F wave m left in Z buffer zb: twiddle, column transform pruned to Q outputs
+    // (Sec. 3.3), exact BF16 split, into XS[xb]
+    auto stage_b = [&](int zb, int xbuf) __attribute__((always_inline)) {
+        const c64 *zcol = Zl + zb * C::Z_BUF + ztile;
+        c64 xo[Q];
+        dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
+            constexpr int tt = decltype(ttc)::value;
+            if constexpr (tt == 0) return zcol[p];
+            else return cmul(zcol[tt ^ p], TW[tt * P + p]);
+        }, xo);
+        unsigned *dst = XS + xbuf * C::XS_BUF + (m * 32 + p) * 2 + h;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
+            dst[(0 * Q + q) * 256] = pack_bf16(re.t0, im.t0);
+            dst[(1 * Q + q) * 256] = pack_bf16(re.t1, im.t1);
+            dst[(2 * Q + q) * 256] = pack_bf16(re.t2, im.t2);
+        }
+    };
     auto mfma_block = [&](int buf) __attribute__((always_inline)) {
         // lane (n = p, g = h) needs dwords [wave 2g][n][0..1] and [wave 2g+1][n][0..1] of every (term, q)
         const unsigned *src = XS + buf * C::XS_BUF + (2 * h * 32 + p) * 2;
@@ -231,22 +262,37 @@ k_fused1d_ws(Fused1dArgs a)
         }
     };
 
+    // the twiddle table is only read by the column stage, so the M waves build it (accurate sincospi) while
+    // the F waves already stream the first pencils; barrier P1 publishes it
+    for (int i = tid - 256; i < N; i += 256) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
     load_w(0);
     split_w();
-    __syncthreads();
+    __syncthreads();                                        // P1
+    stage_b(0, 0);
+    __syncthreads();                                        // P2: XS[0] holds block 0
     for (int it = 0; it < n_it; ++it) {
         const bool more = it + 1 < n_it;
+        TFNO_WS_STAMP(1, it, 0);
         if (more) load_w((it + 1) * PPI);
+#ifndef TFNO_DBG_NO_MFMA
         mfma_block(it & 1);
+#endif
+        TFNO_WS_STAMP(1, it, 1);
         if (more) {
+#ifndef TFNO_DBG_NO_STAGEB
+            stage_b((it + 1) & 1, (it + 1) & 1);
+#endif
+            TFNO_WS_STAMP(1, it, 2);
             split_w();
+            TFNO_WS_STAMP(1, it, 3);
             __syncthreads();
+            TFNO_WS_STAMP(1, it, 4);
         }
     }
-    TFNO_STAMP(2);
 
-    // ------------------------------------------------------------------ epilogue (M waves only)
-    c64 *Zw = Zl + m * (2 * ZS);     // the Z tile of F wave m, free after the last barrier
+    // ------------------------------------------------------------------ epilogue: column stage from registers
+    // Register r of lane l of mode tile q holds Yh[o][p + 32 q] with o = 32 m + 8(r/4) + 4h + r%4: the Q inputs
+    // lane (h, p) needs for the zero-padded, input-pruned column transform of that pencil (Sec. 3.3).
     for (int r = 0; r < 16; ++r) {
         c64 yin[Q];
         static_for<0, 16>([&](auto rc) {
@@ -256,33 +302,17 @@ k_fused1d_ws(Fused1dArgs a)
                 for (int q = 0; q < Q; ++q) yin[q] = make_float2(acc_re[q][R], acc_im[q][R]);
             }
         });
-        // stage B': zero-padded, input-pruned column transform, conj twiddle, transposed into Z
-        c64 *zcol = Zw + h * ZS + p * ZROW;
+        c64 *zcol = Zl + (r & 1) * C::Z_BUF + ztile;
         dft_prune_in<T, Q, +1>(yin, [&](auto ttc, c64 val) __attribute__((always_inline)) {
             constexpr int tt = decltype(ttc)::value;
-            if constexpr (tt == 0) zcol[0] = val;
+            if constexpr (tt == 0) zcol[p] = val;
             else {
                 c64 w = TW[tt * P + p];
-                zcol[tt] = cmul(val, make_float2(w.x, -w.y));
+                zcol[tt ^ p] = cmul(val, make_float2(w.x, -w.y));
             }
         });
-        wave_sync();
-        // stage A': 32-point inverse transform of the pencil in slot h, coalesced store
-        {
-            c64 z[P], res[P];
-#pragma unroll
-            for (int pp = 0; pp < P; ++pp) z[pp] = Zw[h * ZS + pp * ZROW + p];
-            RegFFT<P, +1, 1>::run(z, res);
-            const int o = o_base + 32 * m + 8 * (r / 4) + 4 * h + (r % 4);
-            if (EVEN || o < a.C_out) {
-                c64 *dst = yb + (long long)o * a.y_chan_stride + p;
-#pragma unroll
-                for (int jj = 0; jj < P; ++jj) dst[T * jj] = res[jj];
-            }
-        }
-        wave_sync();
+        __syncthreads();                                    // E_r
     }
-    TFNO_STAMP(3);
 }
 
 template <int K>
