@@ -47,16 +47,16 @@ def time_calls(torch, fn, steps: int, warmup: int):
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
+    e0.record()
+    for _ in range(steps):
         fn()
-        b.record()
+    e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    dev = sum(a.elapsed_time(b) for a, b in ev) / steps * 1e-3
+    dev = e0.elapsed_time(e1) / steps * 1e-3     # back-to-back launches on one stream
     return wall, dev
 
 
@@ -104,6 +104,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy three times (reads 256 MiB, writes "
+                         "256 MiB per launch): the known-size kernel that calibrates rocprofv3's FETCH_SIZE / "
+                         "WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (the path shards over the batch axis with no "
@@ -115,12 +119,26 @@ def main():
         raise SystemExit("bench.py needs the MI355X (no CPU fallback exists)")
     binding.lib()
 
+    if args.copy_probe:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     w = pick_config(args.config)
     wall, dev = measure(w, torch, binding, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
     layers_per_s = args.steps / wall
     alg_bytes = w.compulsory_bytes
     achieved = alg_bytes / dev / 1e9
+    # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary, if one covers this workload
+    traffic = None
+    tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(w.name, {}).get("hbm_bytes_per_launch")
 
     out = {
         "metric": "fused_spectral_conv_layers_per_s",
@@ -141,8 +159,8 @@ def main():
         "effective_hbm_frac_of_peak": alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "contraction_TFLOPs": flops_of(w) / dev / 1e12,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "k_fused1d" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "kernel": "fused 1-D kernel (k_fused1d_ws / k_fused1d)" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": dev * 1e3},
     }
 
