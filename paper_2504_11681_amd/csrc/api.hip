@@ -2,6 +2,7 @@
 #include "../../include/tfno.h"
 #include "common.h"
 #include "fused1d.h"
+#include "fused2d.h"
 #include "staged.h"
 
 #include <atomic>
@@ -43,7 +44,8 @@ tfno_status validate(int dims, const void *x, const void *W, const void *y, int 
     return TFNO_OK;
 }
 
-size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int N, int K)
+// the strip pipeline keeps two [B, C, K, N] intermediates
+size_t strip2d_workspace_bytes(long long B, int C_in, int C_out, int N, int K)
 {
     return sizeof(c64) * (size_t)B * K * N * ((size_t)C_in + C_out);
 }
@@ -66,7 +68,7 @@ tfno_status run(int dims, bool staged, const void *x, const void *W, void *y, in
     bool empty;
     tfno_status st = validate(dims, x, W, y, B, C_in, C_out, N, K, &empty);
     if (st != TFNO_OK || empty) return st;
-    if (!staged && !fused1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+    if (!staged && !(dims == 2 && fused2d_supported(N, K)) && !fused1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
 
     const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
@@ -90,8 +92,11 @@ tfno_status run(int dims, bool staged, const void *x, const void *W, void *y, in
         a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
         a.scale = 1.0f / (float)N;
         e = fused1d_launch(N, K, a, B, s);
+    } else if (fused2d_supported(N, K)) {
+        // image kernels: only the truncated K x K spectra cross global memory
+        e = fused2d_launch(xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
     } else {
-        // 2-D pipeline (Sec. 3.2 / 3.3): truncated forward transform along the first axis, fused
+        // strip pipeline (Sec. 3.2 / 3.3), for shapes the image kernels do not cover: truncated forward transform along the first axis, fused
         // kernel along the last axis on the K retained rows, zero-padded inverse along the first axis.
         c64 *T1 = (c64 *)ws;                                   // [B, C_in,  K, N]
         c64 *T2 = T1 + (size_t)B * C_in * K * N;               // [B, C_out, K, N]
@@ -187,7 +192,8 @@ size_t tfno_workspace_bytes(int dims, int staged, int B, int C_in, int C_out, in
     if ((dims != 1 && dims != 2) || B < 1 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N)
         return 0;
     if (staged) return staged_workspace_bytes(dims, B, C_in, C_out, N, K);
-    return dims == 2 ? fused2d_workspace_bytes(B, C_in, C_out, N, K) : 0;
+    if (dims == 1) return 0;
+    return fused2d_supported(N, K) ? fused2d_workspace_bytes(B, C_in, C_out, K) : strip2d_workspace_bytes(B, C_in, C_out, N, K);
 }
 
 tfno_status tfno_set_workspace(void *dev_ptr, size_t bytes)

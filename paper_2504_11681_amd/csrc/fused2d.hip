@@ -1,0 +1,59 @@
+// Instantiations and launcher of the 2-D kernels.
+#include "fused2d_kernel.h"
+#include "fused2d.h"
+
+namespace tfno {
+
+bool fused2d_supported(int N, int K)
+{
+    return (N == 64 || N == 128 || N == 256) && (K == 16 || K == 32 || K == 64) && K <= N;
+}
+
+size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K)
+{
+    return sizeof(c64) * (size_t)B * K * K * ((size_t)C_in + C_out);
+}
+
+template <int N, int K>
+static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
+                            hipStream_t s)
+{
+    const int M = K * K;
+    c64 *Xh = ws, *Yh = ws + (size_t)B * C_in * M;
+    hipLaunchKernelGGL((k_fwd2d<N, K>), dim3((unsigned)(B * C_in)), dim3(256), 0, s, x, Xh);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int mblocks = (M + 255) / 256;
+    const float scale = 1.0f / ((float)N * (float)N);
+    hipLaunchKernelGGL(k_cgemm_modes, dim3((unsigned)(B * mblocks), (unsigned)((C_out + 31) / 32)), dim3(256), 0, s,
+                       (const c64 *)Xh, W, Yh, C_in, C_out, M, mblocks, scale);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((k_inv2d<N, K>), dim3((unsigned)(B * C_out)), dim3(256), 0, s, (const c64 *)Yh, y);
+    return hipGetLastError();
+}
+
+template <int N>
+static hipError_t launch_n(int K, const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
+                           hipStream_t s)
+{
+    switch (K) {
+    case 16: return launch_nk<N, 16>(x, W, y, B, C_in, C_out, ws, s);
+    case 32: return launch_nk<N, 32>(x, W, y, B, C_in, C_out, ws, s);
+    case 64: return launch_nk<N, 64>(x, W, y, B, C_in, C_out, ws, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
+                          c64 *ws, hipStream_t s)
+{
+    if (!fused2d_supported(N, K)) return hipErrorInvalidValue;
+    switch (N) {
+    case 64: return launch_n<64>(K, x, W, y, B, C_in, C_out, ws, s);
+    case 128: return launch_n<128>(K, x, W, y, B, C_in, C_out, ws, s);
+    case 256: return launch_n<256>(K, x, W, y, B, C_in, C_out, ws, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tfno

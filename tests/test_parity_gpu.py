@@ -100,7 +100,10 @@ def test_1d_staged_general_shapes(gpu, oracle_mod, shape):
     check(run_gpu(gpu, "spectral_conv1d_staged", x, W, K), want, "staged")
 
 
-SMALL_2D = [(2, 3, 5, 64, 16), (1, 8, 8, 64, 8), (2, 5, 33, 128, 32), (1, 4, 3, 256, 64), (1, 2, 2, 64, 64)]
+# image kernels (N in {64,128,256}, K in {16,32,64}) and, for the other shapes, the strip pipeline
+SMALL_2D = [(2, 3, 5, 64, 16), (1, 8, 8, 64, 8), (2, 5, 33, 128, 32), (1, 4, 3, 256, 64), (1, 2, 2, 64, 64),
+            (1, 3, 2, 64, 32), (1, 3, 2, 128, 16), (2, 2, 2, 128, 64), (1, 2, 3, 256, 16), (1, 2, 2, 256, 32),
+            (3, 7, 70, 256, 64), (1, 2, 2, 128, 128), (1, 2, 2, 512, 64)]
 
 
 @pytest.mark.parametrize("shape", SMALL_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
