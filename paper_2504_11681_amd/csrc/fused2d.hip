@@ -20,15 +20,17 @@ static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int
 {
     const int M = K * K;
     c64 *Xh = ws, *Yh = ws + (size_t)B * C_in * M;
-    hipLaunchKernelGGL((k_fwd2d<N, K>), dim3((unsigned)(B * C_in)), dim3(256), 0, s, x, Xh);
+    hipLaunchKernelGGL((k_fwd2d<N, K>), dim3((unsigned)(B * C_in)), dim3(256), 0, s, x, Xh, C_in);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int mblocks = (M + 255) / 256;
     const float scale = 1.0f / ((float)N * (float)N);
-    hipLaunchKernelGGL(k_cgemm_modes, dim3((unsigned)(B * mblocks), (unsigned)((C_out + 31) / 32)), dim3(256), 0, s,
-                       (const c64 *)Xh, W, Yh, C_in, C_out, M, mblocks, scale);
+    // about two workgroups per CU, each walking several mode tiles
+    const long long tiles = B * (M / 128);
+    const int tpw = tiles >= 1024 ? (int)(tiles / 512 > 16 ? 16 : tiles / 512) : 1;
+    hipLaunchKernelGGL(k_cgemm_modes, dim3((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64)),
+                       dim3(256), 0, s, (const c64 *)Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_inv2d<N, K>), dim3((unsigned)(B * C_out)), dim3(256), 0, s, (const c64 *)Yh, y);
+    hipLaunchKernelGGL((k_inv2d<N, K>), dim3((unsigned)(B * C_out)), dim3(256), 0, s, (const c64 *)Yh, y, C_out);
     return hipGetLastError();
 }
 

@@ -3,6 +3,8 @@
 //
 //   k_fwd2d   one workgroup per input image x[b, c]: truncated, output-pruned 2-D forward transform
 //             -> Xh[b, c, k1, k2], k1, k2 < K                           (reads N*N, writes K*K)
+//             stored mode-tile major, [b][m / 128][c][m % 128] with m = k1 K + k2, so that the CGEMM streams
+//             one contiguous [C, 128] block per workgroup
 //   k_cgemm_modes   Yh[b, o, m] = sum_c Xh[b, c, m] * W[c, o] / N^2 over the K*K retained modes; one W for
 //             all modes (Sec. 3.1), FP32 MFMA
 //   k_inv2d   one workgroup per output image: zero-padded, input-pruned 2-D inverse -> y[b, o]
@@ -28,13 +30,14 @@
 
 namespace tfno {
 
-template <int N, int K>
+// RP16: 16-row passes with two tile buffers (one barrier per pass) instead of 32-row passes with one buffer
+template <int N, int K, bool RP16>
 struct Cfg2d {
     static constexpr int NT = 256;
     static constexpr int LPR = N / 16;                          // lanes per row
-    static constexpr int RPS = (NT / LPR) < 32 ? NT / LPR : 32; // rows per sweep of the workgroup
+    static constexpr int RP = RP16 ? 16 : 32;                   // rows per pass
+    static constexpr int RPS = (NT / LPR) < RP ? NT / LPR : RP; // rows per sweep of the workgroup
     static constexpr int ACTIVE = RPS * LPR;                    // threads that take part in the row stage
-    static constexpr int RP = 32;                               // rows per pass
     static constexpr int S = N / RP;                            // passes
     static constexpr int SWEEPS = RP / RPS;
     static constexpr int NSWEEP = S * SWEEPS;
@@ -42,13 +45,14 @@ struct Cfg2d {
     static constexpr int CPL = 16 / LPR;                        // columns k_lo per lane after the transpose
     static constexpr int GS = N + (LPR < 16 ? LPR : 0);         // patch stride between the rows of a sweep
     static constexpr int TS = K + 4;                            // tile row stride (== 4 mod 16)
-    static constexpr int MREP = (K + 31) / 32;                  // k1 = k' + 32 m
-    static constexpr int NACC = 8 * MREP;
-    static constexpr size_t LDS_BYTES = sizeof(c64) * ((size_t)RPS * GS + (size_t)RP * TS + 2 * N);
+    static constexpr int RPL = RP / 4;                          // tile rows per lane in the column stage
+    static constexpr int MREP = (K + RP - 1) / RP;              // k1 = k' + RP m
+    static constexpr int NACC = RPL * MREP;
+    static constexpr int NBUF = RP == 16 ? 2 : 1;               // tile buffers (2: one barrier per pass)
+    static constexpr size_t LDS_BYTES = sizeof(c64) * ((size_t)RPS * GS + (size_t)NBUF * RP * TS + 2 * N);
     static_assert(N == 64 || N == 128 || N == 256, "N in {64, 128, 256}");
     static_assert(K == 16 || K == 32 || K == 64, "K in {16, 32, 64}");
     static_assert(K <= N && KH <= LPR && LPR % KH == 0, "K must divide N");
-    static_assert(NSWEEP % 2 == 0, "the sweep loop is unrolled by two");
     static_assert(LDS_BYTES <= 64 * 1024, "static LDS limit");
 };
 
@@ -81,19 +85,19 @@ __device__ __forceinline__ c64 quad_dft4_inv(c64 g, int q4)
 
 struct Lds2d {
     c64 *scr;    // [RPS][GS]   transpose patches, one per row of a sweep
-    c64 *tile;   // [32][TS]    truncated rows of one pass
+    c64 *tile;   // [NBUF][RP][TS]  truncated rows of one pass
     c64 *tw;     // [16][LPR]   w_N^(p k_lo)
     c64 *twn;    // [N]         w_N^t
 };
 
-template <int N, int K>
+template <int N, int K, bool RP16>
 __device__ __forceinline__ Lds2d lds_setup(unsigned char *raw, int tid)
 {
-    using C = Cfg2d<N, K>;
+    using C = Cfg2d<N, K, RP16>;
     Lds2d l;
     l.scr = reinterpret_cast<c64 *>(raw);
     l.tile = l.scr + C::RPS * C::GS;
-    l.tw = l.tile + C::RP * C::TS;
+    l.tw = l.tile + C::NBUF * C::RP * C::TS;
     l.twn = l.tw + N;
     for (int i = tid; i < N; i += C::NT) {
         l.tw[i] = cis2pi(-(float)((i / C::LPR) * (i % C::LPR)), (float)N);
@@ -103,16 +107,22 @@ __device__ __forceinline__ Lds2d lds_setup(unsigned char *raw, int tid)
 }
 
 // ------------------------------------------------------------------------------------------------ forward
-template <int N, int K>
-__global__ void __launch_bounds__(256)
-k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh)
+// element offset of (channel c, mode m) of batch element b in a mode-tile-major spectrum buffer
+__device__ __forceinline__ long long spec_index(long long b, int c, int C, int m, int M)
 {
-    using C = Cfg2d<N, K>;
+    return ((b * (M / 128) + m / 128) * C + c) * 128 + m % 128;
+}
+
+template <int N, int K>
+__global__ void __launch_bounds__(256, 3)
+k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
+{
+    using C = Cfg2d<N, K, N == 256>;
     constexpr int LPR = C::LPR, RPS = C::RPS, S = C::S, SWEEPS = C::SWEEPS, KH = C::KH, CPL = C::CPL;
-    constexpr int GS = C::GS, TS = C::TS, MREP = C::MREP;
+    constexpr int GS = C::GS, TS = C::TS, MREP = C::MREP, RP = C::RP, RPL = C::RPL, NBUF = C::NBUF;
     __shared__ __align__(16) unsigned char raw[C::LDS_BYTES];
     const int tid = threadIdx.x;
-    const Lds2d L = lds_setup<N, K>(raw, tid);
+    const Lds2d L = lds_setup<N, K, C::RP == 16>(raw, tid);
 
     const c64 *__restrict__ img = x + (long long)blockIdx.x * N * N;
     // row-stage identity
@@ -127,19 +137,48 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh)
 #pragma unroll
     for (int i = 0; i < C::NACC; ++i) acc[i] = make_float2(0.f, 0.f);
 
+    // Passes may run in any order (their contributions are summed).  The rows of one pass are N*S*8 bytes apart
+    // in memory, which maps them to a fraction of the L2 channels; workgroups that share an XCD (every 8th
+    // workgroup id) therefore start at different passes so that together they use all channels.
+    const int r_rot = (int)(blockIdx.x >> 3);
     auto load_rows = [&](c64 *v, int sweep) __attribute__((always_inline)) {
-        const int r = sweep / SWEEPS, s = (sweep % SWEEPS) * RPS + g;
+        const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
         const c64 *src = img + (long long)(r + S * s) * N + p;
         if (row_on) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) v[j] = src[LPR * j];
         }
     };
-    auto row_stage = [&](const c64 *v, int sweep) __attribute__((always_inline)) {
+    // Row transforms of the sweep held in v.  The first butterfly level consumes v, so the loads of the next
+    // sweep are issued right after it and stay in flight while the rest of this sweep is computed.
+    auto row_stage = [&](c64 *v, int sweep) __attribute__((always_inline)) {
         if (!row_on) return;
         const int s = (sweep % SWEEPS) * RPS + g;
+        c64 *tile = L.tile + ((sweep / SWEEPS) % NBUF) * (RP * TS);
         c64 z[16];
-        RegFFT<16, -1, 1>::run(v, z);
+#ifdef TFNO2D_DBG_NO_ROW
+        {   // timing experiment: keep the loads, drop the transform
+            c64 t = make_float2(0.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) t = cadd(t, v[j]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (sweep + 1 < C::NSWEEP) load_rows(v, sweep + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            tile[s * TS + p] = t;
+            return;
+        }
+#endif
+        {
+            c64 ea[8], eb[8], za[8], zo[8];
+            dif_first_level<16, -1>(v, ea, eb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (sweep + 1 < C::NSWEEP) load_rows(v, sweep + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            RegFFT<8, -1, 1>::run(ea, za);
+            RegFFT<8, -1, 1>::run(eb, zo);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { z[2 * k] = za[k]; z[2 * k + 1] = zo[k]; }
+        }
         wave_sync();                                        // the previous sweep's patch reads are done
 #pragma unroll
         for (int kl = 0; kl < 16; ++kl) {
@@ -156,68 +195,70 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh)
                 return scr[kl * LPR + (pp ^ p)];
             }, xo);
 #pragma unroll
-            for (int kh = 0; kh < KH; ++kh) L.tile[s * TS + kl + 16 * kh] = xo[kh];
+            for (int kh = 0; kh < KH; ++kh) tile[s * TS + kl + 16 * kh] = xo[kh];
         }
     };
-    auto col_stage = [&](int r) __attribute__((always_inline)) {
+    // RP-point transform of the tile columns of pass `i` (rows r + S s), accumulated with the pass twiddle
+    auto col_stage = [&](int i) __attribute__((always_inline)) {
         if (!col_on) return;
-        c64 u[8], G[8];
+#ifdef TFNO2D_DBG_NO_COL
+        return;
+#endif
+        const int r = (i + r_rot) & (S - 1);
+        const c64 *tile = L.tile + (i % NBUF) * (RP * TS);
+        c64 u[RPL], G[RPL];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) u[j] = L.tile[(q4 + 4 * j) * TS + k2];
-        RegFFT<8, -1, 1>::run(u, G);
+        for (int j = 0; j < RPL; ++j) u[j] = tile[(q4 + 4 * j) * TS + k2];
+        RegFFT<RPL, -1, 1>::run(u, G);
 #pragma unroll
-        for (int ka = 0; ka < 8; ++ka) {
-            c64 t = ka == 0 ? G[0] : cmul(G[ka], L.twn[(q4 * ka) * (N / 32)]);
-            t = quad_dft4_fwd(t, q4);                       // F_r[ka + 8 kb]
+        for (int ka = 0; ka < RPL; ++ka) {
+            c64 t = ka == 0 ? G[0] : cmul(G[ka], L.twn[(q4 * ka) * (N / RP)]);
+            t = quad_dft4_fwd(t, q4);                       // F_r[ka + RPL kb]
 #pragma unroll
             for (int m = 0; m < MREP; ++m) {
-                const int k1 = ka + 8 * kb + 32 * m;
-                acc[m * 8 + ka] = cmac(acc[m * 8 + ka], t, L.twn[(r * k1) & (N - 1)]);
+                const int k1 = ka + RPL * kb + RP * m;
+                acc[m * RPL + ka] = cmac(acc[m * RPL + ka], t, L.twn[(r * k1) & (N - 1)]);
             }
         }
     };
 
-    c64 va[16], vb[16];
-    load_rows(va, 0);
+    c64 v[16];
+    load_rows(v, 0);
     __syncthreads();                                        // twiddle tables are ready
-    for (int sweep = 0; sweep < C::NSWEEP; sweep += 2) {
-        load_rows(vb, sweep + 1);
-        row_stage(va, sweep);
-        if constexpr (SWEEPS == 1) {
-            __syncthreads();
-            col_stage(sweep);
-            __syncthreads();
-        }
-        if (sweep + 2 < C::NSWEEP) load_rows(va, sweep + 2);
-        row_stage(vb, sweep + 1);
+    for (int i = 0; i < S; ++i) {
+#pragma unroll
+        for (int w = 0; w < SWEEPS; ++w) row_stage(v, i * SWEEPS + w);
+#ifndef TFNO2D_DBG_NO_BAR
         __syncthreads();
-        col_stage((sweep + 1) / SWEEPS);
-        __syncthreads();
+#endif
+        col_stage(i);
+        if constexpr (NBUF == 1) __syncthreads();           // with two tile buffers the next pass writes the other one
     }
 
     if (col_on) {
-        c64 *dst = Xh + (long long)blockIdx.x * K * K + k2;
+        const long long b = blockIdx.x / C_in;
+        const int c = (int)(blockIdx.x % C_in);
 #pragma unroll
         for (int m = 0; m < MREP; ++m)
 #pragma unroll
-            for (int ka = 0; ka < 8; ++ka) {
-                const int k1 = ka + 8 * kb + 32 * m;
-                if (k1 < K) dst[k1 * K] = acc[m * 8 + ka];
+            for (int ka = 0; ka < RPL; ++ka) {
+                const int k1 = ka + RPL * kb + RP * m;
+                if (k1 < K) Xh[spec_index(b, c, C_in, k1 * K + k2, K * K)] = acc[m * RPL + ka];
             }
     }
 }
 
 // ------------------------------------------------------------------------------------------------ inverse
 template <int N, int K>
-__global__ void __launch_bounds__(256)
-k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y)
+__global__ void __launch_bounds__(256, 3)
+k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
 {
-    using C = Cfg2d<N, K>;
+    using C = Cfg2d<N, K, false>;
     constexpr int LPR = C::LPR, RPS = C::RPS, S = C::S, SWEEPS = C::SWEEPS, KH = C::KH, CPL = C::CPL;
-    constexpr int GS = C::GS, TS = C::TS, MREP = C::MREP;
+    constexpr int GS = C::GS, TS = C::TS, MREP = C::MREP, RP = C::RP, RPL = C::RPL, NBUF = C::NBUF;
     __shared__ __align__(16) unsigned char raw[C::LDS_BYTES];
     const int tid = threadIdx.x;
-    const Lds2d L = lds_setup<N, K>(raw, tid);
+    const Lds2d L = lds_setup<N, K, C::RP == 16>(raw, tid);
 
     c64 *__restrict__ img = y + (long long)blockIdx.x * N * N;
     const bool row_on = tid < C::ACTIVE;
@@ -229,52 +270,69 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y)
     // the retained spectrum of this image, K*K/256 (or fewer) bins per thread, for all passes
     c64 Y[C::NACC];
     {
-        const c64 *src = Yh + (long long)blockIdx.x * K * K + (col_on ? k2 : 0);
+        const long long b = blockIdx.x / C_out;
+        const int o = (int)(blockIdx.x % C_out);
 #pragma unroll
         for (int m = 0; m < MREP; ++m)
 #pragma unroll
-            for (int ka = 0; ka < 8; ++ka) {
-                const int k1 = ka + 8 * kb + 32 * m;
+            for (int ka = 0; ka < RPL; ++ka) {
+                const int k1 = ka + RPL * kb + RP * m;
                 const bool ok = col_on && k1 < K;
-                c64 v = src[ok ? k1 * K : 0];
-                Y[m * 8 + ka] = ok ? v : make_float2(0.f, 0.f);
+                c64 v = Yh[spec_index(b, o, C_out, ok ? k1 * K + k2 : 0, K * K)];
+                Y[m * RPL + ka] = ok ? v : make_float2(0.f, 0.f);
             }
     }
 
-    auto col_stage = [&](int r) __attribute__((always_inline)) {
+    const int r_rot = (int)(blockIdx.x >> 3);               // pass order rotated as in the forward kernel
+    // twiddled RP-point inverse column transform of pass `i` (rows r + S s) into the tile
+    auto col_stage = [&](int i) __attribute__((always_inline)) {
         if (!col_on) return;
-        c64 G[8], f[8];
+#ifdef TFNO2D_DBG_NO_COL
+        return;
+#endif
+        const int r = (i + r_rot) & (S - 1);
+        c64 *tile = L.tile + (i % NBUF) * (RP * TS);
+        c64 G[RPL], f[RPL];
 #pragma unroll
-        for (int ka = 0; ka < 8; ++ka) {
+        for (int ka = 0; ka < RPL; ++ka) {
             c64 t = make_float2(0.f, 0.f);
 #pragma unroll
             for (int m = 0; m < MREP; ++m) {
-                const int k1 = ka + 8 * kb + 32 * m;
+                const int k1 = ka + RPL * kb + RP * m;
                 const c64 w = L.twn[(r * k1) & (N - 1)];
-                t = cmac(t, Y[m * 8 + ka], make_float2(w.x, -w.y));
+                t = cmac(t, Y[m * RPL + ka], make_float2(w.x, -w.y));
             }
             t = quad_dft4_inv(t, q4);
             if (ka != 0) {
-                const c64 w = L.twn[(q4 * ka) * (N / 32)];
+                const c64 w = L.twn[(q4 * ka) * (N / RP)];
                 t = cmul(t, make_float2(w.x, -w.y));
             }
             G[ka] = t;
         }
-        RegFFT<8, +1, 1>::run(G, f);
+        RegFFT<RPL, +1, 1>::run(G, f);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) L.tile[(q4 + 4 * j) * TS + k2] = f[j];
+        for (int j = 0; j < RPL; ++j) tile[(q4 + 4 * j) * TS + k2] = f[j];
     };
     // zero-padded inverse row transforms of sweep `sweep`, results left in out[]
     auto row_stage = [&](c64 *out, int sweep) __attribute__((always_inline)) {
         if (!row_on) return;
         const int s = (sweep % SWEEPS) * RPS + g;
+        const c64 *tile = L.tile + ((sweep / SWEEPS) % NBUF) * (RP * TS);
+#ifdef TFNO2D_DBG_NO_ROW
+        {   // timing experiment: keep the stores, drop the transform
+            const c64 t = tile[s * TS + p];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) out[j] = make_float2(t.x + j, t.y);
+            return;
+        }
+#endif
         wave_sync();                                        // the previous sweep's patch reads are done
 #pragma unroll
         for (int i = 0; i < CPL; ++i) {
             const int kl = p + LPR * i;
             c64 yin[KH];
 #pragma unroll
-            for (int kh = 0; kh < KH; ++kh) yin[kh] = L.tile[s * TS + kl + 16 * kh];
+            for (int kh = 0; kh < KH; ++kh) yin[kh] = tile[s * TS + kl + 16 * kh];
             dft_prune_in<LPR, KH, +1>(yin, [&](auto ppc, c64 val) __attribute__((always_inline)) {
                 constexpr int pp = decltype(ppc)::value;
                 scr[kl * LPR + (pp ^ p)] = val;
@@ -295,79 +353,113 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y)
     };
     auto store_rows = [&](const c64 *out, int sweep) __attribute__((always_inline)) {
         if (!row_on) return;
-        const int r = sweep / SWEEPS, s = (sweep % SWEEPS) * RPS + g;
+        const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
         c64 *dst = img + (long long)(r + S * s) * N + p;
 #pragma unroll
         for (int j = 0; j < 16; ++j) dst[LPR * j] = out[j];
     };
 
     __syncthreads();                                        // twiddle tables are ready
-    for (int r = 0; r < S; ++r) {
-        col_stage(r);
+    for (int i = 0; i < S; ++i) {
+        col_stage(i);
+#ifndef TFNO2D_DBG_NO_BAR
         __syncthreads();
+#endif
 #pragma unroll
         for (int w = 0; w < SWEEPS; ++w) {
             c64 out[16];
-            row_stage(out, r * SWEEPS + w);
-            store_rows(out, r * SWEEPS + w);
+            row_stage(out, i * SWEEPS + w);
+            store_rows(out, i * SWEEPS + w);
         }
-        __syncthreads();
+        if constexpr (NBUF == 1) __syncthreads();           // with two tile buffers the next pass writes the other one
     }
 }
 
 // ------------------------------------------------------------------------------------------------ CGEMM
-// Yh[b, o, m] = sum_c Xh[b, c, m] * (scale * W[c, o]),  m < M (M a multiple of 64).
-// One wave per (b, 32 outputs, 64 modes); v_mfma_f32_32x32x2_f32 with the two k-slots of an instruction
-// carrying (re, im) of one channel: real part with A = (W.re, -W.im), imaginary part with A = (W.im, W.re).
-__global__ void __launch_bounds__(256)
+// Yh[b, o, m] = sum_c Xh[b, c, m] * (scale * W[c, o]),  m < M (M a multiple of 128), both spectra mode-tile
+// major, so a tile of 128 modes of one batch element is a contiguous [C, 128] block.  A workgroup walks
+// `tiles_per_wg` consecutive tiles for 64 outputs, one wave per 32 modes: every spectrum element is read once
+// per 64 outputs, the stores of one tile drain under the MFMAs of the next, and the spectrum chunks are
+// double buffered in registers across tile boundaries.  W (scaled) is staged in LDS 64 channels at a time.
+// v_mfma_f32_32x32x2_f32 with the two k-slots of an instruction carrying (re, im) of one channel: real part
+// with A = (W.re, -W.im), imaginary part with A = (W.im, W.re).
+__global__ void __launch_bounds__(256, 2)
 k_cgemm_modes(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh,
-              int C_in, int C_out, int M, int mblocks, float scale)
+              int C_in, int C_out, float scale, long long num_tiles, int tiles_per_wg)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long b = blockIdx.x / mblocks;
-    const int m0 = ((int)(blockIdx.x % mblocks) * 4 + wave) * 64;
-    if (m0 >= M) return;
+    constexpr int U = 8;                                    // channels per register chunk
+    __shared__ c64 Wl[64 * 64];                             // [channel in block][output in slab pair]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31;
     const bool hi = lane >= 32;
-    const int o0 = blockIdx.y * 32, o_lane = o0 + col;
-    const bool o_ok = o_lane < C_out;
-    const c64 *__restrict__ Xb = Xh + b * C_in * (long long)M + m0 + col;
-    const c64 *__restrict__ Wl = W + (o_ok ? o_lane : 0);
+    const int o0 = blockIdx.y * 64;
+    const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
+    const int ntile = (int)(num_tiles - tile0 < tiles_per_wg ? num_tiles - tile0 : tiles_per_wg);
+    const int c_pad = (C_in + 2 * U - 1) / (2 * U) * (2 * U);
+    const bool one_block = C_in <= 64;
 
     floatx16 acc_re[2], acc_im[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { acc_re[t][r] = 0.f; acc_im[t][r] = 0.f; }
 
-    auto step = [&](int c) __attribute__((always_inline)) {
-        c64 wv = Wl[(long long)c * C_out];
-        if (!o_ok) wv = make_float2(0.f, 0.f);
-        const float a_re = (hi ? -wv.y : wv.x) * scale, a_im = (hi ? wv.x : wv.y) * scale;
+    // position of the next chunk to load: (tile, channel); channels past C_in are read from a valid address
+    // and meet zero weights, tiles past the end are not loaded
+    int nt = 0, nc = 0;
+    auto load_next = [&](c64 *xv) __attribute__((always_inline)) {
+        if (nt < ntile) {
+            const c64 *src = Xh + (tile0 + nt) * C_in * 128 + 32 * wave + col;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const c64 xv = Xb[(long long)c * M + 32 * t];
-            const float bx = hi ? xv.y : xv.x;
-            acc_re[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re, bx, acc_re[t], 0, 0, 0);
-            acc_im[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im, bx, acc_im[t], 0, 0, 0);
+            for (int u = 0; u < U; ++u) xv[u] = src[(nc + u < C_in ? nc + u : 0) * 128];
+        }
+        nc += U;
+        if (nc >= c_pad) { nc = 0; ++nt; }
+    };
+    auto mac_chunk = [&](const c64 *xv, int cl) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const c64 w0 = Wl[(cl + u) * 64 + col], w1 = Wl[(cl + u) * 64 + 32 + col];
+            const float bx = hi ? xv[u].y : xv[u].x;
+            acc_re[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(hi ? -w0.y : w0.x, bx, acc_re[0], 0, 0, 0);
+            acc_im[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(hi ? w0.x : w0.y, bx, acc_im[0], 0, 0, 0);
+            acc_re[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(hi ? -w1.y : w1.x, bx, acc_re[1], 0, 0, 0);
+            acc_im[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(hi ? w1.x : w1.y, bx, acc_im[1], 0, 0, 0);
         }
     };
-    int c = 0;
-    for (; c + 4 <= C_in; c += 4) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) step(c + u);
-    }
-    for (; c < C_in; ++c) step(c);
 
-    c64 *__restrict__ Yb = Yh + b * C_out * (long long)M + m0 + col;
+    c64 xa[U], xb[U];
+    load_next(xa);
+    for (int t = 0; t < ntile; ++t) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int o = o0 + 8 * (r / 4) + 4 * (hi ? 1 : 0) + (r % 4);
-        if (o < C_out) {
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-                Yb[(long long)o * M + 32 * t] = make_float2(acc_re[t][r], acc_im[t][r]);
+            for (int r = 0; r < 16; ++r) { acc_re[i][r] = 0.f; acc_im[i][r] = 0.f; }
+        for (int cb = 0; cb < C_in; cb += 64) {
+            if (!one_block || t == 0) {
+                __syncthreads();                            // the previous block of W has been consumed
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int idx = i * 256 + tid, c = cb + idx / 64, o = o0 + idx % 64;
+                    const bool ok = c < C_in && o < C_out;
+                    const c64 w = W[ok ? (long long)c * C_out + o : 0];
+                    Wl[idx] = ok ? make_float2(w.x * scale, w.y * scale) : make_float2(0.f, 0.f);
+                }
+                __syncthreads();
+            }
+            const int left = C_in - cb, lim = left >= 64 ? 64 : (left + 2 * U - 1) / (2 * U) * (2 * U);
+#pragma unroll 1
+            for (int cl = 0; cl < lim; cl += 2 * U) {
+                load_next(xb);
+                mac_chunk(xa, cl);
+                load_next(xa);
+                mac_chunk(xb, cl + U);
+            }
         }
+        c64 *__restrict__ Yb = Yh + (tile0 + t) * C_out * 128 + 32 * wave + col;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = o0 + 32 * i + 8 * (r / 4) + 4 * (hi ? 1 : 0) + (r % 4);
+                if (o < C_out) Yb[o * 128] = make_float2(acc_re[i][r], acc_im[i][r]);
+            }
     }
 }
 
