@@ -151,7 +151,8 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
     };
     // Row transforms of the sweep held in v.  The first butterfly level consumes v, so the loads of the next
     // sweep are issued right after it and stay in flight while the rest of this sweep is computed.
-    auto row_stage = [&](c64 *v, int sweep) __attribute__((always_inline)) {
+    auto row_stage = [&](c64 *v, int sweep, auto refill) __attribute__((always_inline)) {
+        constexpr bool REFILL = decltype(refill)::value;    // false only for the last sweep of the image
         if (!row_on) return;
         const int s = (sweep % SWEEPS) * RPS + g;
         c64 *tile = L.tile + ((sweep / SWEEPS) % NBUF) * (RP * TS);
@@ -162,7 +163,7 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
 #pragma unroll
             for (int j = 0; j < 16; ++j) t = cadd(t, v[j]);
             __builtin_amdgcn_sched_barrier(0);
-            if (sweep + 1 < C::NSWEEP) load_rows(v, sweep + 1);
+            if constexpr (REFILL) load_rows(v, sweep + 1);
             __builtin_amdgcn_sched_barrier(0);
             tile[s * TS + p] = t;
             return;
@@ -172,7 +173,7 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
             c64 ea[8], eb[8], za[8], zo[8];
             dif_first_level<16, -1>(v, ea, eb);
             __builtin_amdgcn_sched_barrier(0);
-            if (sweep + 1 < C::NSWEEP) load_rows(v, sweep + 1);
+            if constexpr (REFILL) load_rows(v, sweep + 1);
             __builtin_amdgcn_sched_barrier(0);
             RegFFT<8, -1, 1>::run(ea, za);
             RegFFT<8, -1, 1>::run(eb, zo);
@@ -225,15 +226,23 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
     c64 v[16];
     load_rows(v, 0);
     __syncthreads();                                        // twiddle tables are ready
-    for (int i = 0; i < S; ++i) {
+    // the last pass is peeled off so that every other sweep refills v unconditionally
+    for (int i = 0; i < S - 1; ++i) {
 #pragma unroll
-        for (int w = 0; w < SWEEPS; ++w) row_stage(v, i * SWEEPS + w);
+        for (int w = 0; w < SWEEPS; ++w) row_stage(v, i * SWEEPS + w, std::true_type{});
 #ifndef TFNO2D_DBG_NO_BAR
         __syncthreads();
 #endif
         col_stage(i);
         if constexpr (NBUF == 1) __syncthreads();           // with two tile buffers the next pass writes the other one
     }
+#pragma unroll
+    for (int w = 0; w < SWEEPS; ++w) {
+        if (w + 1 < SWEEPS) row_stage(v, (S - 1) * SWEEPS + w, std::true_type{});
+        else row_stage(v, (S - 1) * SWEEPS + w, std::false_type{});
+    }
+    __syncthreads();
+    col_stage(S - 1);
 
     if (col_on) {
         const long long b = blockIdx.x / C_in;
