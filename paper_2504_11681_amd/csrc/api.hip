@@ -136,7 +136,7 @@ bool fused1d_supported(int N, int K)
 
 // TFNO_CONTRACTION=f32 forces the kernels whose channel contraction uses FP32 MFMA; the default lets
 // shapes that have a wave-specialised kernel use the exact-split BF16x3 contraction.
-static bool contraction_forced_f32()
+bool contraction_forced_f32()
 {
     static const bool forced = [] {
         const char *e = getenv("TFNO_CONTRACTION");

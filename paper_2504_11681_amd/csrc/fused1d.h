@@ -24,6 +24,9 @@ bool fused1d_supported(int N, int K);
 // Enqueues the fused kernel; hipErrorInvalidValue when (N, K) is unsupported.
 hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long batch_rows, hipStream_t s);
 
+// True when the environment asks for FP32-MFMA contractions only (TFNO_CONTRACTION=f32).
+bool contraction_forced_f32();
+
 // Wave-specialised variant (BF16x3 split contraction on the matrix pipe beside the VALU transforms).
 bool fused1d_ws_supported(int N, int K);
 hipError_t fused1d_ws_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);

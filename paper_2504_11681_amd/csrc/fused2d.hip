@@ -1,6 +1,7 @@
 // Instantiations and launcher of the 2-D kernels.
 #include "fused2d_kernel.h"
 #include "fused2d.h"
+#include "fused1d.h"
 
 namespace tfno {
 
@@ -27,8 +28,11 @@ static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int
     // about two workgroups per CU, each walking several mode tiles
     const long long tiles = B * (M / 128);
     const int tpw = tiles >= 1024 ? (int)(tiles / 512 > 16 ? 16 : tiles / 512) : 1;
-    hipLaunchKernelGGL(k_cgemm_modes, dim3((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64)),
-                       dim3(256), 0, s, (const c64 *)Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
+    const dim3 ggrid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64));
+    if (contraction_forced_f32())
+        hipLaunchKernelGGL(k_cgemm_modes_f32, ggrid, dim3(256), 0, s, (const c64 *)Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
+    else
+        hipLaunchKernelGGL(k_cgemm_modes, ggrid, dim3(256), 0, s, (const c64 *)Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL((k_inv2d<N, K>), dim3((unsigned)(B * C_out)), dim3(256), 0, s, (const c64 *)Yh, y, C_out);
     return hipGetLastError();

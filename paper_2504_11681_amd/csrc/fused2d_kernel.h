@@ -27,6 +27,7 @@
 #include "common.h"
 #include "fft_regs.h"
 #include "fused1d_kernel.h"   // wave_sync, floatx16
+#include "bf16x3.h"
 
 namespace tfno {
 
@@ -393,8 +394,8 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
 // v_mfma_f32_32x32x2_f32 with the two k-slots of an instruction carrying (re, im) of one channel: real part
 // with A = (W.re, -W.im), imaginary part with A = (W.im, W.re).
 __global__ void __launch_bounds__(256, 2)
-k_cgemm_modes(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh,
-              int C_in, int C_out, float scale, long long num_tiles, int tiles_per_wg)
+k_cgemm_modes_f32(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh,
+                  int C_in, int C_out, float scale, long long num_tiles, int tiles_per_wg)
 {
     constexpr int U = 8;                                    // channels per register chunk
     __shared__ c64 Wl[64 * 64];                             // [channel in block][output in slab pair]
@@ -467,6 +468,121 @@ k_cgemm_modes(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__rest
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int o = o0 + 32 * i + 8 * (r / 4) + 4 * (hi ? 1 : 0) + (r % 4);
+                if (o < C_out) Yb[o * 128] = make_float2(acc_re[i][r], acc_im[i][r]);
+            }
+    }
+}
+
+// The same contraction on the BF16 matrix pipe with every FP32 operand split exactly into three BF16 terms
+// and the six largest cross products accumulated in FP32 (the scheme of the wave-specialised 1-D kernel; the
+// dropped products are below 2^-23 |a||b|).  v_mfma_f32_32x32x16_bf16: the 16 k-slots of an instruction are
+// 8 channels x (re, im); lanes 0-31 carry channels 0-3 of the step, lanes 32-63 channels 4-7, dword d of a lane
+// = (re | im << 16) of channel 4g + d.  W is staged in LDS already split, as [channel / 4][term][output][channel % 4]
+// dwords (re | im << 16), so an A operand is one 16-byte LDS read plus a sign flip (real part: (W.re, -W.im))
+// or a half-word swap (imaginary part: (W.im, W.re)).
+__global__ void __launch_bounds__(256, 2)
+k_cgemm_modes(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh,
+              int C_in, int C_out, float scale, long long num_tiles, int tiles_per_wg)
+{
+    __shared__ __align__(16) unsigned Wl[16 * 3 * 64 * 4];  // 48 KB
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int o0 = blockIdx.y * 64;
+    const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
+    const int ntile = (int)(num_tiles - tile0 < tiles_per_wg ? num_tiles - tile0 : tiles_per_wg);
+    const int c_pad = (C_in + 15) / 16 * 16;
+    const bool one_block = C_in <= 64;
+
+    floatx16 acc_re[2], acc_im[2];
+
+    // position of the next 8-channel step to load: (tile, channel); channels past C_in are read from a valid
+    // address and meet zero weights, tiles past the end are not loaded
+    int nt = 0, nc = 0;
+    auto load_next = [&](c64 *xv) __attribute__((always_inline)) {
+        if (nt < ntile) {
+            const c64 *src = Xh + (tile0 + nt) * C_in * 128 + 32 * wave + col;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int c = nc + 4 * g + d;
+                xv[d] = src[(c < C_in ? c : 0) * 128];
+            }
+        }
+        nc += 8;
+        if (nc >= c_pad) { nc = 0; ++nt; }
+    };
+    // one step: channels cl .. cl+7 of the staged block
+    auto mac_step = [&](const c64 *xv, int cl) __attribute__((always_inline)) {
+        uintx4 b[3];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const Split3 re = split3(xv[d].x), im = split3(xv[d].y);
+            b[0][d] = pack_bf16(re.t0, im.t0);
+            b[1][d] = pack_bf16(re.t1, im.t1);
+            b[2][d] = pack_bf16(re.t2, im.t2);
+        }
+        const unsigned *wsrc = Wl + (((cl >> 2) + g) * 3 * 64 + col) * 4;
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            uintx4 a_re[3], a_im[3];
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                const uintx4 w = *reinterpret_cast<const uintx4 *>(wsrc + (t * 64 + 32 * sl) * 4);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    a_re[t][d] = w[d] ^ 0x80000000u;
+                    a_im[t][d] = __builtin_amdgcn_alignbit(w[d], w[d], 16);
+                }
+            }
+            // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
+            constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+            for (int k = 0; k < 6; ++k) {
+                const bf16x8 bb = __builtin_bit_cast(bf16x8, b[SB[k]]);
+                acc_re[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb, acc_re[sl], 0, 0, 0);
+                acc_im[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb, acc_im[sl], 0, 0, 0);
+            }
+        }
+    };
+
+    c64 xa[4], xb[4];
+    load_next(xa);
+    for (int t = 0; t < ntile; ++t) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc_re[i][r] = 0.f; acc_im[i][r] = 0.f; }
+        for (int cb = 0; cb < C_in; cb += 64) {
+            if (!one_block || t == 0) {
+                __syncthreads();                            // the previous block of W has been consumed
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int idx = i * 256 + tid, cl = idx / 64, ol = idx % 64;
+                    const int c = cb + cl, o = o0 + ol;
+                    const bool ok = c < C_in && o < C_out;
+                    const c64 w = W[ok ? (long long)c * C_out + o : 0];
+                    const Split3 re = split3(ok ? w.x * scale : 0.f), im = split3(ok ? w.y * scale : 0.f);
+                    unsigned *dst = Wl + (((cl >> 2) * 3) * 64 + ol) * 4 + (cl & 3);
+                    dst[0 * 64 * 4] = pack_bf16(re.t0, im.t0);
+                    dst[1 * 64 * 4] = pack_bf16(re.t1, im.t1);
+                    dst[2 * 64 * 4] = pack_bf16(re.t2, im.t2);
+                }
+                __syncthreads();
+            }
+            const int left = C_in - cb, lim = left >= 64 ? 64 : (left + 15) / 16 * 16;
+#pragma unroll 1
+            for (int cl = 0; cl < lim; cl += 16) {
+                load_next(xb);
+                mac_step(xa, cl);
+                load_next(xa);
+                mac_step(xb, cl + 8);
+            }
+        }
+        c64 *__restrict__ Yb = Yh + (tile0 + t) * C_out * 128 + 32 * wave + col;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = o0 + 32 * i + 8 * (r / 4) + 4 * g + (r % 4);
                 if (o < C_out) Yb[o * 128] = make_float2(acc_re[i][r], acc_im[i][r]);
             }
     }
