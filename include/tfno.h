@@ -68,12 +68,18 @@ tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y,
                                  int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
- * Fused 2-D spectral convolution (Sec. 3.2/3.3, 2-D pipeline): a truncated
- * forward FFT along the first spatial axis, the fused 1-D kernel along the last
- * axis on the K retained rows, and a zero-padded inverse FFT along the first
- * axis.  Three launches; the two [B, C, K, N] intermediates live in the workspace
- * set with tfno_set_workspace (tfno_workspace_bytes(2, 0, ...) bytes).
- * Shape support as for the 1-D fused entry point.
+ * Fused 2-D spectral convolution (Sec. 3.2 / 3.3: separable transform, truncation and zero padding built
+ * into both axes, pruned butterflies):
+ *
+ *   y[b,o] = iFFT2( pad_NxN( sum_c trunc_KxK( FFT2(x[b,c]) ) * W[c,o] ) )
+ *
+ * N in {64,128,256}, K in {16,32,64}, K <= N: three launches -- a per-image truncated forward transform, the
+ * CGEMM over the K*K retained modes, a per-image zero-padded inverse -- whose only intermediates are the
+ * truncated spectra (tfno_workspace_bytes(2, 0, ...) = 8 B K^2 (C_in + C_out) bytes of workspace).
+ * Other shapes that the 1-D fused kernel supports run the paper's 2-D pipeline instead: truncated forward
+ * FFT along the first axis, the fused 1-D kernel along the last axis on the K retained rows, zero-padded
+ * inverse along the first axis, with two [B, C, K, N] strips in the workspace.  Shapes neither path covers:
+ * TFNO_ERR_UNSUPPORTED.
  */
 tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y,
                                  int B, int C_in, int C_out, int N, int K, void *stream);

@@ -9,20 +9,22 @@
 //             all modes (Sec. 3.1), FP32 MFMA
 //   k_inv2d   one workgroup per output image: zero-padded, input-pruned 2-D inverse -> y[b, o]
 //
-// Both transforms are separable (Sec. 3.3).  With S = N/32 the pruned first-axis transform is written as
-//   X[k1] = sum_{r<S} w_N^(r k1) * F_r[k1 mod 32],   F_r = 32-point DFT of the rows n1 = r + S s, s < 32,
-// so an image is processed in S passes of 32 rows: the last-axis transform of the 32 rows (truncated to K
-// bins, Sec. 3.3) goes into a 32 x K LDS tile, the 32-point column transform of that tile is accumulated
+// Both transforms are separable (Sec. 3.3).  With RP rows per pass (16 or 32) and S = N/RP the pruned first-axis
+// transform is written as
+//   X[k1] = sum_{r<S} w_N^(r k1) * F_r[k1 mod RP],   F_r = RP-point DFT of the rows n1 = r + S s, s < RP,
+// so an image is processed in S passes of RP rows: the last-axis transform of these rows (truncated to K
+// bins, Sec. 3.3) goes into an RP x K LDS tile, the RP-point column transform of that tile is accumulated
 // into registers with the pass twiddle, and the full N x K strip never exists anywhere.  The inverse runs
-// the transposed network: spectrum in registers, per pass a twiddled 32-point inverse column transform
-// into the tile and zero-padded inverse row transforms of its 32 rows.
+// the transposed network: spectrum in registers, per pass a twiddled RP-point inverse column transform
+// into the tile and zero-padded inverse row transforms of its rows.  The passes of an image can run in any
+// order; workgroups start at different passes (see r_rot) because the rows of one pass map to few L2 channels.
 //
 // Row transform (N = 16 * LPR): LPR lanes per row, lane p holds x[p + LPR j], j < 16 (coalesced loads),
 // 16-point DFT in registers, twiddle w_N^(p k_lo), transpose through a wave-private XOR-swizzled LDS patch,
 // then the LPR-point DFT pruned to the K/16 retained outputs of each column k_lo (bins k_lo + 16 k_hi).
-// Column transform: 4 adjacent lanes per tile column, 8-point DFT in registers, 4-point DFT across the quad
+// Column transform: 4 adjacent lanes per tile column, RP/4-point DFT in registers, 4-point DFT across the quad
 // with DPP.  All LDS accesses of the handoffs hit distinct banks per 16 lanes (the counterpart of the two
-// swizzles of Sec. 4.1 / 4.2 for 8-byte accesses on wave64).
+// swizzles of Sec. 4.1 / 4.2 for 8-byte accesses on wave64; checked with an LDS microbenchmark).
 #pragma once
 #include "common.h"
 #include "fft_regs.h"
@@ -158,18 +160,6 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
         const int s = (sweep % SWEEPS) * RPS + g;
         c64 *tile = L.tile + ((sweep / SWEEPS) % NBUF) * (RP * TS);
         c64 z[16];
-#ifdef TFNO2D_DBG_NO_ROW
-        {   // timing experiment: keep the loads, drop the transform
-            c64 t = make_float2(0.f, 0.f);
-#pragma unroll
-            for (int j = 0; j < 16; ++j) t = cadd(t, v[j]);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (REFILL) load_rows(v, sweep + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            tile[s * TS + p] = t;
-            return;
-        }
-#endif
         {
             c64 ea[8], eb[8], za[8], zo[8];
             dif_first_level<16, -1>(v, ea, eb);
@@ -203,9 +193,6 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
     // RP-point transform of the tile columns of pass `i` (rows r + S s), accumulated with the pass twiddle
     auto col_stage = [&](int i) __attribute__((always_inline)) {
         if (!col_on) return;
-#ifdef TFNO2D_DBG_NO_COL
-        return;
-#endif
         const int r = (i + r_rot) & (S - 1);
         const c64 *tile = L.tile + (i % NBUF) * (RP * TS);
         c64 u[RPL], G[RPL];
@@ -231,9 +218,7 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
     for (int i = 0; i < S - 1; ++i) {
 #pragma unroll
         for (int w = 0; w < SWEEPS; ++w) row_stage(v, i * SWEEPS + w, std::true_type{});
-#ifndef TFNO2D_DBG_NO_BAR
         __syncthreads();
-#endif
         col_stage(i);
         if constexpr (NBUF == 1) __syncthreads();           // with two tile buffers the next pass writes the other one
     }
@@ -297,9 +282,6 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
     // twiddled RP-point inverse column transform of pass `i` (rows r + S s) into the tile
     auto col_stage = [&](int i) __attribute__((always_inline)) {
         if (!col_on) return;
-#ifdef TFNO2D_DBG_NO_COL
-        return;
-#endif
         const int r = (i + r_rot) & (S - 1);
         c64 *tile = L.tile + (i % NBUF) * (RP * TS);
         c64 G[RPL], f[RPL];
@@ -328,14 +310,6 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
         if (!row_on) return;
         const int s = (sweep % SWEEPS) * RPS + g;
         const c64 *tile = L.tile + ((sweep / SWEEPS) % NBUF) * (RP * TS);
-#ifdef TFNO2D_DBG_NO_ROW
-        {   // timing experiment: keep the stores, drop the transform
-            const c64 t = tile[s * TS + p];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) out[j] = make_float2(t.x + j, t.y);
-            return;
-        }
-#endif
         wave_sync();                                        // the previous sweep's patch reads are done
 #pragma unroll
         for (int i = 0; i < CPL; ++i) {
@@ -372,9 +346,7 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
     __syncthreads();                                        // twiddle tables are ready
     for (int i = 0; i < S; ++i) {
         col_stage(i);
-#ifndef TFNO2D_DBG_NO_BAR
         __syncthreads();
-#endif
 #pragma unroll
         for (int w = 0; w < SWEEPS; ++w) {
             c64 out[16];
@@ -521,25 +493,28 @@ k_cgemm_modes(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__rest
             b[2][d] = pack_bf16(re.t2, im.t2);
         }
         const unsigned *wsrc = Wl + (((cl >> 2) + g) * 3 * 64 + col) * 4;
+        uintx4 a_re[2][3], a_im[2][3];
 #pragma unroll
-        for (int sl = 0; sl < 2; ++sl) {
-            uintx4 a_re[3], a_im[3];
+        for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
             for (int t = 0; t < 3; ++t) {
                 const uintx4 w = *reinterpret_cast<const uintx4 *>(wsrc + (t * 64 + 32 * sl) * 4);
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    a_re[t][d] = w[d] ^ 0x80000000u;
-                    a_im[t][d] = __builtin_amdgcn_alignbit(w[d], w[d], 16);
+                    a_re[sl][t][d] = w[d] ^ 0x80000000u;
+                    a_im[sl][t][d] = __builtin_amdgcn_alignbit(w[d], w[d], 16);
                 }
             }
-            // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
-            constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
+        // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0); the four accumulators are interleaved
+        // because a dependent MFMA can only issue about four issue slots after its predecessor
+        constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
 #pragma unroll
-            for (int k = 0; k < 6; ++k) {
-                const bf16x8 bb = __builtin_bit_cast(bf16x8, b[SB[k]]);
-                acc_re[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb, acc_re[sl], 0, 0, 0);
-                acc_im[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb, acc_im[sl], 0, 0, 0);
+        for (int k = 0; k < 6; ++k) {
+            const bf16x8 bb = __builtin_bit_cast(bf16x8, b[SB[k]]);
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                acc_re[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[sl][SA[k]]), bb, acc_re[sl], 0, 0, 0);
+                acc_im[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[sl][SA[k]]), bb, acc_im[sl], 0, 0, 0);
             }
         }
     };

@@ -73,7 +73,10 @@ def test_fused_entry_points_report_unsupported_shapes(L):
 def test_workspace_contract(L):
     assert binding.workspace_bytes(1, False, 4, 16, 16, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 4, 16, 16, 64, 16) == 8 * 4 * (16 * 64 + 16 * 16 + 16 * 16 + 16 * 64)
-    assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 16) == 8 * 2 * 16 * 64 * (3 + 5)
+    # 2-D image kernels keep the truncated K x K spectra of input and output; the strip pipeline (shapes the
+    # image kernels do not cover, here K = 8) keeps two [B, C, K, N] strips
+    assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 16) == 8 * 2 * 16 * 16 * (3 + 5)
+    assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 8) == 8 * 2 * 8 * 64 * (3 + 5)
     assert binding.workspace_bytes(2, True, 2, 3, 5, 64, 16) == 8 * 2 * (3 * 4096 + 3 * 256 + 5 * 256 + 5 * 4096)
     assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0

@@ -196,3 +196,34 @@ def test_config4_full_size(gpu, oracle_mod, fn):
 def test_config5_sweep_full_size(gpu, oracle_mod, w):
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d", [0, 511])
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d_staged", [257])
+
+
+def test_fp32_contraction_kernels_in_a_child_process(gpu, oracle_mod, tmp_path):
+    """TFNO_CONTRACTION=f32 (read once per process) selects the FP32-MFMA contraction kernels: the generic fused
+    1-D kernel for N = 1024 and the FP32 mode CGEMM of the 2-D path.  A child process runs both and saves the
+    results; they are compared with the oracle here."""
+    import os
+    import subprocess
+    import textwrap
+    say("[case] TFNO_CONTRACTION=f32 child process")
+    out = str(tmp_path / "f32.npz")
+    code = textwrap.dedent(f"""
+        import numpy as np, torch
+        from paper_2504_11681_amd import binding, inputs
+        x1 = inputs.make_x(31, 2, 20, (1024,)); W1 = inputs.make_W(31, 20, 40)
+        y1 = torch.empty((2, 40, 1024), dtype=torch.complex64, device='cuda')
+        binding.spectral_conv1d(torch.from_numpy(x1).cuda(), torch.from_numpy(W1).cuda(), y1, 128)
+        x2 = inputs.make_x(32, 2, 5, (128, 128)); W2 = inputs.make_W(32, 5, 70)
+        y2 = torch.empty((2, 70, 128, 128), dtype=torch.complex64, device='cuda')
+        binding.spectral_conv2d(torch.from_numpy(x2).cuda(), torch.from_numpy(W2).cuda(), y2, 32)
+        torch.cuda.synchronize()
+        np.savez({out!r}, y1=y1.cpu().numpy(), y2=y2.cpu().numpy())
+    """)
+    env = dict(os.environ, TFNO_CONTRACTION="f32")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    subprocess.run([sys.executable, "-c", code], check=True, env=env, cwd=root, timeout=110)
+    got = np.load(out)
+    x1 = inputs.make_x(31, 2, 20, (1024,)); W1 = inputs.make_W(31, 20, 40)
+    check(got["y1"], oracle_mod.spectral_conv1d(x1, W1, 128)[0], "f32 1-D N=1024")
+    x2 = inputs.make_x(32, 2, 5, (128, 128)); W2 = inputs.make_W(32, 5, 70)
+    check(got["y2"], oracle_mod.spectral_conv2d(x2, W2, 32)[0], "f32 2-D 128x128")
