@@ -172,12 +172,22 @@ def main():
                          "fused_speedup": (swall / s_steps) / (wall / args.steps)}
         if w.name.startswith("cfg3"):
             w4 = pick_config("cfg4")
-            steps4 = max(5, args.steps // 5)
-            wall4, dev4 = measure(w4, torch, binding, steps4, 2)
-            out["cfg4_2d"] = {"workload": w4.name, "ms_per_step": wall4 / steps4 * 1e3,
+            steps4 = max(10, args.steps // 2)
+            wall4, dev4 = measure(w4, torch, binding, steps4, 5)
+            traffic4 = None
+            if os.path.exists(tpath):
+                traffic4 = json.load(open(tpath)).get(w4.name, {}).get("hbm_bytes_per_launch")
+            out["cfg4_2d"] = {"workload": w4.name, "steps": steps4, "ms_per_step": wall4 / steps4 * 1e3,
                               "layers_per_s": steps4 / wall4,
                               "effective_hbm_GBps": w4.compulsory_bytes / (wall4 / steps4) / 1e9,
-                              "effective_hbm_frac_of_peak": w4.compulsory_bytes / (wall4 / steps4) / 1e9 / HBM_PEAK_GBPS}
+                              "effective_hbm_frac_of_peak": w4.compulsory_bytes / (wall4 / steps4) / 1e9 / HBM_PEAK_GBPS,
+                              "roofline": {"bound": "hbm", "achieved": w4.compulsory_bytes / dev4 / 1e9,
+                                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                           "frac": w4.compulsory_bytes / dev4 / 1e9 / HBM_PEAK_GBPS,
+                                           "traffic": traffic4,
+                                           "kernel": "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)",
+                                           "algorithmic_bytes_per_launch": w4.compulsory_bytes,
+                                           "avg_launch_ms": dev4 * 1e3}}
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
 
