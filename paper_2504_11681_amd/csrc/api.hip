@@ -148,7 +148,15 @@ bool contraction_forced_f32()
 hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
 {
     if (!fused1d_supported(N, K)) return hipErrorInvalidValue;
-    if (fused1d_ws_supported(N, K) && !contraction_forced_f32()) return fused1d_ws_launch(N, K, a, rows, s);
+    if (!contraction_forced_f32()) {
+        // TFNO_KERNEL=ws keeps the wave-specialised kernel where the symmetric one would be chosen
+        static const bool prefer_ws = [] {
+            const char *e = getenv("TFNO_KERNEL");
+            return e && e[0] == 'w' && e[1] == 's' && e[2] == 0;
+        }();
+        if (fused1d_sym_supported(N, K) && !prefer_ws) return fused1d_sym_launch(N, K, a, rows, s);
+        if (fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
+    }
     switch (N) {
     case 64: return fused1d_launch_n64(K, a, rows, s);
     case 128: return fused1d_launch_n128(K, a, rows, s);

@@ -31,6 +31,10 @@ bool contraction_forced_f32();
 bool fused1d_ws_supported(int N, int K);
 hipError_t fused1d_ws_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 
+// Symmetric-wave variant (every wave runs transforms and contraction; BF16x3 split contraction).
+bool fused1d_sym_supported(int N, int K);
+hipError_t fused1d_sym_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+
 // Per-N dispatchers, one translation unit each.
 hipError_t fused1d_launch_n64(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s);

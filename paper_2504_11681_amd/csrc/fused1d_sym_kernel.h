@@ -1,0 +1,336 @@
+// Fused FFT -> CGEMM -> iFFT kernel for N = 1024 with eight symmetric waves (Sec. 4.3), gfx950.
+//
+//   workgroup = one batch row x 128 output channels, 512 threads = 8 waves, two per SIMD.
+//   Every wave does the same work, so the VALU load of the transforms is spread evenly:
+//     k-loop, 8 input channels per iteration (one pencil per wave), one barrier per iteration:
+//       row stage of block i+1: a whole wave owns a pencil, lane p holds x[p + 64 j], j < 16 (512-byte coalesced
+//         loads); 16-point DFT in registers, twiddle w_N^(p k_lo), transpose through a wave-private XOR-swizzled
+//         LDS patch, then four lanes per column k_lo: 16-point DFT of every fourth patch entry pruned to the
+//         K/16 retained outputs (Sec. 3.3), twiddle w_64^(a k_hi), sum over the quad with DPP; the retained bins
+//         k = k_lo + 16 k_hi are split exactly into three BF16 terms and written as MFMA operands to XS
+//         (double buffered).  The first butterfly level frees the load registers, so the loads of block i+2 are
+//         issued right after it and stay in flight for a whole iteration.
+//       contraction of block i: wave w owns outputs 32 (w/2) .. +31 and K/64 of the K/32 mode tiles;
+//         v_mfma_f32_32x32x16_bf16 on operands split into three BF16 terms, six products per tile and part
+//         (FP32-accurate, see bf16x3.h); four independent accumulators are interleaved because a dependent MFMA
+//         can only issue about four issue slots after its predecessor.
+//       The two waves of a SIMD run the two parts in opposite order, so one is on the matrix pipe while the
+//       other is on the VALU.
+//     epilogue, 16 rounds of 8 output pencils (one per wave), one barrier per round: accumulators -> LDS (mode
+//       order), twiddled zero-padded input-pruned column transform (Sec. 3.3) into the patch, 16-point inverse
+//       row transform, 512-byte coalesced stores.  1/N is folded into W.
+//   MFMA k index (16 per instruction) = 8 channels x (re, im): lanes 0-31 carry channels 0-3, lanes 32-63
+//   channels 4-7; dword d of a lane = (re | im << 16) of channel 4g + d.  Real part: A = (W.re, -W.im), imaginary
+//   part: A = (W.im, W.re).  Accumulator register r of lane l holds output 8(r/4) + 4(l/32) + r%4, mode l%32.
+#pragma once
+#include "common.h"
+#include "fft_regs.h"
+#include "fused1d.h"
+#include "fused1d_kernel.h"   // wave_sync, floatx16
+#include "bf16x3.h"
+
+namespace tfno {
+
+template <int K>
+struct SymCfg {
+    static constexpr int N = 1024, NT = 512, NW = 8, PPI = 8;
+    static constexpr int KH = K / 16;               // retained k_hi per column k_lo
+    static constexpr int KT = K / 32;               // 32-mode tiles
+    static constexpr int TPW = KT / 2;              // mode tiles per wave
+    static constexpr int OPL = KH / 4;              // retained bins per lane after the quad reduction
+    static constexpr int PATCH = 16 * 64;           // complex elements of one wave's transpose patch
+    static constexpr int XS_BUF = 3 * 2 * KT * 128; // dwords per operand buffer: [term][g][tile][n][d]
+    static constexpr int YH_BUF = 8 * K;            // complex elements per spectrum buffer: [pencil][mode]
+    static constexpr size_t LDS_PATCH = sizeof(c64) * NW * PATCH;
+    static constexpr size_t LDS_XS = sizeof(unsigned) * 2 * XS_BUF;
+    static constexpr size_t LDS_YH = sizeof(c64) * 2 * YH_BUF;
+    static constexpr size_t LDS_DYN = LDS_PATCH + (LDS_XS > LDS_YH ? LDS_XS : LDS_YH);
+    static_assert(K == 64 || K == 128, "K in {64, 128}");
+    static_assert(LDS_DYN + sizeof(c64) * (N + 64) <= 160 * 1024, "LDS budget of one gfx950 CU");
+};
+
+template <int CTRL>
+__device__ __forceinline__ float sym_quad_perm(float v)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+template <int K, bool EVEN>
+__global__ void __launch_bounds__(512)
+k_fused1d_sym(Fused1dArgs a)
+{
+    using C = SymCfg<K>;
+    constexpr int N = C::N, KH = C::KH, KT = C::KT, TPW = C::TPW, OPL = C::OPL, PPI = C::PPI;
+
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    c64 *patch_all = reinterpret_cast<c64 *>(lds_raw);                          // [8 waves][16][64]
+    unsigned *XS = reinterpret_cast<unsigned *>(lds_raw + C::LDS_PATCH);         // [2][3][2][KT][32][4]
+    c64 *YH = reinterpret_cast<c64 *>(lds_raw + C::LDS_PATCH);                   // [2][8][K]  (aliases XS)
+    __shared__ c64 TW[N];                                                        // [k_lo][p]: w_N^(p k_lo)
+    __shared__ c64 TW64[64];                                                     // w_64^t
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int bb = blockIdx.x;
+    const int o_base = blockIdx.y * 128;
+    const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
+    const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
+    c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
+
+    TFNO_STAMP(0);
+    const int n_it = (a.C_in + PPI - 1) / PPI;
+    c64 *patch = patch_all + wave * C::PATCH;
+    const int p = lane;                                 // row-stage identity
+    const int kl = lane >> 2, qa = lane & 3;            // column-stage identity: column k_lo, quad position
+    const int swz = 4 * (kl & 3);                       // patch entry (k_lo, p) lives at k_lo*64 + (p ^ 4(k_lo & 3))
+    const int g = lane >> 5, nn = lane & 31;            // MFMA identity
+    const int slab = wave >> 1;                         // 32-output slab of this wave
+    const int tile0 = (wave & 1) * TPW;                 // first mode tile of this wave
+    const int o_lane = o_base + 32 * slab + nn;         // the output channel whose W this lane feeds
+
+    for (int i = tid; i < N; i += C::NT) TW[i] = cis2pi(-(float)((i >> 6) * (i & 63)), (float)N);
+    if (tid < 64) TW64[tid] = cis2pi(-(float)tid, 64.f);
+
+    floatx16 acc_re[TPW], acc_im[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc_re[i][r] = 0.f; acc_im[i][r] = 0.f; }
+
+    c64 v[16];                  // the pencil this wave transforms next
+    c64 wraw[4];                // W[c0 + 4g + d][o_lane], d < 4, of the next block
+    uintx4 a_re[3], a_im[3];    // split A operands of the current block
+
+    auto load_pencil = [&](int c0) __attribute__((always_inline)) {
+        const int c = c0 + wave;
+        if constexpr (EVEN) {
+            const c64 *src = xb + (long long)c * a.x_chan_stride + p;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = src[64 * j];
+        } else {
+            const bool ok = c < a.C_in;
+            const c64 *src = xb + (long long)(ok ? c : 0) * a.x_chan_stride + p;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                c64 val = src[64 * j];
+                v[j] = ok ? val : make_float2(0.f, 0.f);
+            }
+        }
+    };
+    auto load_w = [&](int c0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int c = c0 + 4 * g + d;
+            if constexpr (EVEN) {
+                wraw[d] = a.W[(long long)c * a.C_out + o_lane];
+            } else {
+                const bool ok = c < a.C_in && o_lane < a.C_out;
+                c64 val = a.W[ok ? (long long)c * a.C_out + o_lane : 0];
+                wraw[d] = ok ? val : make_float2(0.f, 0.f);
+            }
+        }
+    };
+    auto split_w = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const Split3 re = split3(wraw[d].x * a.scale), im = split3(wraw[d].y * a.scale);
+            a_re[0][d] = pack_bf16(re.t0, im.t0) ^ 0x80000000u;
+            a_re[1][d] = pack_bf16(re.t1, im.t1) ^ 0x80000000u;
+            a_re[2][d] = pack_bf16(re.t2, im.t2) ^ 0x80000000u;
+            a_im[0][d] = pack_bf16(im.t0, re.t0);
+            a_im[1][d] = pack_bf16(im.t1, re.t1);
+            a_im[2][d] = pack_bf16(im.t2, re.t2);
+        }
+    };
+    // Forward transform of the pencil in v, pruned to the K retained bins, into operand buffer `buf`;
+    // REFILL: the loads of block refill_c0 are issued as soon as the first butterfly level has consumed v.
+    auto row_stage = [&](int buf, auto refill, int refill_c0) __attribute__((always_inline)) {
+        constexpr bool REFILL = decltype(refill)::value;
+        c64 z[16];
+        {
+            c64 ea[8], eb[8], za[8], zo[8];
+            dif_first_level<16, -1>(v, ea, eb);
+            __builtin_amdgcn_sched_barrier(0);
+#ifndef TFNO_DBG_SYM_NOLOAD
+            if constexpr (REFILL) load_pencil(refill_c0);
+#else
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = make_float2(ea[j / 2].x + eb[j / 2].y, ea[j / 2].y);   // timing experiment
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+            RegFFT<8, -1, 1>::run(ea, za);
+            RegFFT<8, -1, 1>::run(eb, zo);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { z[2 * k] = za[k]; z[2 * k + 1] = zo[k]; }
+        }
+        wave_sync();                                        // the previous pencil's patch reads are done
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const c64 zt = c == 0 ? z[0] : cmul(z[c], TW[c * 64 + p]);
+            patch[c * 64 + (p ^ (4 * (c & 3)))] = zt;
+        }
+        wave_sync();
+        // lane (k_lo, qa): entries p = qa + 4 p', p' < 16, of column k_lo
+        c64 P[KH];
+        dft_prune_out<16, KH, -1>([&](auto ppc) __attribute__((always_inline)) {
+            constexpr int pp = decltype(ppc)::value;
+            return patch[kl * 64 + ((qa + 4 * pp) ^ swz)];
+        }, P);
+#pragma unroll
+        for (int kh = 1; kh < KH; ++kh) P[kh] = cmul(P[kh], TW64[qa * kh]);
+        // sum over the quad; lane qa keeps bins k_hi = OPL qa + i
+        c64 R[KH / 2], O[OPL];
+        {
+            const bool hi = (qa & 2) != 0;
+#pragma unroll
+            for (int i = 0; i < KH / 2; ++i) {
+                const c64 mine = hi ? P[KH / 2 + i] : P[i], send = hi ? P[i] : P[KH / 2 + i];
+                R[i] = make_float2(mine.x + sym_quad_perm<0x4E>(send.x), mine.y + sym_quad_perm<0x4E>(send.y));
+            }
+        }
+        {
+            const bool hi = (qa & 1) != 0;
+#pragma unroll
+            for (int i = 0; i < OPL; ++i) {
+                const c64 mine = hi ? R[OPL + i] : R[i], send = hi ? R[i] : R[OPL + i];
+                O[i] = make_float2(mine.x + sym_quad_perm<0xB1>(send.x), mine.y + sym_quad_perm<0xB1>(send.y));
+            }
+        }
+        // bin k = k_lo + 16 (OPL qa + i)  ->  XS[buf][term][wave / 4][k / 32][k % 32][wave % 4]
+        unsigned *dst = XS + buf * C::XS_BUF + (wave >> 2) * (KT * 128) + (wave & 3);
+#pragma unroll
+        for (int i = 0; i < OPL; ++i) {
+            const int k = kl + 16 * (OPL * qa + i);
+            const Split3 re = split3(O[i].x), im = split3(O[i].y);
+            unsigned *d = dst + (k >> 5) * 128 + (k & 31) * 4;
+            d[0 * 2 * KT * 128] = pack_bf16(re.t0, im.t0);
+            d[1 * 2 * KT * 128] = pack_bf16(re.t1, im.t1);
+            d[2 * 2 * KT * 128] = pack_bf16(re.t2, im.t2);
+        }
+    };
+    auto mfma_block = [&](int buf) __attribute__((always_inline)) {
+        const unsigned *src = XS + buf * C::XS_BUF + (g * KT + tile0) * 128 + nn * 4;
+        uintx4 b[TPW][3];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) b[i][t] = *reinterpret_cast<const uintx4 *>(src + t * 2 * KT * 128 + i * 128);
+        // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
+        constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+        for (int k = 0; k < 6; ++k)
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const bf16x8 bb16 = __builtin_bit_cast(bf16x8, b[i][SB[k]]);
+                acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb16, acc_re[i], 0, 0, 0);
+                acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[i], 0, 0, 0);
+            }
+    };
+    // one k-loop iteration: contraction of block `it`, row stage of block it + 1, W of block it + 1
+    auto body = [&](int it, auto refill) __attribute__((always_inline)) {
+        load_w((it + 1) * PPI);
+        if (wave < 4) {
+            mfma_block(it & 1);
+            row_stage((it + 1) & 1, refill, (it + 2) * PPI);
+        } else {
+            row_stage((it + 1) & 1, refill, (it + 2) * PPI);
+            mfma_block(it & 1);
+        }
+        split_w();
+        __syncthreads();
+    };
+
+    // ------------------------------------------------------------------ k-loop over input channels
+    load_pencil(0);
+    load_w(0);
+    __syncthreads();                                        // twiddle tables are ready
+    if (n_it > 1) row_stage(0, std::true_type{}, PPI);
+    else row_stage(0, std::false_type{}, 0);
+    split_w();
+    __syncthreads();                                        // XS[0] holds block 0
+    TFNO_STAMP(1);
+    {
+        int it = 0;
+        for (; it + 2 < n_it; ++it) body(it, std::true_type{});
+        if (it + 1 < n_it) { body(it, std::false_type{}); ++it; }
+        mfma_block(it & 1);
+    }
+
+    // ------------------------------------------------------------------ epilogue
+    TFNO_STAMP(2);
+    __syncthreads();                                        // every wave is done reading XS, which YH aliases
+    for (int r = 0; r < 16; ++r) {
+        // spectra of this round's 8 output pencils (slot 2 slab + l/32), in mode order
+        {
+            c64 *dst = YH + (r & 1) * C::YH_BUF + (2 * slab + g) * K + 32 * tile0 + nn;
+            static_for<0, 16>([&](auto rc) {
+                constexpr int R = decltype(rc)::value;
+                if (r == R) {
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) dst[32 * i] = make_float2(acc_re[i][R], acc_im[i][R]);
+                }
+            });
+        }
+        __syncthreads();
+        // wave w inverts pencil slot w: output 32 (w/2) + 8 (r/4) + 4 (w%2) + r%4
+        const c64 *Yp = YH + (r & 1) * C::YH_BUF + wave * K;
+        c64 yin[KH];
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+            c64 t = Yp[kl + 16 * kh];
+            if (kh != 0) {
+                const c64 w = TW64[qa * kh];
+                t = cmul(t, make_float2(w.x, -w.y));
+            }
+            yin[kh] = t;
+        }
+        wave_sync();                                        // the previous pencil's patch reads are done
+        dft_prune_in<16, KH, +1>(yin, [&](auto ppc, c64 val) __attribute__((always_inline)) {
+            constexpr int pp = decltype(ppc)::value;
+            patch[kl * 64 + ((qa + 4 * pp) ^ swz)] = val;
+        });
+        wave_sync();
+        c64 z[16], res[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            c64 t = patch[c * 64 + (p ^ (4 * (c & 3)))];
+            if (c != 0) {
+                const c64 w = TW[c * 64 + p];
+                t = cmul(t, make_float2(w.x, -w.y));
+            }
+            z[c] = t;
+        }
+        RegFFT<16, +1, 1>::run(z, res);
+        const int o = o_base + 32 * (wave >> 1) + 8 * (r / 4) + 4 * (wave & 1) + (r % 4);
+        if (EVEN || o < a.C_out) {
+            c64 *dst = yb + (long long)o * a.y_chan_stride + p;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dst[64 * j] = res[j];
+        }
+    }
+    TFNO_STAMP(3);
+}
+
+template <int K>
+hipError_t launch_fused1d_sym(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
+{
+    using C = SymCfg<K>;
+    static bool attr_done = false;   // benign race: every thread sets the same value
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_sym<K, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_sym<K, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 127) / 128));
+    if (a.C_in % C::PPI == 0 && a.C_out % 128 == 0)
+        hipLaunchKernelGGL((k_fused1d_sym<K, true>), grid, dim3(512), C::LDS_DYN, s, a);
+    else
+        hipLaunchKernelGGL((k_fused1d_sym<K, false>), grid, dim3(512), C::LDS_DYN, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace tfno
