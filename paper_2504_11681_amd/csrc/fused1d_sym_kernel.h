@@ -55,7 +55,9 @@ __device__ __forceinline__ float sym_quad_perm(float v)
     return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 
-template <int K, bool EVEN>
+// EVEN: C_in is a multiple of 8 and C_out a multiple of 128 (no masks).  DEEP: the number of 8-channel blocks
+// is even and at least four; the k-loop then keeps two blocks of loads in flight per wave.
+template <int K, bool EVEN, bool DEEP>
 __global__ void __launch_bounds__(512)
 k_fused1d_sym(Fused1dArgs a)
 {
@@ -78,6 +80,10 @@ k_fused1d_sym(Fused1dArgs a)
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
 
     TFNO_STAMP(0);
+#ifdef TFNO_DBG_SKEW
+    // timing experiment: start the workgroups of an XCD in four phases a fraction of an iteration apart
+    for (int i = 0; i < (int)((blockIdx.x >> 3) & 3); ++i) __builtin_amdgcn_s_sleep(TFNO_DBG_SKEW);
+#endif
     const int n_it = (a.C_in + PPI - 1) / PPI;
     c64 *patch = patch_all + wave * C::PATCH;
     const int p = lane;                                 // row-stage identity
@@ -97,11 +103,11 @@ k_fused1d_sym(Fused1dArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { acc_re[i][r] = 0.f; acc_im[i][r] = 0.f; }
 
-    c64 v[16];                  // the pencil this wave transforms next
+    c64 va[16], vb[16];         // the next two pencils of this wave: block b lives in buffer b & 1
     c64 wraw[4];                // W[c0 + 4g + d][o_lane], d < 4, of the next block
     uintx4 a_re[3], a_im[3];    // split A operands of the current block
 
-    auto load_pencil = [&](int c0) __attribute__((always_inline)) {
+    auto load_pencil = [&](c64 *v, int c0) __attribute__((always_inline)) {
         const int c = c0 + wave;
         if constexpr (EVEN) {
             const c64 *src = xb + (long long)c * a.x_chan_stride + p;
@@ -142,32 +148,37 @@ k_fused1d_sym(Fused1dArgs a)
             a_im[2][d] = pack_bf16(im.t2, re.t2);
         }
     };
-    // Forward transform of the pencil in v, pruned to the K retained bins, into operand buffer `buf`;
-    // REFILL: the loads of block refill_c0 are issued as soon as the first butterfly level has consumed v.
-    auto row_stage = [&](int buf, auto refill, int refill_c0) __attribute__((always_inline)) {
+    // Forward transform of the pencil in v, pruned to the K retained bins, into operand buffer `buf`.
+    // REFILL, DEEP: v is reloaded with block refill_c0, two blocks ahead, as soon as its transform has left the
+    // registers (after the patch writes): two blocks of loads per wave, 128 KB per CU, are then in flight, which
+    // the loaded HBM latency needs; one block (64 KB) leaves the k-loop waiting for memory.
+    // REFILL, not DEEP: v is reloaded with the next block right after the first butterfly level.
+    auto row_stage = [&](c64 *v, int buf, auto refill, int refill_c0) __attribute__((always_inline)) {
         constexpr bool REFILL = decltype(refill)::value;
-        c64 z[16];
         {
             c64 ea[8], eb[8], za[8], zo[8];
             dif_first_level<16, -1>(v, ea, eb);
-            __builtin_amdgcn_sched_barrier(0);
-#ifndef TFNO_DBG_SYM_NOLOAD
-            if constexpr (REFILL) load_pencil(refill_c0);
-#else
-#pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] = make_float2(ea[j / 2].x + eb[j / 2].y, ea[j / 2].y);   // timing experiment
-#endif
-            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (REFILL && !DEEP) {
+                __builtin_amdgcn_sched_barrier(0);
+                load_pencil(v, refill_c0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             RegFFT<8, -1, 1>::run(ea, za);
             RegFFT<8, -1, 1>::run(eb, zo);
+            wave_sync();                                    // the previous pencil's patch reads are done
 #pragma unroll
-            for (int k = 0; k < 8; ++k) { z[2 * k] = za[k]; z[2 * k + 1] = zo[k]; }
+            for (int k = 0; k < 8; ++k) {
+                const int c0 = 2 * k, c1 = 2 * k + 1;       // z[2k] = za[k], z[2k+1] = zo[k]
+                const c64 t0 = c0 == 0 ? za[0] : cmul(za[k], TW[c0 * 64 + p]);
+                const c64 t1 = cmul(zo[k], TW[c1 * 64 + p]);
+                patch[c0 * 64 + (p ^ (4 * (c0 & 3)))] = t0;
+                patch[c1 * 64 + (p ^ (4 * (c1 & 3)))] = t1;
+            }
         }
-        wave_sync();                                        // the previous pencil's patch reads are done
-#pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            const c64 zt = c == 0 ? z[0] : cmul(z[c], TW[c * 64 + p]);
-            patch[c * 64 + (p ^ (4 * (c & 3)))] = zt;
+        if constexpr (REFILL && DEEP) {
+            __builtin_amdgcn_sched_barrier(0);
+            load_pencil(v, refill_c0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         wave_sync();
         // lane (k_lo, qa): entries p = qa + 4 p', p' < 16, of column k_lo
@@ -226,33 +237,51 @@ k_fused1d_sym(Fused1dArgs a)
                 acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[i], 0, 0, 0);
             }
     };
-    // one k-loop iteration: contraction of block `it`, row stage of block it + 1, W of block it + 1
-    auto body = [&](int it, auto refill) __attribute__((always_inline)) {
+    // one k-loop iteration: contraction of block `it`, row stage of block it + 1 (held in v), W of block it + 1
+    auto body = [&](int it, c64 *v, auto refill) __attribute__((always_inline)) {
         load_w((it + 1) * PPI);
         if (wave < 4) {
             mfma_block(it & 1);
-            row_stage((it + 1) & 1, refill, (it + 2) * PPI);
+            row_stage(v, (it + 1) & 1, refill, (it + (DEEP ? 3 : 2)) * PPI);
         } else {
-            row_stage((it + 1) & 1, refill, (it + 2) * PPI);
+            row_stage(v, (it + 1) & 1, refill, (it + (DEEP ? 3 : 2)) * PPI);
             mfma_block(it & 1);
         }
         split_w();
         __syncthreads();
     };
+    const std::true_type yes{};
+    const std::false_type no{};
 
     // ------------------------------------------------------------------ k-loop over input channels
-    load_pencil(0);
+    load_pencil(va, 0);
+    if constexpr (DEEP) load_pencil(vb, PPI);
     load_w(0);
     __syncthreads();                                        // twiddle tables are ready
-    if (n_it > 1) row_stage(0, std::true_type{}, PPI);
-    else row_stage(0, std::false_type{}, 0);
+    if constexpr (DEEP) {
+        row_stage(va, 0, yes, 2 * PPI);
+    } else {
+        if (n_it > 1) row_stage(va, 0, yes, PPI);
+        else row_stage(va, 0, no, 0);
+    }
     split_w();
     __syncthreads();                                        // XS[0] holds block 0
     TFNO_STAMP(1);
-    {
+    if constexpr (DEEP) {
+        // iteration `it` transforms block it + 1 (buffer (it + 1) & 1) and refills that buffer with block it + 3
         int it = 0;
-        for (; it + 2 < n_it; ++it) body(it, std::true_type{});
-        if (it + 1 < n_it) { body(it, std::false_type{}); ++it; }
+        for (; it + 4 < n_it; it += 2) {
+            body(it, vb, yes);
+            body(it + 1, va, yes);
+        }
+        body(it, vb, yes);          // it = n_it - 4: block n_it - 3, refill with the last block
+        body(it + 1, va, no);       // block n_it - 2
+        body(it + 2, vb, no);       // block n_it - 1
+        mfma_block((it + 3) & 1);
+    } else {
+        int it = 0;
+        for (; it + 2 < n_it; ++it) body(it, va, yes);
+        if (it + 1 < n_it) { body(it, va, no); ++it; }
         mfma_block(it & 1);
     }
 
@@ -317,19 +346,24 @@ hipError_t launch_fused1d_sym(const Fused1dArgs &a, long long batch_rows, hipStr
     using C = SymCfg<K>;
     static bool attr_done = false;   // benign race: every thread sets the same value
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_sym<K, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_sym<K, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-        if (e != hipSuccess) return e;
+        const void *kernels[3] = {reinterpret_cast<const void *>(&k_fused1d_sym<K, true, true>),
+                                  reinterpret_cast<const void *>(&k_fused1d_sym<K, true, false>),
+                                  reinterpret_cast<const void *>(&k_fused1d_sym<K, false, false>)};
+        for (const void *k : kernels) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
+            if (e != hipSuccess) return e;
+        }
         attr_done = true;
     }
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 127) / 128));
-    if (a.C_in % C::PPI == 0 && a.C_out % 128 == 0)
-        hipLaunchKernelGGL((k_fused1d_sym<K, true>), grid, dim3(512), C::LDS_DYN, s, a);
+    const bool even = a.C_in % C::PPI == 0 && a.C_out % 128 == 0;
+    const int n_it = (a.C_in + C::PPI - 1) / C::PPI;
+    if (even && n_it % 2 == 0 && n_it >= 4)
+        hipLaunchKernelGGL((k_fused1d_sym<K, true, true>), grid, dim3(512), C::LDS_DYN, s, a);
+    else if (even)
+        hipLaunchKernelGGL((k_fused1d_sym<K, true, false>), grid, dim3(512), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d_sym<K, false>), grid, dim3(512), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d_sym<K, false, false>), grid, dim3(512), C::LDS_DYN, s, a);
     return hipGetLastError();
 }
 

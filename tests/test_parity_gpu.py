@@ -71,6 +71,9 @@ SMALL_1D = [
     (2, 20, 30, 1024, 32),
     (2, 9, 64, 1024, 256),
     (1, 1, 1, 1024, 64),
+    (2, 32, 128, 1024, 128),
+    (1, 48, 256, 1024, 64),
+    (2, 16, 128, 1024, 128),
 ]
 
 
@@ -196,6 +199,41 @@ def test_config4_full_size(gpu, oracle_mod, fn):
 def test_config5_sweep_full_size(gpu, oracle_mod, w):
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d", [0, 511])
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d_staged", [257])
+
+
+SYM_1D = [(2, 32, 128, 1024, 128),   # two blocks of loads in flight (even block count >= 4), no masks
+          (1, 48, 256, 1024, 64),
+          (2, 16, 128, 1024, 128),   # unmasked, two blocks only
+          (3, 13, 129, 1024, 128),   # masked
+          (1, 1, 1, 1024, 64)]
+
+
+def test_symmetric_kernel_in_a_child_process(gpu, oracle_mod, tmp_path):
+    """TFNO_KERNEL=sym (read once per process) selects the symmetric-wave kernel for N = 1024, K in {64, 128}."""
+    import os
+    import subprocess
+    import textwrap
+    say("[case] TFNO_KERNEL=sym child process")
+    out = str(tmp_path / "sym.npz")
+    code = textwrap.dedent(f"""
+        import numpy as np, torch
+        from paper_2504_11681_amd import binding, inputs
+        res = {{}}
+        for i, (B, Ci, Co, N, K) in enumerate({SYM_1D!r}):
+            x = inputs.make_x(40 + i, B, Ci, (N,)); W = inputs.make_W(40 + i, Ci, Co)
+            y = torch.empty((B, Co, N), dtype=torch.complex64, device='cuda')
+            binding.spectral_conv1d(torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda(), y, K)
+            torch.cuda.synchronize()
+            res['y%d' % i] = y.cpu().numpy()
+        np.savez({out!r}, **res)
+    """)
+    env = dict(os.environ, TFNO_KERNEL="sym")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    subprocess.run([sys.executable, "-c", code], check=True, env=env, cwd=root, timeout=110)
+    got = np.load(out)
+    for i, (B, Ci, Co, N, K) in enumerate(SYM_1D):
+        x = inputs.make_x(40 + i, B, Ci, (N,)); W = inputs.make_W(40 + i, Ci, Co)
+        check(got["y%d" % i], oracle_mod.spectral_conv1d(x, W, K)[0], f"sym {(B, Ci, Co, N, K)}")
 
 
 def test_fp32_contraction_kernels_in_a_child_process(gpu, oracle_mod, tmp_path):
