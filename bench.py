@@ -65,11 +65,12 @@ def flops_of(w):
     return 8.0 * w.B * (w.K ** w.dims) * w.C_in * w.C_out
 
 
-def measure(w, torch, binding, steps, warmup, staged=False):
+def measure(w, torch, binding, steps, warmup, staged=False, pruned=False):
     xd, Wd, yd = device_inputs(w, torch)
-    name = ("spectral_conv%dd" % w.dims) + ("_staged" if staged else "")
+    variant = 2 if pruned else 1 if staged else 0
+    name = ("spectral_conv%dd" % w.dims) + ("", "_staged", "_pruned")[variant]
     fn = getattr(binding, name)
-    binding.ensure_workspace(binding.workspace_bytes(w.dims, staged, w.B, w.C_in, w.C_out, w.N, w.K), xd.device)
+    binding.ensure_workspace(binding.workspace_bytes(w.dims, variant, w.B, w.C_in, w.C_out, w.N, w.K), xd.device)
     stream = torch.cuda.current_stream().cuda_stream
     call = lambda: fn(xd, Wd, yd, w.K, stream)
     wall, dev = time_calls(torch, call, steps, warmup)

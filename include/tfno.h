@@ -98,11 +98,23 @@ tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y,
                                         int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
- * Workspace (device memory for intermediates) that an entry point needs for a
- * shape: dims = 1 or 2, staged = 0 (fused entry point) or 1 (staged twin).
- * Returns 0 when none is needed or the arguments are invalid.
+ * 1-D spectral convolution as three launches with truncation, zero padding and butterfly pruning built into the
+ * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
+ * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and
+ * same result as tfno_spectral_conv1d.  Shapes: N in {64,128,256} with K a multiple of 16 such that K/16 is a
+ * power of two not above N/16, or N = 1024 with K in {64,128}; others TFNO_ERR_UNSUPPORTED.  Needs
+ * tfno_workspace_bytes(1, 2, ...) bytes of workspace.  It is the faster path where the fused kernel is bound by
+ * its contraction (hidden dimension >= 128 with K/N = 1/2, the crossover Sec. 5.1 describes).
  */
-size_t tfno_workspace_bytes(int dims, int staged, int B, int C_in, int C_out, int N, int K);
+tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y,
+                                        int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
+ * Workspace (device memory for intermediates) that an entry point needs for a
+ * shape: dims = 1 or 2, variant = 0 (fused entry point), 1 (staged twin) or 2
+ * (tfno_spectral_conv1d_pruned).  Returns 0 when none is needed or the arguments are invalid.
+ */
+size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K);
 
 /*
  * Registers a caller-owned device buffer as the library's workspace for all

@@ -19,6 +19,7 @@ EXPORTS = (
     "tfno_spectral_conv2d",
     "tfno_spectral_conv1d_staged",
     "tfno_spectral_conv2d_staged",
+    "tfno_spectral_conv1d_pruned",
     "tfno_workspace_bytes",
     "tfno_set_workspace",
     "tfno_status_string",
@@ -44,7 +45,7 @@ def lib() -> ctypes.CDLL:
                                "(there is no fallback path)")
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
-        for name in EXPORTS[:4]:
+        for name in EXPORTS[:5]:
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
@@ -68,8 +69,9 @@ def version() -> int:
     return lib().tfno_version()
 
 
-def workspace_bytes(dims: int, staged: bool, B: int, C_in: int, C_out: int, N: int, K: int) -> int:
-    return lib().tfno_workspace_bytes(dims, int(staged), B, C_in, C_out, N, K)
+def workspace_bytes(dims: int, variant, B: int, C_in: int, C_out: int, N: int, K: int) -> int:
+    """variant: 0 / False = fused entry point, 1 / True = staged twin, 2 = spectral_conv1d_pruned."""
+    return lib().tfno_workspace_bytes(dims, int(variant), B, C_in, C_out, N, K)
 
 
 def set_workspace(tensor) -> None:
@@ -93,7 +95,7 @@ def ensure_workspace(nbytes: int, device) -> None:
         set_workspace(torch.empty(nbytes, dtype=torch.uint8, device=device))
 
 
-def _call(name: str, dims: int, staged: bool, x, W, y, K: int, stream):
+def _call(name: str, dims: int, variant, x, W, y, K: int, stream):
     import torch
     for t, what in ((x, "x"), (W, "W"), (y, "y")):
         if t.dtype != torch.complex64 or not t.is_contiguous() or not t.is_cuda:
@@ -104,7 +106,7 @@ def _call(name: str, dims: int, staged: bool, x, W, y, K: int, stream):
     C_out = W.shape[1]
     if W.shape[0] != C_in or tuple(y.shape) != (B, C_out) + tuple(x.shape[2:]) or any(s != N for s in x.shape[2:]):
         raise ValueError("inconsistent tensor shapes")
-    ensure_workspace(workspace_bytes(dims, staged, B, C_in, C_out, N, K), x.device)
+    ensure_workspace(workspace_bytes(dims, variant, B, C_in, C_out, N, K), x.device)
     if stream is None:
         stream = torch.cuda.current_stream(x.device).cuda_stream
     st = getattr(lib(), name)(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, K, stream)
@@ -127,3 +129,7 @@ def spectral_conv1d_staged(x, W, y, K: int, stream=None):
 
 def spectral_conv2d_staged(x, W, y, K: int, stream=None):
     return _call("tfno_spectral_conv2d_staged", 2, True, x, W, y, K, stream)
+
+
+def spectral_conv1d_pruned(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv1d_pruned", 1, 2, x, W, y, K, stream)

@@ -3,6 +3,7 @@
 #include "common.h"
 #include "fused1d.h"
 #include "fused2d.h"
+#include "pruned1d.h"
 #include "staged.h"
 
 #include <atomic>
@@ -62,19 +63,26 @@ tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W
     return TFNO_OK;
 }
 
-tfno_status run(int dims, bool staged, const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
-                void *stream)
+enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2 };
+
+tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                int K, void *stream)
 {
+    const bool staged = variant == STAGED;
     bool empty;
     tfno_status st = validate(dims, x, W, y, B, C_in, C_out, N, K, &empty);
     if (st != TFNO_OK || empty) return st;
-    if (!staged && !(dims == 2 && fused2d_supported(N, K)) && !fused1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+    if (variant == PRUNED) {
+        if (dims != 1 || !pruned1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+    } else if (!staged && !(dims == 2 && fused2d_supported(N, K)) && !fused1d_supported(N, K)) {
+        return TFNO_ERR_UNSUPPORTED;
+    }
 
     const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     void *ws = nullptr;
-    st = check_workspace(tfno_workspace_bytes(dims, staged ? 1 : 0, B, C_in, C_out, N, K), x, xb, W, wb, y, yb, &ws);
+    st = check_workspace(tfno_workspace_bytes(dims, (int)variant, B, C_in, C_out, N, K), x, xb, W, wb, y, yb, &ws);
     if (st != TFNO_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
@@ -84,6 +92,8 @@ tfno_status run(int dims, bool staged, const void *x, const void *W, void *y, in
 
     if (staged) {
         e = staged_conv(dims, xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
+    } else if (variant == PRUNED) {
+        e = pruned1d_launch(xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
     } else if (dims == 1) {
         Fused1dArgs a{};
         a.x = xc; a.W = Wc; a.y = yc; a.C_in = C_in; a.C_out = C_out;
@@ -175,29 +185,41 @@ extern "C" {
 tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
                                  void *stream)
 {
-    return run(1, false, x, W, y, B, C_in, C_out, N, K, stream);
+    return run(1, FUSED, x, W, y, B, C_in, C_out, N, K, stream);
 }
 
 tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
                                  void *stream)
 {
-    return run(2, false, x, W, y, B, C_in, C_out, N, K, stream);
+    return run(2, FUSED, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                        int K, void *stream)
+{
+    return run(1, PRUNED, x, W, y, B, C_in, C_out, N, K, stream);
 }
 
 tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
                                         int K, void *stream)
 {
-    return run(1, true, x, W, y, B, C_in, C_out, N, K, stream);
+    return run(1, STAGED, x, W, y, B, C_in, C_out, N, K, stream);
 }
 
 tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
                                         int K, void *stream)
 {
-    return run(2, true, x, W, y, B, C_in, C_out, N, K, stream);
+    return run(2, STAGED, x, W, y, B, C_in, C_out, N, K, stream);
 }
 
-size_t tfno_workspace_bytes(int dims, int staged, int B, int C_in, int C_out, int N, int K)
+size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K)
 {
+    const int staged = variant == 1;
+    if (variant < 0 || variant > 2) return 0;
+    if (variant == 2) {
+        if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !pruned1d_supported(N, K)) return 0;
+        return pruned1d_workspace_bytes(B, C_in, C_out, K);
+    }
     if ((dims != 1 && dims != 2) || B < 1 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N)
         return 0;
     if (staged) return staged_workspace_bytes(dims, B, C_in, C_out, N, K);

@@ -12,4 +12,8 @@ size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K);
 hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
                           c64 *ws, hipStream_t s);
 
+// Yh = Xh . (scale W) over `tiles` tiles of 128 modes; both spectra mode-tile major ([tile][channel][128]).
+hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,
+                              hipStream_t s);
+
 }  // namespace tfno

@@ -15,6 +15,19 @@ size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K)
     return sizeof(c64) * (size_t)B * K * K * ((size_t)C_in + C_out);
 }
 
+hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,
+                              hipStream_t s)
+{
+    // about two workgroups per CU, each walking several mode tiles
+    const int tpw = tiles >= 1024 ? (int)(tiles / 512 > 16 ? 16 : tiles / 512) : 1;
+    const dim3 ggrid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64));
+    if (contraction_forced_f32())
+        hipLaunchKernelGGL(k_cgemm_modes_f32, ggrid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
+    else
+        hipLaunchKernelGGL(k_cgemm_modes, ggrid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
+    return hipGetLastError();
+}
+
 template <int N, int K>
 static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
                             hipStream_t s)
@@ -24,16 +37,8 @@ static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int
     hipLaunchKernelGGL((k_fwd2d<N, K>), dim3((unsigned)(B * C_in)), dim3(256), 0, s, x, Xh, C_in);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const float scale = 1.0f / ((float)N * (float)N);
-    // about two workgroups per CU, each walking several mode tiles
-    const long long tiles = B * (M / 128);
-    const int tpw = tiles >= 1024 ? (int)(tiles / 512 > 16 ? 16 : tiles / 512) : 1;
-    const dim3 ggrid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64));
-    if (contraction_forced_f32())
-        hipLaunchKernelGGL(k_cgemm_modes_f32, ggrid, dim3(256), 0, s, (const c64 *)Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
-    else
-        hipLaunchKernelGGL(k_cgemm_modes, ggrid, dim3(256), 0, s, (const c64 *)Xh, W, Yh, C_in, C_out, scale, tiles, tpw);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / ((float)N * (float)N), B * (M / 128), s)) != hipSuccess)
+        return e;
     hipLaunchKernelGGL((k_inv2d<N, K>), dim3((unsigned)(B * C_out)), dim3(256), 0, s, (const c64 *)Yh, y, C_out);
     return hipGetLastError();
 }

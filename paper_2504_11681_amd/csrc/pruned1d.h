@@ -1,0 +1,14 @@
+// Host-visible interface of the unfused 1-D variant with pruned transforms (three kernels).
+#pragma once
+#include "common.h"
+
+namespace tfno {
+
+// N in {64, 128, 256} with K a multiple of 16 such that K/16 divides N/16, or N = 1024 with K in {64, 128}.
+bool pruned1d_supported(int N, int K);
+// Workspace for the truncated spectra of input and output, padded to whole 128-mode tiles.
+size_t pruned1d_workspace_bytes(long long B, int C_in, int C_out, int K);
+hipError_t pruned1d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
+                           c64 *ws, hipStream_t s);
+
+}  // namespace tfno

@@ -1,0 +1,75 @@
+// Instantiations and launcher of the unfused 1-D variant with pruned transforms.
+#include "pruned1d_kernel.h"
+#include "fused2d.h"          // cgemm_modes_launch
+#include "pruned1d.h"
+
+namespace tfno {
+
+bool pruned1d_supported(int N, int K)
+{
+    if (K < 16 || K % 16 != 0 || K > N) return false;
+    const int KH = K / 16;
+    if (N == 1024) return KH == 4 || KH == 8;
+    if (N != 64 && N != 128 && N != 256) return false;
+    const int LPR = N / 16;
+    return (KH & (KH - 1)) == 0 && KH <= LPR;
+}
+
+static long long mode_tiles(long long B, int K) { return (B * K + 127) / 128; }
+
+size_t pruned1d_workspace_bytes(long long B, int C_in, int C_out, int K)
+{
+    return sizeof(c64) * (size_t)mode_tiles(B, K) * 128 * ((size_t)C_in + C_out);
+}
+
+template <int N, int K>
+static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
+                            hipStream_t s)
+{
+    using Cf = CfgP1<N, K>;
+    const long long tiles = mode_tiles(B, K);
+    c64 *Xh = ws, *Yh = ws + (size_t)tiles * 128 * C_in;
+    const long long pin = B * C_in, pout = B * C_out;
+    const long long sin = (pin + Cf::PPS - 1) / Cf::PPS, sout = (pout + Cf::PPS - 1) / Cf::PPS;
+    // a few sweeps per workgroup amortise the twiddle tables and keep a prefetch in flight
+    const unsigned gin = (unsigned)(sin < 1024 ? sin : 1024), gout = (unsigned)(sout < 1024 ? sout : 1024);
+    hipLaunchKernelGGL((k_fwd1d<N, K>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / (float)N, tiles, s)) != hipSuccess) return e;
+    hipLaunchKernelGGL((k_inv1d<N, K>), dim3(gout), dim3(256), 0, s, (const c64 *)Yh, y, C_out, pout);
+    return hipGetLastError();
+}
+
+template <int N>
+static hipError_t launch_n(int K, const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
+                           hipStream_t s)
+{
+    constexpr int LPR = N / 16;
+    switch (K) {
+    case 16: return launch_nk<N, 16>(x, W, y, B, C_in, C_out, ws, s);
+    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32>(x, W, y, B, C_in, C_out, ws, s); break;
+    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64>(x, W, y, B, C_in, C_out, ws, s); break;
+    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128>(x, W, y, B, C_in, C_out, ws, s); break;
+    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256>(x, W, y, B, C_in, C_out, ws, s); break;
+    default: break;
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t pruned1d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
+                           c64 *ws, hipStream_t s)
+{
+    if (!pruned1d_supported(N, K)) return hipErrorInvalidValue;
+    switch (N) {
+    case 64: return launch_n<64>(K, x, W, y, B, C_in, C_out, ws, s);
+    case 128: return launch_n<128>(K, x, W, y, B, C_in, C_out, ws, s);
+    case 256: return launch_n<256>(K, x, W, y, B, C_in, C_out, ws, s);
+    case 1024:
+        if (K == 64) return launch_nk<1024, 64>(x, W, y, B, C_in, C_out, ws, s);
+        return launch_nk<1024, 128>(x, W, y, B, C_in, C_out, ws, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tfno

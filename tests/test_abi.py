@@ -45,7 +45,7 @@ def call(L, name, x, W, y, B, Ci, Co, N, K):
     return getattr(L, name)(x, W, y, B, Ci, Co, N, K, None)
 
 
-@pytest.mark.parametrize("name", binding.EXPORTS[:4])
+@pytest.mark.parametrize("name", binding.EXPORTS[:5])
 def test_argument_errors_are_caught_on_the_host(L, name):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, name, None, W, y, 2, 4, 4, 64, 16) == binding.ERR_NULL
@@ -78,6 +78,11 @@ def test_workspace_contract(L):
     assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 16) == 8 * 2 * 16 * 16 * (3 + 5)
     assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 8) == 8 * 2 * 8 * 64 * (3 + 5)
     assert binding.workspace_bytes(2, True, 2, 3, 5, 64, 16) == 8 * 2 * (3 * 4096 + 3 * 256 + 5 * 256 + 5 * 4096)
+    # pruned 1-D variant: truncated spectra of input and output, joint mode index padded to 128-mode tiles
+    assert binding.workspace_bytes(1, 2, 4, 16, 16, 64, 16) == 8 * 128 * (16 + 16)
+    assert binding.workspace_bytes(1, 2, 256, 128, 128, 1024, 128) == 8 * 256 * 128 * (128 + 128)
+    assert binding.workspace_bytes(1, 2, 4, 16, 16, 64, 48) == 0          # K/16 not a power of two
+    assert binding.workspace_bytes(2, 2, 4, 16, 16, 64, 16) == 0          # 1-D only
     assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)

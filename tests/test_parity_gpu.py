@@ -89,6 +89,34 @@ def test_1d_small(gpu, oracle_mod, fn, shape):
     check(got, want, fn)
 
 
+# unfused variant with pruned transforms (three kernels): narrow path N <= 256, wide path N = 1024
+PRUNED_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 64), (2, 33, 40, 64, 32), (3, 9, 70, 128, 32), (2, 37, 17, 128, 128),
+             (2, 5, 3, 128, 16), (64, 64, 64, 256, 64), (5, 19, 130, 256, 32), (2, 40, 33, 256, 16), (3, 24, 96, 256, 128),
+             (2, 20, 40, 256, 256), (3, 13, 129, 1024, 128), (1, 1, 1, 1024, 64), (2, 20, 30, 1024, 64),
+             (7, 3, 2, 256, 16)]
+
+
+@pytest.mark.parametrize("shape", PRUNED_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_pruned_variant(gpu, oracle_mod, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] spectral_conv1d_pruned {shape}")
+    x = inputs.make_x(300 + N + K, B, Ci, (N,))
+    W = inputs.make_W(300 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    check(run_gpu(gpu, "spectral_conv1d_pruned", x, W, K), want, "pruned")
+
+
+def test_1d_pruned_unsupported_shapes(gpu):
+    torch, binding = gpu
+    for (N, K) in [(512, 64), (1024, 32), (256, 48), (64, 8), (2048, 128)]:
+        x = torch.zeros((1, 2, N), dtype=torch.complex64, device="cuda")
+        W = torch.zeros((2, 2), dtype=torch.complex64, device="cuda")
+        y = torch.zeros((1, 2, N), dtype=torch.complex64, device="cuda")
+        with pytest.raises(binding.TfnoError) as e:
+            binding.spectral_conv1d_pruned(x, W, y, K)
+        assert e.value.status == binding.ERR_UNSUPPORTED, (N, K)
+
+
 STAGED_ONLY_1D = [(2, 3, 4, 2, 1), (2, 3, 4, 4, 3), (3, 6, 5, 32, 5), (2, 4, 4, 2048, 100), (1, 2, 3, 4096, 4096),
                   (2, 5, 3, 256, 48)]
 
@@ -185,7 +213,7 @@ def full_size_case(gpu, oracle_mod, w, fn_name, sample_b):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("fn", ["spectral_conv1d", "spectral_conv1d_staged"])
+@pytest.mark.parametrize("fn", ["spectral_conv1d", "spectral_conv1d_staged", "spectral_conv1d_pruned"])
 def test_config3_full_size(gpu, oracle_mod, fn):
     full_size_case(gpu, oracle_mod, inputs.CONFIGS[2], fn, [0, 101, 255])
 
@@ -199,6 +227,7 @@ def test_config4_full_size(gpu, oracle_mod, fn):
 def test_config5_sweep_full_size(gpu, oracle_mod, w):
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d", [0, 511])
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d_staged", [257])
+    full_size_case(gpu, oracle_mod, w, "spectral_conv1d_pruned", [3, 510])
 
 
 SYM_1D = [(2, 32, 128, 1024, 128),   # two blocks of loads in flight (even block count >= 4), no masks
