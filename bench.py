@@ -105,6 +105,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of one workload, time every cell of the hidden-dimension sweep (B=512, N=256, C in "
+                         "{32,64,128,256}, K in {32,64,128}) with the fused kernel, the unfused pruned variant and the "
+                         "five-kernel staged baseline, and print one JSON line with all cells")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy three times (reads 256 MiB, writes "
                          "256 MiB per launch): the known-size kernel that calibrates rocprofv3's FETCH_SIZE / "
@@ -128,6 +132,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.sweep:
+        from paper_2504_11681_amd import inputs
+        cells = []
+        for w in inputs.sweep_configs():
+            _, dev = measure(w, torch, binding, args.steps, args.warmup)
+            _, pdev = measure(w, torch, binding, args.steps, args.warmup, pruned=True)
+            _, sdev = measure(w, torch, binding, max(5, args.steps // 5), 2, staged=True)
+            cells.append({"workload": w.name, "C": w.C_in, "K": w.K, "fused_us": dev * 1e6, "pruned_us": pdev * 1e6,
+                          "staged_us": sdev * 1e6, "best": "fused" if dev <= pdev else "pruned",
+                          "fused_hbm_frac": w.compulsory_bytes / dev / 1e9 / HBM_PEAK_GBPS,
+                          "fused_contraction_TFLOPs": flops_of(w) / dev / 1e12})
+        print(json.dumps({"metric": "fused_vs_unfused_crossover", "unit": "us per layer (HIP events)", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "dtype": "f32", "data": "synthetic",
+                          "cells": cells}), flush=True)
+        return
 
     w = pick_config(args.config)
     wall, dev = measure(w, torch, binding, args.steps, args.warmup)
