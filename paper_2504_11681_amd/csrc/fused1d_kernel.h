@@ -33,6 +33,7 @@
 #include "common.h"
 #include "fft_regs.h"
 #include "fused1d.h"
+#include "bf16x3.h"
 
 #ifndef TFNO_STAMP
 #define TFNO_STAMP(i)   // phase-timestamp hooks of the development harness; empty in the library
@@ -52,7 +53,9 @@ template <> struct Decomp<256>  { static constexpr int P = 16, T = 16; };
 template <> struct Decomp<512>  { static constexpr int P = 32, T = 16; };
 template <> struct Decomp<1024> { static constexpr int P = 32, T = 32; };
 
-template <int N, int K, int OT>
+// BF: the contraction runs on the BF16 matrix pipe with the exact three-term operand split (bf16x3.h) instead of
+// FP32 MFMA; the operand tile then holds packed BF16 terms, [term][channel / 4][mode tile][mode % 32][channel % 4].
+template <int N, int K, int OT, bool BF = false>
 struct FusedCfg {
     static constexpr int P = Decomp<N>::P, T = Decomp<N>::T;
     static constexpr int Q = K / P;                 // retained outputs per column of stage B
@@ -70,7 +73,8 @@ struct FusedCfg {
     static constexpr int ZROW = T + 1;
     static constexpr int ZS = P * ZROW + (T == 8 ? 8 - (P * ZROW) % 16 + ((P * ZROW) % 16 > 8 ? 16 : 0) : 0);
     static constexpr int YROW = K + 1;
-    static constexpr int XH_BUF = PPI * 2 * KPAD;   // floats per XH buffer
+    static constexpr int XH_BUF = BF ? 3 * (PPI / 4) * KT * 128 : PPI * 2 * KPAD;   // 4-byte words per XH buffer
+    static constexpr int NWV = BF ? PPI / 2 : PPI;  // W values a lane holds per iteration
     static constexpr size_t LDS_Z = sizeof(c64) * NW * PPW * ZS;
     static constexpr size_t LDS_XH = sizeof(float) * 2 * XH_BUF;
     static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * 32 * YROW;
@@ -79,9 +83,10 @@ struct FusedCfg {
     static constexpr size_t LDS_BYTES = LDS_DYN + LDS_TW;
     static_assert(K % P == 0 && Q >= 1 && Q <= T && T % Q == 0, "K must be a multiple of P that divides N");
     static_assert(8 % PPW == 0, "a wave inverts 8 rows of a 32-output slab");
+    static_assert(PPI % 8 == 0, "an iteration is a whole number of 8-channel MFMA steps");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
     static_assert(TPW * 32 <= 128, "accumulators must fit the register file");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one gfx950 CU");
+    static constexpr bool FITS = LDS_BYTES <= 160 * 1024;           // LDS budget of one gfx950 CU
 };
 
 // Orders this wave's LDS traffic (all lanes) without a workgroup barrier.
@@ -93,11 +98,13 @@ __device__ __forceinline__ void wave_sync()
 }
 
 // EVEN: C_in is a multiple of PPI and C_out a multiple of 32, so no load or store needs a mask.
-template <int N, int K, int OT, bool EVEN>
+template <int N, int K, int OT, bool EVEN, bool BF>
 __global__ void __launch_bounds__(256)
 k_fused1d(Fused1dArgs a)
 {
-    using C = FusedCfg<N, K, OT>;
+    using C = FusedCfg<N, K, OT, BF>;
+    static_assert(C::FITS, "LDS budget of one gfx950 CU");
+    constexpr int NWV = C::NWV;
     constexpr int P = C::P, T = C::T, Q = C::Q, PPW = C::PPW, PPI = C::PPI, CPL = C::CPL, KT = C::KT;
     constexpr int KPAD = C::KPAD, TPW = C::TPW, ZROW = C::ZROW, ZS = C::ZS, YROW = C::YROW, NT = C::NT;
     constexpr bool ALLT = C::ALLT;
@@ -142,7 +149,12 @@ k_fused1d(Fused1dArgs a)
     const int n_it = (a.C_in + PPI - 1) / PPI;
 
     c64 v[P];       // the pencil slice this lane transforms next
-    c64 wv[PPI];    // W[c][o_lane] for the channels of the iteration whose MFMAs run next
+    // W[c][o_lane] for the channels of the iteration whose MFMAs run next: all PPI of them (FP32 MFMA), or, for
+    // the BF16 path, the four channels 8 s + 4 (lane / 32) + d of every 8-channel step s, at index 4 s + d
+    c64 wv[NWV];
+    auto wv_channel = [&](int i) __attribute__((always_inline)) {
+        return BF ? 8 * (i / 4) + 4 * (lane >> 5) + (i % 4) : i;
+    };
 
     auto load_pencil = [&](int c0) __attribute__((always_inline)) {
         const int c = c0 + ja;
@@ -162,8 +174,8 @@ k_fused1d(Fused1dArgs a)
     };
     auto load_w = [&](c64 *dst, int c0) __attribute__((always_inline)) {
 #pragma unroll
-        for (int jc = 0; jc < PPI; ++jc) {
-            const int c = c0 + jc;
+        for (int jc = 0; jc < NWV; ++jc) {
+            const int c = c0 + wv_channel(jc);
             if constexpr (EVEN && ALLT) {
                 dst[jc] = a.W[(long long)c * a.C_out + o_lane];
             } else {
@@ -195,25 +207,75 @@ k_fused1d(Fused1dArgs a)
                 else return cmul(zcol[tt], TW[tt * P + p]);
             }, xo);
             const int jg = wave * PPW + j;
+            if constexpr (BF) {
+                unsigned *XS = reinterpret_cast<unsigned *>(XHb) + (jg >> 2) * (KT * 128) + (jg & 3);
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                XHb[(jg * 2 + 0) * KPAD + p + P * q] = xo[q].x;
-                XHb[(jg * 2 + 1) * KPAD + p + P * q] = xo[q].y;
+                for (int q = 0; q < Q; ++q) {
+                    const int k = p + P * q;
+                    const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
+                    unsigned *d = XS + (k >> 5) * 128 + (k & 31) * 4;
+                    d[0 * (PPI / 4) * KT * 128] = pack_bf16(re.t0, im.t0);
+                    d[1 * (PPI / 4) * KT * 128] = pack_bf16(re.t1, im.t1);
+                    d[2 * (PPI / 4) * KT * 128] = pack_bf16(re.t2, im.t2);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    XHb[(jg * 2 + 0) * KPAD + p + P * q] = xo[q].x;
+                    XHb[(jg * 2 + 1) * KPAD + p + P * q] = xo[q].y;
+                }
             }
         }
     };
     // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)
     auto mfma_block = [&](int buf) __attribute__((always_inline)) {
         const float *XHb = XH + buf * C::XH_BUF;
+        if constexpr (BF) {
+            // 8 channels per v_mfma_f32_32x32x16_bf16: lanes 0-31 carry channels 0-3 of the step, lanes 32-63
+            // channels 4-7, dword d = (re | im << 16) of channel 4 g + d.  Six products per tile and part; the
+            // accumulators of the wave's tiles are interleaved (a dependent MFMA issues about four slots later).
+            const unsigned *XS = reinterpret_cast<const unsigned *>(XHb) + (hi ? 1 : 0) * (KT * 128) + kt0 * 128 + (lane & 31) * 4;
 #pragma unroll
-        for (int jc = 0; jc < PPI; ++jc) {
-            const float a_re = (hi ? -wv[jc].y : wv[jc].x) * a.scale;
-            const float a_im = (hi ? wv[jc].x : wv[jc].y) * a.scale;
+            for (int s = 0; s < PPI / 8; ++s) {
+                uintx4 a_re[3], a_im[3];
 #pragma unroll
-            for (int i = 0; i < TPW; ++i) {
-                const float bx = XHb[(jc * 2 + (hi ? 1 : 0)) * KPAD + 32 * (kt0 + i) + (lane & 31)];
-                acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re, bx, acc_re[i], 0, 0, 0);
-                acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im, bx, acc_im[i], 0, 0, 0);
+                for (int d = 0; d < 4; ++d) {
+                    const Split3 re = split3(wv[4 * s + d].x * a.scale), im = split3(wv[4 * s + d].y * a.scale);
+                    a_re[0][d] = pack_bf16(re.t0, im.t0) ^ 0x80000000u;
+                    a_re[1][d] = pack_bf16(re.t1, im.t1) ^ 0x80000000u;
+                    a_re[2][d] = pack_bf16(re.t2, im.t2) ^ 0x80000000u;
+                    a_im[0][d] = pack_bf16(im.t0, re.t0);
+                    a_im[1][d] = pack_bf16(im.t1, re.t1);
+                    a_im[2][d] = pack_bf16(im.t2, re.t2);
+                }
+                uintx4 b[TPW][3];
+#pragma unroll
+                for (int i = 0; i < TPW; ++i)
+#pragma unroll
+                    for (int t = 0; t < 3; ++t)
+                        b[i][t] = *reinterpret_cast<const uintx4 *>(XS + ((t * (PPI / 4) + 2 * s) * KT + i) * 128);
+                // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
+                constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+                for (int k = 0; k < 6; ++k)
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) {
+                        const bf16x8 bb16 = __builtin_bit_cast(bf16x8, b[i][SB[k]]);
+                        acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb16, acc_re[i], 0, 0, 0);
+                        acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[i], 0, 0, 0);
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int jc = 0; jc < PPI; ++jc) {
+                const float a_re = (hi ? -wv[jc].y : wv[jc].x) * a.scale;
+                const float a_im = (hi ? wv[jc].x : wv[jc].y) * a.scale;
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const float bx = XHb[(jc * 2 + (hi ? 1 : 0)) * KPAD + 32 * (kt0 + i) + (lane & 31)];
+                    acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re, bx, acc_re[i], 0, 0, 0);
+                    acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im, bx, acc_im[i], 0, 0, 0);
+                }
             }
         }
     };
@@ -223,7 +285,7 @@ k_fused1d(Fused1dArgs a)
     auto step = [&](auto do_b, auto do_a, auto do_load, int it) __attribute__((always_inline)) {
         constexpr bool DO_B = decltype(do_b)::value, DO_A = decltype(do_a)::value, DO_LOAD = decltype(do_load)::value;
         const int cur = it & 1;
-        c64 wn[PPI];
+        c64 wn[NWV];
         TFNO_STEP_STAMP(it, 0);
         if constexpr (DO_B) load_w(wn, (it + 1) * PPI);
         if constexpr (ALLT) mfma_block(cur);
@@ -237,7 +299,7 @@ k_fused1d(Fused1dArgs a)
         TFNO_STEP_STAMP(it, 4);
         if constexpr (DO_B) {
 #pragma unroll
-            for (int jc = 0; jc < PPI; ++jc) wv[jc] = wn[jc];
+            for (int jc = 0; jc < NWV; ++jc) wv[jc] = wn[jc];
             __syncthreads();
         }
         TFNO_STEP_STAMP(it, 5);
@@ -370,26 +432,37 @@ k_fused1d(Fused1dArgs a)
     TFNO_STAMP(3);
 }
 
-template <int N, int K, int OT>
-hipError_t launch_fused1d(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
+template <int N, int K, int OT, bool BF>
+hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
-    using C = FusedCfg<N, K, OT>;
+    using C = FusedCfg<N, K, OT, BF>;
     static bool attr_done = false;   // benign race: every thread sets the same value
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
     if (a.C_in % C::PPI == 0 && a.C_out % 32 == 0)
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, true>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF>), grid, dim3(256), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, false>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF>), grid, dim3(256), C::LDS_DYN, s, a);
     return hipGetLastError();
+}
+
+// BF16x3 contraction unless the environment asks for FP32 MFMA (TFNO_CONTRACTION=f32)
+template <int N, int K, int OT>
+hipError_t launch_fused1d(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
+{
+    // (the packed three-term operand tile is 1.5x the FP32 one; the largest shapes only fit with FP32 operands)
+    if constexpr (FusedCfg<N, K, OT, true>::FITS) {
+        if (!contraction_forced_f32()) return launch_fused1d_impl<N, K, OT, true>(a, batch_rows, s);
+    }
+    return launch_fused1d_impl<N, K, OT, false>(a, batch_rows, s);
 }
 
 }  // namespace tfno
