@@ -6,6 +6,8 @@
 A step is one pass of the whole hot path (load, pruned forward FFT, truncation, CGEMM over the hidden
 dimension, zero padding, pruned inverse FFT, store) over one batch of synthetic input that is already
 resident in HBM.  The default workload is the 1-D production shape (B=256, C=128, N=1024, K=128).
+Successive steps rotate through a pool of identical (x, y) buffer pairs larger than the last-level cache, so
+every step reads its input from HBM and no step overwrites output lines still cached from an earlier one.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -41,9 +43,22 @@ def device_inputs(w, torch):
     return xd, Wd, yd
 
 
-def time_calls(torch, fn, steps: int, warmup: int):
+RAMP_SECONDS = 0.3   # the engine clock needs ~0.1 s of continuous work to climb from its idle state to the sustained one
+
+
+def time_calls(torch, fn, steps: int, warmup: int, ramp: float = RAMP_SECONDS):
     """Returns (wall seconds for `steps` calls, mean per-call device time in seconds from HIP events
-    recorded on the stream the kernels are launched on)."""
+    recorded on the stream the kernels are launched on).
+
+    Before the `warmup` untimed calls the same call is repeated for `ramp` seconds: a GPU that has been idle sits
+    in a low-power state (engine clock near 100 MHz) and reaches its sustained clock (about 2.25 GHz under this
+    load) only after some tens of milliseconds of work, so a short run started from idle reports the clock ramp,
+    not the kernel (measured: 139 us per layer over 60 calls from idle, 119 us sustained)."""
+    t_end = time.perf_counter() + ramp
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -65,16 +80,31 @@ def flops_of(w):
     return 8.0 * w.B * (w.K ** w.dims) * w.C_in * w.C_out
 
 
+def buffer_sets(w):
+    """Number of (x, y) buffer pairs the timed launches rotate through: enough that one round of the pool is
+    at least 1 GiB, four times the 256 MB last-level cache, so that no launch finds its input or the lines of
+    its output left there by an earlier launch."""
+    pair = 16 * w.B * (w.C_in + w.C_out) * (w.N ** w.dims) // 2
+    return max(2, min(64, -(-(1 << 30) // pair)))
+
+
 def measure(w, torch, binding, steps, warmup, staged=False, pruned=False):
     xd, Wd, yd = device_inputs(w, torch)
+    sets = [(xd, yd)] + [(xd.clone(), torch.zeros_like(yd)) for _ in range(buffer_sets(w) - 1)]
     variant = 2 if pruned else 1 if staged else 0
     name = ("spectral_conv%dd" % w.dims) + ("", "_staged", "_pruned")[variant]
     fn = getattr(binding, name)
     binding.ensure_workspace(binding.workspace_bytes(w.dims, variant, w.B, w.C_in, w.C_out, w.N, w.K), xd.device)
     stream = torch.cuda.current_stream().cuda_stream
-    call = lambda: fn(xd, Wd, yd, w.K, stream)
+    turn = [0]
+
+    def call():
+        xi, yi = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        fn(xi, Wd, yi, w.K, stream)
+
     wall, dev = time_calls(torch, call, steps, warmup)
-    del xd, Wd, yd
+    del xd, Wd, yd, sets
     torch.cuda.empty_cache()
     return wall, dev
 
@@ -101,8 +131,8 @@ def cpu_baseline(w):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
     ap.add_argument("--sweep", action="store_true",
@@ -139,7 +169,7 @@ def main():
         for w in inputs.sweep_configs():
             _, dev = measure(w, torch, binding, args.steps, args.warmup)
             _, pdev = measure(w, torch, binding, args.steps, args.warmup, pruned=True)
-            _, sdev = measure(w, torch, binding, max(5, args.steps // 5), 2, staged=True)
+            _, sdev = measure(w, torch, binding, max(5, args.steps // 10), 2, staged=True)
             cells.append({"workload": w.name, "C": w.C_in, "K": w.K, "fused_us": dev * 1e6, "pruned_us": pdev * 1e6,
                           "staged_us": sdev * 1e6, "best": "fused" if dev <= pdev else "pruned",
                           "fused_hbm_frac": w.compulsory_bytes / dev / 1e9 / HBM_PEAK_GBPS,
@@ -174,6 +204,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
+        "buffer_sets": buffer_sets(w),
+        "clock_ramp_s": RAMP_SECONDS,
         "config": {"workload": w.name, "dims": w.dims, "B": w.B, "C_in": w.C_in, "C_out": w.C_out,
                    "N": w.N, "K": w.K, "seed": w.seed, "entry_point": "tfno_spectral_conv%dd" % w.dims},
         "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
@@ -186,14 +218,14 @@ def main():
     }
 
     if not args.no_extras:
-        s_steps = max(5, args.steps // 5)
+        s_steps = max(5, args.steps // 10)
         swall, sdev = measure(w, torch, binding, s_steps, 2, staged=True)
         out["staged"] = {"ms_per_step": swall / s_steps * 1e3, "layers_per_s": s_steps / swall,
                          "variant": "five kernels: full FFT, truncate copy, CGEMM, pad copy, full iFFT",
                          "fused_speedup": (swall / s_steps) / (wall / args.steps)}
         if w.name.startswith("cfg3"):
             w4 = pick_config("cfg4")
-            steps4 = max(10, args.steps // 2)
+            steps4 = max(10, args.steps // 4)
             wall4, dev4 = measure(w4, torch, binding, steps4, 5)
             traffic4 = None
             if os.path.exists(tpath):

@@ -159,14 +159,16 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
 {
     if (!fused1d_supported(N, K)) return hipErrorInvalidValue;
     if (!contraction_forced_f32()) {
-        // N = 1024 has two kernels; the wave-specialised one measures 5 % faster on the production shape, so the
-        // symmetric one only runs when TFNO_KERNEL=sym asks for it
-        static const bool prefer_sym = [] {
+        // N = 1024 has three kernels: the wave-specialised one is the default; TFNO_KERNEL=sym selects the
+        // symmetric-wave kernel, TFNO_KERNEL=generic the four-wave kernel every other N uses
+        static const int which = [] {
             const char *e = getenv("TFNO_KERNEL");
-            return e && e[0] == 's' && e[1] == 'y' && e[2] == 'm' && e[3] == 0;
+            if (e && e[0] == 's' && e[1] == 'y' && e[2] == 'm' && e[3] == 0) return 1;
+            if (e && e[0] == 'g' && e[1] == 'e' && e[2] == 'n') return 2;
+            return 0;
         }();
-        if (prefer_sym && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
-        if (fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
+        if (which == 1 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
+        if (which != 2 && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
     }
     switch (N) {
     case 64: return fused1d_launch_n64(K, a, rows, s);

@@ -101,23 +101,31 @@ TFNO_HD void dif_first_level(const c64 *v, c64 *a, c64 *b)
 // out[q] = sum_{t<T} in(t) exp(DIR 2 pi i t q / T),  q < Q,  Q | T.     in: callable int -> c64
 // t = t1 + S t2 (S = T/Q):  S full Q-point transforms of the decimated input, then a twiddled S-term sum.
 // The input is consumed Q values at a time, so a caller that reads it from LDS keeps only one group live.
+// One group of the network: g = inputs t1, t1 + S, ..., t1 + (Q-1) S (destroyed); adds its share to out.
+template <int T, int Q, int DIR, int T1>
+TFNO_HD void dft_prune_out_group(c64 *g, c64 *out)
+{
+    c64 F[Q];
+    RegFFT<Q, DIR, 1>::run(g, F);
+    static_for<0, Q>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        if constexpr (T1 == 0) out[q] = F[q];
+        else out[q] = mac_tw<T, DIR, T1 * q>(out[q], F[q]);
+    });
+}
+
 template <int T, int Q, int DIR, class In>
 TFNO_HD void dft_prune_out(In &&in, c64 *out)
 {
     constexpr int S = T / Q;
     static_for<0, S>([&](auto t1c) {
         constexpr int t1 = decltype(t1c)::value;
-        c64 g[Q], F[Q];
+        c64 g[Q];
         static_for<0, Q>([&](auto t2c) {
             constexpr int t2 = decltype(t2c)::value;
             g[t2] = in(std::integral_constant<int, t1 + S * t2>{});
         });
-        RegFFT<Q, DIR, 1>::run(g, F);
-        static_for<0, Q>([&](auto qc) {
-            constexpr int q = decltype(qc)::value;
-            if constexpr (t1 == 0) out[q] = F[q];
-            else out[q] = mac_tw<T, DIR, t1 * q>(out[q], F[q]);
-        });
+        dft_prune_out_group<T, Q, DIR, t1>(g, out);
     });
 }
 

@@ -362,7 +362,7 @@ k_fused1d(Fused1dArgs a)
         if (EVEN || o < a.C_out) {
             c64 *dst = yb + (long long)o * a.y_chan_stride + t;
 #pragma unroll
-            for (int jj = 0; jj < P; ++jj) dst[T * jj] = r[jj];
+            for (int jj = 0; jj < P; ++jj) store_nt(dst + T * jj, r[jj]);
         }
     };
 

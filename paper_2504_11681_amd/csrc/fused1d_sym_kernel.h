@@ -334,7 +334,7 @@ k_fused1d_sym(Fused1dArgs a)
         if (EVEN || o < a.C_out) {
             c64 *dst = yb + (long long)o * a.y_chan_stride + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) dst[64 * j] = res[j];
+            for (int j = 0; j < 16; ++j) store_nt(dst + 64 * j, res[j]);
         }
     }
     TFNO_STAMP(3);

@@ -38,6 +38,8 @@
 #define TFNO_WS_STAMP(role, it, i)   // development hook, empty in the library
 #endif
 
+#include <type_traits>
+
 namespace tfno {
 
 
@@ -72,7 +74,11 @@ k_fused1d_ws(Fused1dArgs a)
     __shared__ c64 TW[N];                                                     // [t][p]: w_N^(t p)
 
     const int tid = threadIdx.x;
+#ifdef TFNO_DBG_M_FIRST
+    const int lane = tid & 63, wave = (tid >> 6) ^ 4;       // hardware waves 0-3 take the M role
+#else
     const int lane = tid & 63, wave = tid >> 6;
+#endif
     const int bb = blockIdx.x;
     const int o_base = blockIdx.y * 128;
 
@@ -88,8 +94,8 @@ k_fused1d_ws(Fused1dArgs a)
     // 8-byte slots, with no padding.
 
     if (wave < 4) {
-        // ================================================================== F waves: global memory + row stage
-        const int ztile = (wave * 2 + h) * ZS;
+        // ============================================= F waves: global memory, both stages of the forward transform
+        const int ztile = (wave * 2 + h) * ZS;  // this half-wave's pencil tile: only this half-wave touches it in the k-loop
         const int ja = wave * 2 + h;            // channel of this lane within the iteration's 8
         c64 v[P];
 
@@ -109,40 +115,96 @@ k_fused1d_ws(Fused1dArgs a)
                 }
             }
         };
-        // stage A: 32-point transform of the slice in v, written transposed into Z buffer `zb`.  The first
-        // butterfly level consumes v, so the loads of block `next_c0` (if >= 0) are issued right after it and
-        // stay in flight for a whole iteration while the two 16-point halves run.
-        auto stage_a = [&](int zb, int next_c0) __attribute__((always_inline)) {
+        // Row stage: 32-point transform of the slice in v, written transposed into the pencil's Z tile.  The first
+        // butterfly level consumes v, so the loads of the next block are issued right after it and stay in flight
+        // for a whole iteration.  The refill is a compile-time choice (`refill` is std::true_type or
+        // std::false_type): a run-time condition around the loads would make v a merge of old and new values, which
+        // the compiler resolves by loading into spare registers and copying them at the end of the iteration after
+        // waiting for the data, and that wait exposes the whole memory latency in every iteration.
+        auto row_stage = [&](auto refill, int next_c0) __attribute__((always_inline)) {
             c64 ea[P / 2], eb[P / 2], za[P / 2], zo[P / 2];
             dif_first_level<P, -1>(v, ea, eb);
             // keep the refill right here: the scheduler must not sink these loads below the butterflies
             __builtin_amdgcn_sched_barrier(0);
-            if (next_c0 >= 0) load_pencil(next_c0);
+            if constexpr (decltype(refill)::value) load_pencil(next_c0);
             __builtin_amdgcn_sched_barrier(0);
             RegFFT<P / 2, -1, 1>::run(ea, za);
             RegFFT<P / 2, -1, 1>::run(eb, zo);
-            c64 *Zt = Zl + zb * C::Z_BUF + ztile;
+            c64 *Zt = Zl + ztile;
 #pragma unroll
             for (int k = 0; k < P / 2; ++k) {
                 Zt[(2 * k) * 32 + (p ^ (2 * k))] = za[k];
                 Zt[(2 * k + 1) * 32 + (p ^ (2 * k + 1))] = zo[k];
             }
         };
+        // Column stage of the same pencil, by the same half-wave (LDS operations of one wave complete in order, so
+        // no barrier separates it from the row stage): twiddle, column transform pruned to Q outputs (Sec. 3.3),
+        // exact BF16 split, into XS[xbuf].  The LDS reads are issued well ahead of their use, the column all at once
+        // and the twiddles two groups ahead of the group being combined: left to itself the compiler waits after
+        // every pair of reads, and 32 exposed LDS round trips cost more than all the arithmetic here.
+        auto col_stage = [&](int xbuf) __attribute__((always_inline)) {
+            constexpr int S = T / Q;                        // groups; group t1 holds inputs t1 + S t2
+            const c64 *zcol = Zl + ztile + p * 32;          // row p of the tile = column p of the pencil
+            const c64 *twp = TW + p;
+            c64 zc[T], tw[T], xo[Q];
+            auto read_tw = [&](auto t1c) __attribute__((always_inline)) {
+                constexpr int t1 = decltype(t1c)::value;
+#pragma unroll
+                for (int t2 = 0; t2 < Q; ++t2)
+                    if (t1 + S * t2 != 0) tw[t1 + S * t2] = twp[(t1 + S * t2) * P];
+            };
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt) zc[(tt % Q) * S + tt / Q] = zcol[((tt % Q) * S + tt / Q) ^ p];   // group order
+            read_tw(std::integral_constant<int, 0>{});
+            if constexpr (S > 1) read_tw(std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, S>([&](auto t1c) {
+                constexpr int t1 = decltype(t1c)::value;
+                if constexpr (t1 + 2 < S) read_tw(std::integral_constant<int, t1 + 2>{});
+                c64 g[Q];
+#pragma unroll
+                for (int t2 = 0; t2 < Q; ++t2) {
+                    const int tt = t1 + S * t2;
+                    g[t2] = tt == 0 ? zc[0] : cmul(zc[tt], tw[tt]);
+                }
+                dft_prune_out_group<T, Q, -1, t1>(g, xo);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            unsigned *dst = XS + xbuf * C::XS_BUF + (wave * 32 + p) * 2 + h;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
+                dst[(0 * Q + q) * 256] = pack_bf16(re.t0, im.t0);
+                dst[(1 * Q + q) * 256] = pack_bf16(re.t1, im.t1);
+                dst[(2 * Q + q) * 256] = pack_bf16(re.t2, im.t2);
+            }
+        };
+        constexpr std::true_type refill{};
+        constexpr std::false_type last{};
 
+        // Block j reaches XS[j & 1] before barrier number j + 2 (P1, P2, then one barrier per loop iteration); the
+        // loads of block j + 1 are issued inside the row stage of block j.
         load_pencil(0);
-        stage_a(0, n_it > 1 ? PPI : -1);
-        __syncthreads();                                    // P1: Z[0] holds block 0
-        if (n_it > 1) stage_a(1, n_it > 2 ? 2 * PPI : -1);
-        __syncthreads();                                    // P2
+        if (n_it > 1) row_stage(refill, PPI); else row_stage(last, 0);
+        __syncthreads();                                    // P1: the M waves have built the twiddle table
+        col_stage(0);
+        __syncthreads();                                    // P2: XS[0] holds block 0
         TFNO_STAMP(1);
-        for (int it = 0; it + 1 < n_it; ++it) {
+        int it = 0;
+        for (; it + 2 < n_it; ++it) {                       // blocks 1 .. n_it - 2, each refilling v with its successor
             TFNO_WS_STAMP(0, it, 0);
 #ifndef TFNO_DBG_NO_F
-            if (it + 2 < n_it) stage_a(it & 1, it + 3 < n_it ? (it + 3) * PPI : -1);
+            row_stage(refill, (it + 2) * PPI);
+            col_stage((it + 1) & 1);
 #endif
             TFNO_WS_STAMP(0, it, 1);
             __syncthreads();
             TFNO_WS_STAMP(0, it, 2);
+        }
+        if (it + 1 < n_it) {                                // the last block: nothing left to load
+            row_stage(last, 0);
+            col_stage((it + 1) & 1);
+            __syncthreads();
         }
         TFNO_STAMP(2);
         // epilogue: stage A' of the pencil the M wave (wave + 4) left in Z[r & 1], coalesced store
@@ -157,7 +219,7 @@ k_fused1d_ws(Fused1dArgs a)
             if (EVEN || o < a.C_out) {
                 c64 *dst = yb + (long long)o * a.y_chan_stride + p;
 #pragma unroll
-                for (int jj = 0; jj < P; ++jj) dst[T * jj] = res[jj];
+                for (int jj = 0; jj < P; ++jj) store_nt(dst + T * jj, res[jj]);
             }
         }
         TFNO_STAMP(3);
@@ -166,6 +228,9 @@ k_fused1d_ws(Fused1dArgs a)
 
     // ====================================================================== M waves: column stage + matrix pipe
     const int m = wave - 4;
+#ifdef TFNO_DBG_M_PRIO
+    __builtin_amdgcn_s_setprio(TFNO_DBG_M_PRIO);
+#endif
     const int o_lane = o_base + 32 * m + p;     // the output channel whose W this lane feeds
     const int ztile = (m * 2 + h) * ZS + p * 32;            // row p of the tile = column p of the pencil
     floatx16 acc_re[Q], acc_im[Q];
@@ -202,25 +267,6 @@ k_fused1d_ws(Fused1dArgs a)
             a_im[2][d] = pack_bf16(im.t2, re.t2);
         }
     };
-    // stage B of the pencil F wave m left in Z buffer zb: twiddle, column transform pruned to Q outputs
-    // (Sec. 3.3), exact BF16 split, into XS[xb]
-    auto stage_b = [&](int zb, int xbuf) __attribute__((always_inline)) {
-        const c64 *zcol = Zl + zb * C::Z_BUF + ztile;
-        c64 xo[Q];
-        dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
-            constexpr int tt = decltype(ttc)::value;
-            if constexpr (tt == 0) return zcol[p];
-            else return cmul(zcol[tt ^ p], TW[tt * P + p]);
-        }, xo);
-        unsigned *dst = XS + xbuf * C::XS_BUF + (m * 32 + p) * 2 + h;
-#pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
-            dst[(0 * Q + q) * 256] = pack_bf16(re.t0, im.t0);
-            dst[(1 * Q + q) * 256] = pack_bf16(re.t1, im.t1);
-            dst[(2 * Q + q) * 256] = pack_bf16(re.t2, im.t2);
-        }
-    };
     auto mfma_block = [&](int buf) __attribute__((always_inline)) {
         // lane (n = p, g = h) needs dwords [wave 2g][n][0..1] and [wave 2g+1][n][0..1] of every (term, q)
         const unsigned *src = XS + buf * C::XS_BUF + (2 * h * 32 + p) * 2;
@@ -233,7 +279,8 @@ k_fused1d_ws(Fused1dArgs a)
                 const uint2 hi2 = *reinterpret_cast<const uint2 *>(src + (s * Q + q) * 256 + 64);
                 b[s][0] = lo.x; b[s][1] = lo.y; b[s][2] = hi2.x; b[s][3] = hi2.y;
             }
-            // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
+            // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0).  Real and imaginary accumulators
+            // alternate; the matrix pipe runs one instruction at a time, so two chains already keep it busy.
             constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
 #pragma unroll
             for (int k = 0; k < 6; ++k) {
@@ -246,11 +293,10 @@ k_fused1d_ws(Fused1dArgs a)
 
     // the twiddle table is only read by the column stage, so the M waves build it (accurate sincospi) while
     // the F waves already stream the first pencils; barrier P1 publishes it
-    for (int i = tid - 256; i < N; i += 256) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
+    for (int i = (wave - 4) * 64 + lane; i < N; i += 256) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
     load_w(0);
     split_w();
     __syncthreads();                                        // P1
-    stage_b(0, 0);
     __syncthreads();                                        // P2: XS[0] holds block 0
     for (int it = 0; it < n_it; ++it) {
         const bool more = it + 1 < n_it;
@@ -261,10 +307,6 @@ k_fused1d_ws(Fused1dArgs a)
 #endif
         TFNO_WS_STAMP(1, it, 1);
         if (more) {
-#ifndef TFNO_DBG_NO_STAGEB
-            stage_b((it + 1) & 1, (it + 1) & 1);
-#endif
-            TFNO_WS_STAMP(1, it, 2);
             split_w();
             TFNO_WS_STAMP(1, it, 3);
             __syncthreads();

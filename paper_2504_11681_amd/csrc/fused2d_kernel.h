@@ -340,7 +340,7 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
         const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
         c64 *dst = img + (long long)(r + S * s) * N + p;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) dst[LPR * j] = out[j];
+        for (int j = 0; j < 16; ++j) store_nt(dst + LPR * j, out[j]);
     };
 
     __syncthreads();                                        // twiddle tables are ready

@@ -264,7 +264,7 @@ k_inv1d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C, long long npenci
         if (q < npencils) {
             c64 *dst = y + q * N + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) dst[LPR * j] = res[j];
+            for (int j = 0; j < 16; ++j) store_nt(dst + LPR * j, res[j]);
         }
     };
 
