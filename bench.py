@@ -213,7 +213,7 @@ def main():
         "contraction_TFLOPs": flops_of(w) / dev / 1e12,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "fused 1-D kernel (k_fused1d_ws / k_fused1d)" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
+                     "kernel": "fused 1-D kernel (k_fused1d_sym for N = 1024, K in {64, 128}; k_fused1d_ws / k_fused1d otherwise)" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": dev * 1e3},
     }
 

@@ -159,15 +159,16 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
 {
     if (!fused1d_supported(N, K)) return hipErrorInvalidValue;
     if (!contraction_forced_f32()) {
-        // N = 1024 has three kernels: the wave-specialised one is the default; TFNO_KERNEL=sym selects the
-        // symmetric-wave kernel, TFNO_KERNEL=generic the four-wave kernel every other N uses
+        // N = 1024 has three kernels.  Default: the symmetric-wave kernel where it exists (K in {64, 128}; the
+        // fastest at the sustained clock), else the wave-specialised one.  TFNO_KERNEL=ws forces the
+        // wave-specialised kernel, TFNO_KERNEL=generic the four-wave kernel every other N uses.
         static const int which = [] {
             const char *e = getenv("TFNO_KERNEL");
-            if (e && e[0] == 's' && e[1] == 'y' && e[2] == 'm' && e[3] == 0) return 1;
+            if (e && e[0] == 'w' && e[1] == 's' && e[2] == 0) return 1;
             if (e && e[0] == 'g' && e[1] == 'e' && e[2] == 'n') return 2;
             return 0;
         }();
-        if (which == 1 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
+        if (which == 0 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
         if (which != 2 && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
     }
     switch (N) {

@@ -112,13 +112,13 @@ k_fused1d_sym(Fused1dArgs a)
         if constexpr (EVEN) {
             const c64 *src = xb + (long long)c * a.x_chan_stride + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] = src[64 * j];
+            for (int j = 0; j < 16; ++j) v[j] = load_nt(src + 64 * j);
         } else {
             const bool ok = c < a.C_in;
             const c64 *src = xb + (long long)(ok ? c : 0) * a.x_chan_stride + p;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                c64 val = src[64 * j];
+                c64 val = load_nt(src + 64 * j);
                 v[j] = ok ? val : make_float2(0.f, 0.f);
             }
         }

@@ -237,13 +237,15 @@ SYM_1D = [(2, 32, 128, 1024, 128),   # two blocks of loads in flight (even block
           (1, 1, 1, 1024, 64)]
 
 
-def test_symmetric_kernel_in_a_child_process(gpu, oracle_mod, tmp_path):
-    """TFNO_KERNEL=sym (read once per process) selects the symmetric-wave kernel for N = 1024, K in {64, 128}."""
+@pytest.mark.parametrize("kernel", ["ws", "generic"])
+def test_alternative_n1024_kernels_in_a_child_process(gpu, oracle_mod, tmp_path, kernel):
+    """N = 1024 runs the symmetric-wave kernel by default (K in {64, 128}); TFNO_KERNEL (read once per process)
+    selects the wave-specialised kernel (ws) or the generic four-wave kernel (generic) instead."""
     import os
     import subprocess
     import textwrap
-    say("[case] TFNO_KERNEL=sym child process")
-    out = str(tmp_path / "sym.npz")
+    say(f"[case] TFNO_KERNEL={kernel} child process")
+    out = str(tmp_path / f"{kernel}.npz")
     code = textwrap.dedent(f"""
         import numpy as np, torch
         from paper_2504_11681_amd import binding, inputs
@@ -256,13 +258,13 @@ def test_symmetric_kernel_in_a_child_process(gpu, oracle_mod, tmp_path):
             res['y%d' % i] = y.cpu().numpy()
         np.savez({out!r}, **res)
     """)
-    env = dict(os.environ, TFNO_KERNEL="sym")
+    env = dict(os.environ, TFNO_KERNEL=kernel)
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     subprocess.run([sys.executable, "-c", code], check=True, env=env, cwd=root, timeout=110)
     got = np.load(out)
     for i, (B, Ci, Co, N, K) in enumerate(SYM_1D):
         x = inputs.make_x(40 + i, B, Ci, (N,)); W = inputs.make_W(40 + i, Ci, Co)
-        check(got["y%d" % i], oracle_mod.spectral_conv1d(x, W, K)[0], f"sym {(B, Ci, Co, N, K)}")
+        check(got["y%d" % i], oracle_mod.spectral_conv1d(x, W, K)[0], f"{kernel} {(B, Ci, Co, N, K)}")
 
 
 def test_fp32_contraction_kernels_in_a_child_process(gpu, oracle_mod, tmp_path):
