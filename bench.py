@@ -88,7 +88,7 @@ def buffer_sets(w):
     return max(2, min(64, -(-(1 << 30) // pair)))
 
 
-def measure(w, torch, binding, steps, warmup, staged=False, pruned=False):
+def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=RAMP_SECONDS):
     xd, Wd, yd = device_inputs(w, torch)
     sets = [(xd, yd)] + [(xd.clone(), torch.zeros_like(yd)) for _ in range(buffer_sets(w) - 1)]
     variant = 2 if pruned else 1 if staged else 0
@@ -103,7 +103,7 @@ def measure(w, torch, binding, steps, warmup, staged=False, pruned=False):
         turn[0] += 1
         fn(xi, Wd, yi, w.K, stream)
 
-    wall, dev = time_calls(torch, call, steps, warmup)
+    wall, dev = time_calls(torch, call, steps, warmup, ramp)
     del xd, Wd, yd, sets
     torch.cuda.empty_cache()
     return wall, dev
@@ -134,6 +134,9 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--ramp", type=float, default=RAMP_SECONDS,
+                    help="seconds of untimed calls before the warm-up steps that bring the engine clock from idle to "
+                         "its sustained value (0 for counter-collection runs, where every launch is slow)")
     ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of one workload, time every cell of the hidden-dimension sweep (B=512, N=256, C in "
@@ -167,9 +170,9 @@ def main():
         from paper_2504_11681_amd import inputs
         cells = []
         for w in inputs.sweep_configs():
-            _, dev = measure(w, torch, binding, args.steps, args.warmup)
-            _, pdev = measure(w, torch, binding, args.steps, args.warmup, pruned=True)
-            _, sdev = measure(w, torch, binding, max(5, args.steps // 10), 2, staged=True)
+            _, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp)
+            _, pdev = measure(w, torch, binding, args.steps, args.warmup, pruned=True, ramp=args.ramp)
+            _, sdev = measure(w, torch, binding, max(5, args.steps // 10), 2, staged=True, ramp=args.ramp)
             cells.append({"workload": w.name, "C": w.C_in, "K": w.K, "fused_us": dev * 1e6, "pruned_us": pdev * 1e6,
                           "staged_us": sdev * 1e6, "best": "fused" if dev <= pdev else "pruned",
                           "fused_hbm_frac": w.compulsory_bytes / dev / 1e9 / HBM_PEAK_GBPS,
@@ -180,7 +183,7 @@ def main():
         return
 
     w = pick_config(args.config)
-    wall, dev = measure(w, torch, binding, args.steps, args.warmup)
+    wall, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp)
     ms_per_step = wall / args.steps * 1e3
     layers_per_s = args.steps / wall
     alg_bytes = w.compulsory_bytes
@@ -205,7 +208,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "buffer_sets": buffer_sets(w),
-        "clock_ramp_s": RAMP_SECONDS,
+        "clock_ramp_s": args.ramp,
         "config": {"workload": w.name, "dims": w.dims, "B": w.B, "C_in": w.C_in, "C_out": w.C_out,
                    "N": w.N, "K": w.K, "seed": w.seed, "entry_point": "tfno_spectral_conv%dd" % w.dims},
         "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
@@ -219,14 +222,14 @@ def main():
 
     if not args.no_extras:
         s_steps = max(5, args.steps // 10)
-        swall, sdev = measure(w, torch, binding, s_steps, 2, staged=True)
+        swall, sdev = measure(w, torch, binding, s_steps, 2, staged=True, ramp=args.ramp)
         out["staged"] = {"ms_per_step": swall / s_steps * 1e3, "layers_per_s": s_steps / swall,
                          "variant": "five kernels: full FFT, truncate copy, CGEMM, pad copy, full iFFT",
                          "fused_speedup": (swall / s_steps) / (wall / args.steps)}
         if w.name.startswith("cfg3"):
             w4 = pick_config("cfg4")
             steps4 = max(10, args.steps // 4)
-            wall4, dev4 = measure(w4, torch, binding, steps4, 5)
+            wall4, dev4 = measure(w4, torch, binding, steps4, 5, ramp=args.ramp)
             traffic4 = None
             if os.path.exists(tpath):
                 traffic4 = json.load(open(tpath)).get(w4.name, {}).get("hbm_bytes_per_launch")
