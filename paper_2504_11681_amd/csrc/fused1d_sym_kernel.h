@@ -94,9 +94,6 @@ k_fused1d_sym(Fused1dArgs a)
     const int tile0 = (wave & 1) * TPW;                 // first mode tile of this wave
     const int o_lane = o_base + 32 * slab + nn;         // the output channel whose W this lane feeds
 
-    for (int i = tid; i < N; i += C::NT) TW[i] = cis2pi(-(float)((i >> 6) * (i & 63)), (float)N);
-    if (tid < 64) TW64[tid] = cis2pi(-(float)tid, 64.f);
-
     floatx16 acc_re[TPW], acc_im[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i)
@@ -257,6 +254,10 @@ k_fused1d_sym(Fused1dArgs a)
     load_pencil(va, 0);
     if constexpr (DEEP) load_pencil(vb, PPI);
     load_w(0);
+    // the twiddle tables are built while the first loads are in flight
+    __builtin_amdgcn_sched_barrier(0);
+    for (int i = tid; i < N; i += C::NT) TW[i] = cis2pi(-(float)((i >> 6) * (i & 63)), (float)N);
+    if (tid < 64) TW64[tid] = cis2pi(-(float)tid, 64.f);
     __syncthreads();                                        // twiddle tables are ready
     if constexpr (DEEP) {
         row_stage(va, 0, yes, 2 * PPI);

@@ -171,11 +171,23 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
 #pragma unroll
             for (int k = 0; k < 8; ++k) { z[2 * k] = za[k]; z[2 * k + 1] = zo[k]; }
         }
+        // the twiddles are read eight at a time before their first use: left alone, the compiler reads, waits and
+        // multiplies one at a time (15 exposed LDS round trips per sweep); all 15 at once do not fit the registers
         wave_sync();                                        // the previous sweep's patch reads are done
 #pragma unroll
-        for (int kl = 0; kl < 16; ++kl) {
-            const c64 zt = kl == 0 ? z[0] : cmul(z[kl], L.tw[kl * LPR + p]);
-            scr[kl * LPR + (p ^ (kl % LPR))] = zt;
+        for (int half = 0; half < 2; ++half) {
+            c64 tw[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (half + j != 0) tw[j] = L.tw[(8 * half + j) * LPR + p];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int kl = 8 * half + j;
+                const c64 zt = kl == 0 ? z[0] : cmul(z[kl], tw[j]);
+                scr[kl * LPR + (p ^ (kl % LPR))] = zt;
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         wave_sync();
 #pragma unroll
