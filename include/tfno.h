@@ -103,16 +103,33 @@ tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y,
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and
  * same result as tfno_spectral_conv1d.  Shapes: N in {64,128,256} with K a multiple of 16 such that K/16 is a
  * power of two not above N/16, or N = 1024 with K in {64,128}; others TFNO_ERR_UNSUPPORTED.  Needs
- * tfno_workspace_bytes(1, 2, ...) bytes of workspace.  It is the faster path where the fused kernel is bound by
- * its contraction (hidden dimension >= 128 with K/N = 1/2, the crossover Sec. 5.1 describes).
+ * tfno_workspace_bytes(1, 2, ...) bytes of workspace.  It is faster than a fused kernel whose contraction runs
+ * on FP32 MFMA at hidden dimension 256 (the crossover Sec. 5.1 describes); against the default fused kernel
+ * (BF16 matrix pipe) it is not.
  */
 tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y,
                                         int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
+ * The two partially fused 1-D variants of the paper (variants "B" and "C" of Table 2, Sec. 5), two launches each:
+ *   tfno_spectral_conv1d_fft_gemm   forward transform and CGEMM in one kernel (Sec. 4.1): x is read once, the
+ *                                   truncated output spectrum Yh[B, C_out, K] goes through the workspace to the
+ *                                   zero-padded, input-pruned inverse kernel;
+ *   tfno_spectral_conv1d_gemm_ifft  CGEMM and inverse transform in one kernel (Sec. 4.2): the output-pruned
+ *                                   forward kernel writes the truncated input spectrum Xh[B, C_in, K] to the
+ *                                   workspace, the second kernel contracts it and writes y once.
+ * Same contract and same result as tfno_spectral_conv1d.  Shapes: N in {128, 256}, K in {32, 64, 128} (K <= N);
+ * others TFNO_ERR_UNSUPPORTED.  Workspace: tfno_workspace_bytes(1, 3, ...) and (1, 4, ...) bytes.
+ */
+tfno_status tfno_spectral_conv1d_fft_gemm(const void *x, const void *W, void *y,
+                                          int B, int C_in, int C_out, int N, int K, void *stream);
+tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y,
+                                           int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
  * Workspace (device memory for intermediates) that an entry point needs for a
- * shape: dims = 1 or 2, variant = 0 (fused entry point), 1 (staged twin) or 2
- * (tfno_spectral_conv1d_pruned).  Returns 0 when none is needed or the arguments are invalid.
+ * shape: dims = 1 or 2, variant = 0 (fused entry point), 1 (staged twin), 2
+ * (tfno_spectral_conv1d_pruned), 3 (tfno_spectral_conv1d_fft_gemm) or 4 (tfno_spectral_conv1d_gemm_ifft).  Returns 0 when none is needed or the arguments are invalid.
  */
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K);
 

@@ -20,11 +20,15 @@ EXPORTS = (
     "tfno_spectral_conv1d_staged",
     "tfno_spectral_conv2d_staged",
     "tfno_spectral_conv1d_pruned",
+    "tfno_spectral_conv1d_fft_gemm",
+    "tfno_spectral_conv1d_gemm_ifft",
     "tfno_workspace_bytes",
     "tfno_set_workspace",
     "tfno_status_string",
     "tfno_version",
 )
+
+CONV_EXPORTS = EXPORTS[:7]   # the entry points with the (x, W, y, B, C_in, C_out, N, K, stream) signature
 
 _lib = None
 _workspace = None     # the torch tensor currently registered as workspace (kept alive here)
@@ -45,7 +49,7 @@ def lib() -> ctypes.CDLL:
                                "(there is no fallback path)")
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
-        for name in EXPORTS[:5]:
+        for name in CONV_EXPORTS:
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
@@ -70,7 +74,8 @@ def version() -> int:
 
 
 def workspace_bytes(dims: int, variant, B: int, C_in: int, C_out: int, N: int, K: int) -> int:
-    """variant: 0 / False = fused entry point, 1 / True = staged twin, 2 = spectral_conv1d_pruned."""
+    """variant: 0 / False = fused entry point, 1 / True = staged twin, 2 = spectral_conv1d_pruned,
+    3 = spectral_conv1d_fft_gemm, 4 = spectral_conv1d_gemm_ifft."""
     return lib().tfno_workspace_bytes(dims, int(variant), B, C_in, C_out, N, K)
 
 
@@ -133,3 +138,11 @@ def spectral_conv2d_staged(x, W, y, K: int, stream=None):
 
 def spectral_conv1d_pruned(x, W, y, K: int, stream=None):
     return _call("tfno_spectral_conv1d_pruned", 1, 2, x, W, y, K, stream)
+
+
+def spectral_conv1d_fft_gemm(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv1d_fft_gemm", 1, 3, x, W, y, K, stream)
+
+
+def spectral_conv1d_gemm_ifft(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv1d_gemm_ifft", 1, 4, x, W, y, K, stream)

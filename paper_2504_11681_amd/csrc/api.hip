@@ -63,7 +63,7 @@ tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W
     return TFNO_OK;
 }
 
-enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2 };
+enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2, FFT_GEMM = 3, GEMM_IFFT = 4 };
 
 tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
                 int K, void *stream)
@@ -74,6 +74,8 @@ tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y
     if (st != TFNO_OK || empty) return st;
     if (variant == PRUNED) {
         if (dims != 1 || !pruned1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+    } else if (variant == FFT_GEMM || variant == GEMM_IFFT) {
+        if (dims != 1 || !fused1d_partial_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
     } else if (!staged && !(dims == 2 && fused2d_supported(N, K)) && !fused1d_supported(N, K)) {
         return TFNO_ERR_UNSUPPORTED;
     }
@@ -94,6 +96,23 @@ tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y
         e = staged_conv(dims, xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
     } else if (variant == PRUNED) {
         e = pruned1d_launch(xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
+    } else if (variant == FFT_GEMM || variant == GEMM_IFFT) {
+        // the workspace holds one truncated spectrum: the output's (FFT + CGEMM kernel, then the pruned inverse
+        // kernel) or the input's (pruned forward kernel, then the CGEMM + iFFT kernel)
+        Fused1dArgs a{};
+        a.x = xc; a.W = Wc; a.y = yc; a.C_in = C_in; a.C_out = C_out;
+        a.inner_count = 1;
+        a.x_outer_stride = (long long)C_in * N;  a.x_inner_stride = 0; a.x_chan_stride = N;
+        a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
+        a.scale = 1.0f / (float)N;
+        a.Xh = (const c64 *)ws; a.Yh = (c64 *)ws;
+        if (variant == FFT_GEMM) {
+            e = fused1d_partial_launch(1, N, K, a, B, s);
+            if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, Wc, yc, nullptr, (c64 *)ws, B, C_in, C_out, N, K, s);
+        } else {
+            e = pruned1d_stages(PRUNED_FWD, xc, Wc, yc, (c64 *)ws, nullptr, B, C_in, C_out, N, K, s);
+            if (e == hipSuccess) e = fused1d_partial_launch(2, N, K, a, B, s);
+        }
     } else if (dims == 1) {
         Fused1dArgs a{};
         a.x = xc; a.W = Wc; a.y = yc; a.C_in = C_in; a.C_out = C_out;
@@ -142,6 +161,18 @@ bool fused1d_supported(int N, int K)
     case 1024: return K >= 32 && K <= 256;
     default: return false;
     }
+}
+
+bool fused1d_partial_supported(int N, int K)
+{
+    return (N == 128 || N == 256) && (K == 32 || K == 64 || K == 128) && pruned1d_supported(N, K);
+}
+
+hipError_t fused1d_partial_launch(int mode, int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    if (!fused1d_partial_supported(N, K) || (mode != 1 && mode != 2)) return hipErrorInvalidValue;
+    if (N == 128) return mode == 1 ? fused1d_fftgemm_launch_n128(K, a, rows, s) : fused1d_gemmifft_launch_n128(K, a, rows, s);
+    return mode == 1 ? fused1d_fftgemm_launch_n256(K, a, rows, s) : fused1d_gemmifft_launch_n256(K, a, rows, s);
 }
 
 // TFNO_CONTRACTION=f32 forces the kernels whose channel contraction uses FP32 MFMA; the default lets
@@ -203,6 +234,18 @@ tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y, i
     return run(1, PRUNED, x, W, y, B, C_in, C_out, N, K, stream);
 }
 
+tfno_status tfno_spectral_conv1d_fft_gemm(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                          int K, void *stream)
+{
+    return run(1, FFT_GEMM, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                           int K, void *stream)
+{
+    return run(1, GEMM_IFFT, x, W, y, B, C_in, C_out, N, K, stream);
+}
+
 tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
                                         int K, void *stream)
 {
@@ -218,10 +261,14 @@ tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y, i
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K)
 {
     const int staged = variant == 1;
-    if (variant < 0 || variant > 2) return 0;
+    if (variant < 0 || variant > 4) return 0;
     if (variant == 2) {
         if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !pruned1d_supported(N, K)) return 0;
         return pruned1d_workspace_bytes(B, C_in, C_out, K);
+    }
+    if (variant == 3 || variant == 4) {
+        if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !fused1d_partial_supported(N, K)) return 0;
+        return sizeof(c64) * pruned1d_spectrum_elems(B, variant == 3 ? C_out : C_in, K);
     }
     if ((dims != 1 && dims != 2) || B < 1 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N)
         return 0;

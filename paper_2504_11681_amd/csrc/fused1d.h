@@ -17,6 +17,10 @@ struct Fused1dArgs {
     long long x_outer_stride, x_inner_stride, x_chan_stride;
     long long y_outer_stride, y_inner_stride, y_chan_stride;
     float scale;    // folded into W (1/N for 1-D; the 2-D pipeline passes its full 1/N^2 here)
+    // Partially fused variants only (inner_count = 1): truncated spectra in the mode-tile-major layout of the
+    // unfused pruned variant, joint mode m = row * K + k at ((m / 128) * C + c) * 128 + m % 128.
+    const c64 *Xh;  // read instead of x by the CGEMM + iFFT kernel
+    c64 *Yh;        // written instead of y by the FFT + CGEMM kernel
 };
 
 // Returns true when a fused kernel exists for (N, K).
@@ -34,6 +38,16 @@ hipError_t fused1d_ws_launch(int N, int K, const Fused1dArgs &a, long long rows,
 // Symmetric-wave variant (every wave runs transforms and contraction; BF16x3 split contraction).
 bool fused1d_sym_supported(int N, int K);
 hipError_t fused1d_sym_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+
+// Partially fused variants (Sec. 4.1 and 4.2): mode 1 = FFT + CGEMM in one kernel, writes the truncated output
+// spectrum a.Yh; mode 2 = CGEMM + iFFT in one kernel, reads the truncated input spectrum a.Xh.  Built for
+// N in {128, 256}, K in {32, 64, 128}; the contraction always runs on the BF16 matrix pipe.
+bool fused1d_partial_supported(int N, int K);
+hipError_t fused1d_partial_launch(int mode, int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_fftgemm_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_fftgemm_launch_n256(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_gemmifft_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_gemmifft_launch_n256(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 
 // Per-N dispatchers, one translation unit each.
 hipError_t fused1d_launch_n64(int K, const Fused1dArgs &a, long long rows, hipStream_t s);

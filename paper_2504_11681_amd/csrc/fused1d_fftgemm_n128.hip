@@ -1,0 +1,11 @@
+// Partially fused variant FFT + CGEMM (Sec. 4.1): instantiations for N = 128.
+#include "fused1d_kernel.h"
+
+namespace tfno {
+
+hipError_t fused1d_fftgemm_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    return launch_partial<128, 1>(K, a, rows, s);
+}
+
+}  // namespace tfno

@@ -97,8 +97,10 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// EVEN: C_in is a multiple of PPI and C_out a multiple of 32, so no load or store needs a mask.
-template <int N, int K, int OT, bool EVEN, bool BF>
+// EVEN: C_in is a multiple of PPI and C_out a multiple of 32 OT, so no load or store needs a mask.
+// MODE 0: fully fused.  MODE 1: FFT + CGEMM (Sec. 4.1), the accumulators leave as the truncated output spectrum
+// a.Yh.  MODE 2: CGEMM + iFFT (Sec. 4.2), the operand tiles come from the truncated input spectrum a.Xh.
+template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0>
 __global__ void __launch_bounds__(256)
 k_fused1d(Fused1dArgs a)
 {
@@ -185,6 +187,19 @@ k_fused1d(Fused1dArgs a)
             }
         }
     };
+    // spectrum value of (channel slot jg of the block, mode k) into an operand tile
+    auto put_operand = [&](float *XHb, int jg, int k, c64 val) __attribute__((always_inline)) {
+        if constexpr (BF) {
+            unsigned *d = reinterpret_cast<unsigned *>(XHb) + (jg >> 2) * (KT * 128) + (jg & 3) + (k >> 5) * 128 + (k & 31) * 4;
+            const Split3 re = split3(val.x), im = split3(val.y);
+            d[0 * (PPI / 4) * KT * 128] = pack_bf16(re.t0, im.t0);
+            d[1 * (PPI / 4) * KT * 128] = pack_bf16(re.t1, im.t1);
+            d[2 * (PPI / 4) * KT * 128] = pack_bf16(re.t2, im.t2);
+        } else {
+            XHb[(jg * 2 + 0) * KPAD + k] = val.x;
+            XHb[(jg * 2 + 1) * KPAD + k] = val.y;
+        }
+    };
     // stage A: P-point transform of the slice in v, written transposed into the wave's Z tile
     auto stage_a = [&]() __attribute__((always_inline)) {
         c64 z[P];
@@ -207,24 +222,8 @@ k_fused1d(Fused1dArgs a)
                 else return cmul(zcol[tt], TW[tt * P + p]);
             }, xo);
             const int jg = wave * PPW + j;
-            if constexpr (BF) {
-                unsigned *XS = reinterpret_cast<unsigned *>(XHb) + (jg >> 2) * (KT * 128) + (jg & 3);
 #pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    const int k = p + P * q;
-                    const Split3 re = split3(xo[q].x), im = split3(xo[q].y);
-                    unsigned *d = XS + (k >> 5) * 128 + (k & 31) * 4;
-                    d[0 * (PPI / 4) * KT * 128] = pack_bf16(re.t0, im.t0);
-                    d[1 * (PPI / 4) * KT * 128] = pack_bf16(re.t1, im.t1);
-                    d[2 * (PPI / 4) * KT * 128] = pack_bf16(re.t2, im.t2);
-                }
-            } else {
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    XHb[(jg * 2 + 0) * KPAD + p + P * q] = xo[q].x;
-                    XHb[(jg * 2 + 1) * KPAD + p + P * q] = xo[q].y;
-                }
-            }
+            for (int q = 0; q < Q; ++q) put_operand(XHb, jg, p + P * q, xo[q]);
         }
     };
     // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)
@@ -308,38 +307,106 @@ k_fused1d(Fused1dArgs a)
     const std::false_type no{};
 
     // ------------------------------------------------------------------ k-loop over input channels
-    load_pencil(0);
-    load_w(wv, 0);
-    stage_a();
-    wave_sync();
-    if (n_it > 1) load_pencil(PPI);
-    stage_b(0);
-    wave_sync();
-    if (n_it > 1) {
+    if constexpr (MODE != 2) {
+        load_pencil(0);
+        load_w(wv, 0);
         stage_a();
         wave_sync();
-        if (n_it > 2) load_pencil(2 * PPI);
-    }
-    __syncthreads();
-    TFNO_STAMP(1);
-    {
-        int it = 0;
-        for (; it + 3 < n_it; ++it) step(yes, yes, yes, it);
-        const int left = n_it - it;   // 1, 2 or 3
-        if (left == 3) {
-            step(yes, yes, no, it);
-            step(yes, no, no, it + 1);
-            step(no, no, no, it + 2);
-        } else if (left == 2) {
-            step(yes, no, no, it);
-            step(no, no, no, it + 1);
-        } else {
-            step(no, no, no, it);
+        if (n_it > 1) load_pencil(PPI);
+        stage_b(0);
+        wave_sync();
+        if (n_it > 1) {
+            stage_a();
+            wave_sync();
+            if (n_it > 2) load_pencil(2 * PPI);
         }
+        __syncthreads();
+        TFNO_STAMP(1);
+        {
+            int it = 0;
+            for (; it + 3 < n_it; ++it) step(yes, yes, yes, it);
+            const int left = n_it - it;   // 1, 2 or 3
+            if (left == 3) {
+                step(yes, yes, no, it);
+                step(yes, no, no, it + 1);
+                step(no, no, no, it + 2);
+            } else if (left == 2) {
+                step(yes, no, no, it);
+                step(no, no, no, it + 1);
+            } else {
+                step(no, no, no, it);
+            }
+        }
+    } else {
+        // CGEMM + iFFT: every thread moves K/T spectrum values per block from a.Xh into the operand tile, two
+        // blocks ahead of the MFMAs (registers, then LDS); consecutive threads read consecutive modes.
+        constexpr int NSV = K / T;
+        static_assert(NSV * NT == PPI * K, "a block of spectrum values divides evenly over the workgroup");
+        c64 sv[NSV];
+        auto load_spec = [&](int c0) __attribute__((always_inline)) {
+#pragma unroll
+            for (int e = 0; e < NSV; ++e) {
+                const int idx = tid + NT * e, k = idx % K, c = c0 + idx / K;
+                const long long m = (long long)bb * K + k;
+                const bool ok = EVEN || c < a.C_in;
+                const c64 val = a.Xh[((m >> 7) * a.C_in + (ok ? c : 0)) * 128 + (m & 127)];
+                sv[e] = ok ? val : make_float2(0.f, 0.f);
+            }
+        };
+        auto put_spec = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+            for (int e = 0; e < NSV; ++e) {
+                const int idx = tid + NT * e;
+                put_operand(XH + buf * C::XH_BUF, idx / K, idx % K, sv[e]);
+            }
+        };
+        auto sstep = [&](auto do_put, auto do_load, int it) __attribute__((always_inline)) {
+            constexpr bool DO_PUT = decltype(do_put)::value, DO_LOAD = decltype(do_load)::value;
+            c64 wn[NWV];
+            if constexpr (DO_PUT) load_w(wn, (it + 1) * PPI);
+            if constexpr (ALLT) mfma_block(it & 1);
+            else if (has_tiles) mfma_block(it & 1);
+            if constexpr (DO_PUT) put_spec((it & 1) ^ 1);
+            if constexpr (DO_LOAD) load_spec((it + 2) * PPI);
+            if constexpr (DO_PUT) {
+#pragma unroll
+                for (int jc = 0; jc < NWV; ++jc) wv[jc] = wn[jc];
+                __syncthreads();
+            }
+        };
+        load_spec(0);
+        load_w(wv, 0);
+        put_spec(0);
+        if (n_it > 1) load_spec(PPI);
+        __syncthreads();
+        int it = 0;
+        for (; it + 2 < n_it; ++it) sstep(yes, yes, it);
+        if (it + 1 < n_it) { sstep(yes, no, it); ++it; }
+        sstep(no, no, it);
     }
 
     TFNO_STAMP(2);
     // ------------------------------------------------------------------ epilogue
+    if constexpr (MODE == 1) {
+        // FFT + CGEMM: register r of lane l of tile i holds Yh[o][k] for o = 8(r/4) + 4(l/32) + r%4 of the wave's
+        // slab and k = 32 (kt0 + i) + l%32; a half-wave writes 32 consecutive modes of one output channel
+        if (has_tiles) {
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int k = 32 * (kt0 + i) + (lane & 31);
+                if (k < K) {
+                    const long long m = (long long)bb * K + k;
+                    c64 *dst = a.Yh + (m >> 7) * a.C_out * 128 + (m & 127);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int o = o_base + 32 * ot_w + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                        if (EVEN || o < a.C_out) dst[(long long)o * 128] = make_float2(acc_re[i][r], acc_im[i][r]);
+                    }
+                }
+            }
+        }
+        return;
+    }
     // stage B' for Z slot `slot`, column p: zero-padded, input-pruned T-point inverse transform of the Q
     // retained modes in yin, conj twiddle, written transposed into the wave's Z tile
     auto stage_b_inv = [&](const c64 *yin, int slot, int p) __attribute__((always_inline)) {
@@ -432,26 +499,46 @@ k_fused1d(Fused1dArgs a)
     TFNO_STAMP(3);
 }
 
-template <int N, int K, int OT, bool BF>
+template <int N, int K, int OT, bool BF, int MODE = 0>
 hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
     using C = FusedCfg<N, K, OT, BF>;
     static bool attr_done = false;   // benign race: every thread sets the same value
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
-    if (a.C_in % C::PPI == 0 && a.C_out % 32 == 0)
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF>), grid, dim3(256), C::LDS_DYN, s, a);
+    // unmasked kernel only when every workgroup's slab of 32 OT outputs exists in full
+    if (a.C_in % C::PPI == 0 && a.C_out % (32 * OT) == 0)
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE>), grid, dim3(256), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE>), grid, dim3(256), C::LDS_DYN, s, a);
     return hipGetLastError();
+}
+
+// Partially fused variant MODE (1 or 2) for every K built, workgroup slab chosen by C_out as for the fused kernel
+template <int N, int K, int MODE>
+hipError_t launch_partial_k(const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    if (a.C_out > 64) return launch_fused1d_impl<N, K, 4, true, MODE>(a, rows, s);
+    if (a.C_out > 32) return launch_fused1d_impl<N, K, 2, true, MODE>(a, rows, s);
+    return launch_fused1d_impl<N, K, 1, true, MODE>(a, rows, s);
+}
+template <int N, int MODE>
+hipError_t launch_partial(int K, const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    switch (K) {
+    case 32: return launch_partial_k<N, 32, MODE>(a, rows, s);
+    case 64: return launch_partial_k<N, 64, MODE>(a, rows, s);
+    case 128: return launch_partial_k<N, 128, MODE>(a, rows, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // BF16x3 contraction unless the environment asks for FP32 MFMA (TFNO_CONTRACTION=f32)

@@ -22,54 +22,68 @@ size_t pruned1d_workspace_bytes(long long B, int C_in, int C_out, int K)
     return sizeof(c64) * (size_t)mode_tiles(B, K) * 128 * ((size_t)C_in + C_out);
 }
 
+size_t pruned1d_spectrum_elems(long long B, int C, int K) { return (size_t)mode_tiles(B, K) * 128 * (size_t)C; }
+
 template <int N, int K>
-static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
-                            hipStream_t s)
+static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
+                            int C_out, hipStream_t s)
 {
     using Cf = CfgP1<N, K>;
     const long long tiles = mode_tiles(B, K);
-    c64 *Xh = ws, *Yh = ws + (size_t)tiles * 128 * C_in;
     const long long pin = B * C_in, pout = B * C_out;
     const long long sin = (pin + Cf::PPS - 1) / Cf::PPS, sout = (pout + Cf::PPS - 1) / Cf::PPS;
     // a few sweeps per workgroup amortise the twiddle tables and keep a prefetch in flight
     const unsigned gin = (unsigned)(sin < 1024 ? sin : 1024), gout = (unsigned)(sout < 1024 ? sout : 1024);
-    hipLaunchKernelGGL((k_fwd1d<N, K>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / (float)N, tiles, s)) != hipSuccess) return e;
-    hipLaunchKernelGGL((k_inv1d<N, K>), dim3(gout), dim3(256), 0, s, (const c64 *)Yh, y, C_out, pout);
-    return hipGetLastError();
+    hipError_t e = hipSuccess;
+    if (stages & PRUNED_FWD) {
+        hipLaunchKernelGGL((k_fwd1d<N, K>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (stages & PRUNED_GEMM)
+        if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / (float)N, tiles, s)) != hipSuccess) return e;
+    if (stages & PRUNED_INV) {
+        hipLaunchKernelGGL((k_inv1d<N, K>), dim3(gout), dim3(256), 0, s, (const c64 *)Yh, y, C_out, pout);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 template <int N>
-static hipError_t launch_n(int K, const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
-                           hipStream_t s)
+static hipError_t launch_n(int K, int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B,
+                           int C_in, int C_out, hipStream_t s)
 {
     constexpr int LPR = N / 16;
     switch (K) {
-    case 16: return launch_nk<N, 16>(x, W, y, B, C_in, C_out, ws, s);
-    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32>(x, W, y, B, C_in, C_out, ws, s); break;
-    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64>(x, W, y, B, C_in, C_out, ws, s); break;
-    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128>(x, W, y, B, C_in, C_out, ws, s); break;
-    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256>(x, W, y, B, C_in, C_out, ws, s); break;
+    case 16: return launch_nk<N, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
+    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
+    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
+    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
     default: break;
     }
     return hipErrorInvalidValue;
 }
 
-hipError_t pruned1d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
-                           c64 *ws, hipStream_t s)
+hipError_t pruned1d_stages(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
+                           int C_out, int N, int K, hipStream_t s)
 {
     if (!pruned1d_supported(N, K)) return hipErrorInvalidValue;
     switch (N) {
-    case 64: return launch_n<64>(K, x, W, y, B, C_in, C_out, ws, s);
-    case 128: return launch_n<128>(K, x, W, y, B, C_in, C_out, ws, s);
-    case 256: return launch_n<256>(K, x, W, y, B, C_in, C_out, ws, s);
+    case 64: return launch_n<64>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 128: return launch_n<128>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 256: return launch_n<256>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
     case 1024:
-        if (K == 64) return launch_nk<1024, 64>(x, W, y, B, C_in, C_out, ws, s);
-        return launch_nk<1024, 128>(x, W, y, B, C_in, C_out, ws, s);
+        if (K == 64) return launch_nk<1024, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+        return launch_nk<1024, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
     default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t pruned1d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
+                           c64 *ws, hipStream_t s)
+{
+    return pruned1d_stages(PRUNED_FWD | PRUNED_GEMM | PRUNED_INV, x, W, y, ws, ws + pruned1d_spectrum_elems(B, C_in, K),
+                           B, C_in, C_out, N, K, s);
 }
 
 }  // namespace tfno

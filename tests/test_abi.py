@@ -45,7 +45,7 @@ def call(L, name, x, W, y, B, Ci, Co, N, K):
     return getattr(L, name)(x, W, y, B, Ci, Co, N, K, None)
 
 
-@pytest.mark.parametrize("name", binding.EXPORTS[:5])
+@pytest.mark.parametrize("name", binding.CONV_EXPORTS)
 def test_argument_errors_are_caught_on_the_host(L, name):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, name, None, W, y, 2, 4, 4, 64, 16) == binding.ERR_NULL
@@ -68,6 +68,10 @@ def test_fused_entry_points_report_unsupported_shapes(L):
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 48) == binding.ERR_UNSUPPORTED
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 8) == binding.ERR_UNSUPPORTED
     assert call(L, "tfno_spectral_conv2d", x, W, y, 2, 4, 4, 32, 8) == binding.ERR_UNSUPPORTED
+    for name in ("tfno_spectral_conv1d_fft_gemm", "tfno_spectral_conv1d_gemm_ifft"):
+        assert call(L, name, x, W, y, 2, 4, 4, 1024, 128) == binding.ERR_UNSUPPORTED
+        assert call(L, name, x, W, y, 2, 4, 4, 256, 16) == binding.ERR_UNSUPPORTED
+        assert call(L, name, x, W, y, 2, 4, 4, 64, 32) == binding.ERR_UNSUPPORTED
 
 
 def test_workspace_contract(L):
@@ -83,6 +87,12 @@ def test_workspace_contract(L):
     assert binding.workspace_bytes(1, 2, 256, 128, 128, 1024, 128) == 8 * 256 * 128 * (128 + 128)
     assert binding.workspace_bytes(1, 2, 4, 16, 16, 64, 48) == 0          # K/16 not a power of two
     assert binding.workspace_bytes(2, 2, 4, 16, 16, 64, 16) == 0          # 1-D only
+    # partially fused variants: one truncated spectrum, the output's (3: FFT + CGEMM) or the input's (4: CGEMM + iFFT)
+    assert binding.workspace_bytes(1, 3, 4, 16, 48, 256, 64) == 8 * 2 * 128 * 48
+    assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 64) == 8 * 2 * 128 * 16
+    assert binding.workspace_bytes(1, 3, 4, 16, 48, 1024, 64) == 0        # N in {128, 256} only
+    assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 16) == 0         # K in {32, 64, 128} only
+    assert binding.workspace_bytes(1, 5, 4, 16, 48, 256, 64) == 0
     assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)

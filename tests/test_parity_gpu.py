@@ -63,6 +63,9 @@ SMALL_1D = [
     (5, 19, 130, 256, 32),
     (2, 40, 33, 256, 16),
     (3, 24, 96, 256, 128),
+    (3, 32, 96, 256, 64),       # whole channel blocks, but the last 128-output slab is only partly there
+    (2, 64, 96, 128, 32),
+    (2, 16, 160, 256, 32),
     (2, 20, 40, 256, 256),
     (3, 21, 66, 512, 64),
     (2, 35, 10, 512, 256),
@@ -104,6 +107,23 @@ def test_1d_pruned_variant(gpu, oracle_mod, shape):
     W = inputs.make_W(300 + N + K, Ci, Co)
     want, _ = oracle_mod.spectral_conv1d(x, W, K)
     check(run_gpu(gpu, "spectral_conv1d_pruned", x, W, K), want, "pruned")
+
+
+# partially fused variants (FFT + CGEMM kernel then pruned inverse; pruned forward then CGEMM + iFFT kernel)
+PARTIAL_1D = [(3, 20, 40, 256, 64), (2, 16, 128, 256, 32), (1, 33, 65, 256, 128), (2, 8, 32, 128, 32),
+              (3, 13, 129, 128, 64), (2, 32, 64, 128, 128), (5, 1, 1, 256, 32), (2, 64, 96, 256, 128),
+              (70, 16, 32, 256, 64)]
+
+
+@pytest.mark.parametrize("fn", ["spectral_conv1d_fft_gemm", "spectral_conv1d_gemm_ifft"])
+@pytest.mark.parametrize("shape", PARTIAL_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_partially_fused_variants(gpu, oracle_mod, shape, fn):
+    B, Ci, Co, N, K = shape
+    say(f"[case] {fn} {shape}")
+    x = inputs.make_x(500 + N + K, B, Ci, (N,))
+    W = inputs.make_W(500 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    check(run_gpu(gpu, fn, x, W, K), want, fn)
 
 
 def test_1d_pruned_unsupported_shapes(gpu):
@@ -228,6 +248,8 @@ def test_config5_sweep_full_size(gpu, oracle_mod, w):
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d", [0, 511])
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d_staged", [257])
     full_size_case(gpu, oracle_mod, w, "spectral_conv1d_pruned", [3, 510])
+    full_size_case(gpu, oracle_mod, w, "spectral_conv1d_fft_gemm", [1, 509])
+    full_size_case(gpu, oracle_mod, w, "spectral_conv1d_gemm_ifft", [2, 508])
 
 
 SYM_1D = [(2, 32, 128, 1024, 128),   # two blocks of loads in flight (even block count >= 4), no masks
