@@ -88,11 +88,17 @@ def buffer_sets(w):
     return max(2, min(64, -(-(1 << 30) // pair)))
 
 
-def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=RAMP_SECONDS):
+VARIANT_SUFFIX = ("", "_staged", "_pruned", "_fft_gemm", "_gemm_ifft", "_auto")
+
+
+def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=RAMP_SECONDS, variant=None):
+    """variant: 0 fused, 1 staged (five kernels), 2 pruned (three kernels), 3 FFT+CGEMM fused, 4 CGEMM+iFFT fused,
+    5 per-shape dispatch."""
     xd, Wd, yd = device_inputs(w, torch)
     sets = [(xd, yd)] + [(xd.clone(), torch.zeros_like(yd)) for _ in range(buffer_sets(w) - 1)]
-    variant = 2 if pruned else 1 if staged else 0
-    name = ("spectral_conv%dd" % w.dims) + ("", "_staged", "_pruned")[variant]
+    if variant is None:
+        variant = 2 if pruned else 1 if staged else 0
+    name = ("spectral_conv%dd" % w.dims) + VARIANT_SUFFIX[variant]
     fn = getattr(binding, name)
     binding.ensure_workspace(binding.workspace_bytes(w.dims, variant, w.B, w.C_in, w.C_out, w.N, w.K), xd.device)
     stream = torch.cuda.current_stream().cuda_stream
@@ -140,7 +146,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of one workload, time every cell of the hidden-dimension sweep (B=512, N=256, C in "
-                         "{32,64,128,256}, K in {32,64,128}) with the fused kernel, the unfused pruned variant and the "
+                         "{32,64,128,256}, K in {32,64,128}) with the fused kernel (the paper's variant D), the two "
+                         "partially fused variants (B: FFT+CGEMM, C: CGEMM+iFFT), the unfused pruned variant (A) and the "
                          "five-kernel staged baseline, and print one JSON line with all cells")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy three times (reads 256 MiB, writes "
@@ -172,9 +179,14 @@ def main():
         for w in inputs.sweep_configs():
             _, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp)
             _, pdev = measure(w, torch, binding, args.steps, args.warmup, pruned=True, ramp=args.ramp)
+            _, bdev = measure(w, torch, binding, args.steps, args.warmup, variant=3, ramp=args.ramp)
+            _, cdev = measure(w, torch, binding, args.steps, args.warmup, variant=4, ramp=args.ramp)
+            _, adev = measure(w, torch, binding, args.steps, args.warmup, variant=5, ramp=args.ramp)
             _, sdev = measure(w, torch, binding, max(5, args.steps // 10), 2, staged=True, ramp=args.ramp)
+            times = {"fused": dev, "pruned": pdev, "fft_gemm": bdev, "gemm_ifft": cdev}
             cells.append({"workload": w.name, "C": w.C_in, "K": w.K, "fused_us": dev * 1e6, "pruned_us": pdev * 1e6,
-                          "staged_us": sdev * 1e6, "best": "fused" if dev <= pdev else "pruned",
+                          "fft_gemm_us": bdev * 1e6, "gemm_ifft_us": cdev * 1e6, "auto_us": adev * 1e6,
+                          "staged_us": sdev * 1e6, "best": min(times, key=times.get),
                           "fused_hbm_frac": w.compulsory_bytes / dev / 1e9 / HBM_PEAK_GBPS,
                           "fused_contraction_TFLOPs": flops_of(w) / dev / 1e12})
         print(json.dumps({"metric": "fused_vs_unfused_crossover", "unit": "us per layer (HIP events)", "n_gpus": 1,

@@ -127,9 +127,20 @@ tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y
                                            int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
+ * Per-shape dispatch (variant "E" of Table 2, Sec. 5: the best of the variants for each shape), with the rule
+ * measured on MI355X: the CGEMM + iFFT variant when C_out > 128 and that variant exists for (N, K) (the fully
+ * fused kernel repeats the forward transform for every 128-output slab), else the fully fused kernel where one
+ * exists, else the staged path.  Accepts every valid 1-D shape; same contract and same result as
+ * tfno_spectral_conv1d.  Workspace: tfno_workspace_bytes(1, 5, ...) bytes (0 when the fused kernel is chosen).
+ */
+tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y,
+                                      int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
  * Workspace (device memory for intermediates) that an entry point needs for a
  * shape: dims = 1 or 2, variant = 0 (fused entry point), 1 (staged twin), 2
- * (tfno_spectral_conv1d_pruned), 3 (tfno_spectral_conv1d_fft_gemm) or 4 (tfno_spectral_conv1d_gemm_ifft).  Returns 0 when none is needed or the arguments are invalid.
+ * (tfno_spectral_conv1d_pruned), 3 (tfno_spectral_conv1d_fft_gemm), 4 (tfno_spectral_conv1d_gemm_ifft) or 5
+ * (tfno_spectral_conv1d_auto).  Returns 0 when none is needed or the arguments are invalid.
  */
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K);
 

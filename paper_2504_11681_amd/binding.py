@@ -22,13 +22,14 @@ EXPORTS = (
     "tfno_spectral_conv1d_pruned",
     "tfno_spectral_conv1d_fft_gemm",
     "tfno_spectral_conv1d_gemm_ifft",
+    "tfno_spectral_conv1d_auto",
     "tfno_workspace_bytes",
     "tfno_set_workspace",
     "tfno_status_string",
     "tfno_version",
 )
 
-CONV_EXPORTS = EXPORTS[:7]   # the entry points with the (x, W, y, B, C_in, C_out, N, K, stream) signature
+CONV_EXPORTS = EXPORTS[:8]   # the entry points with the (x, W, y, B, C_in, C_out, N, K, stream) signature
 
 _lib = None
 _workspace = None     # the torch tensor currently registered as workspace (kept alive here)
@@ -75,7 +76,7 @@ def version() -> int:
 
 def workspace_bytes(dims: int, variant, B: int, C_in: int, C_out: int, N: int, K: int) -> int:
     """variant: 0 / False = fused entry point, 1 / True = staged twin, 2 = spectral_conv1d_pruned,
-    3 = spectral_conv1d_fft_gemm, 4 = spectral_conv1d_gemm_ifft."""
+    3 = spectral_conv1d_fft_gemm, 4 = spectral_conv1d_gemm_ifft, 5 = spectral_conv1d_auto."""
     return lib().tfno_workspace_bytes(dims, int(variant), B, C_in, C_out, N, K)
 
 
@@ -146,3 +147,7 @@ def spectral_conv1d_fft_gemm(x, W, y, K: int, stream=None):
 
 def spectral_conv1d_gemm_ifft(x, W, y, K: int, stream=None):
     return _call("tfno_spectral_conv1d_gemm_ifft", 1, 4, x, W, y, K, stream)
+
+
+def spectral_conv1d_auto(x, W, y, K: int, stream=None):
+    return _call("tfno_spectral_conv1d_auto", 1, 5, x, W, y, K, stream)

@@ -146,6 +146,17 @@ tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
 
+// Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
+// sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels
+// (C_out <= 128); above that every 128-output slab repeats the forward transform of its batch row, and the
+// CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins by 4-26 %.
+Variant choose_variant(int N, int K, int C_out)
+{
+    if (C_out > 128 && fused1d_partial_supported(N, K)) return GEMM_IFFT;
+    if (fused1d_supported(N, K)) return FUSED;
+    return STAGED;
+}
+
 }  // namespace
 
 namespace tfno {
@@ -246,6 +257,12 @@ tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y
     return run(1, GEMM_IFFT, x, W, y, B, C_in, C_out, N, K, stream);
 }
 
+tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                      void *stream)
+{
+    return run(1, choose_variant(N, K, C_out), x, W, y, B, C_in, C_out, N, K, stream);
+}
+
 tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
                                         int K, void *stream)
 {
@@ -260,6 +277,10 @@ tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y, i
 
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K)
 {
+    if (variant == 5) {
+        if (dims != 1) return 0;
+        variant = (int)choose_variant(N, K, C_out);
+    }
     const int staged = variant == 1;
     if (variant < 0 || variant > 4) return 0;
     if (variant == 2) {

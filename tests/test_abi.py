@@ -92,7 +92,11 @@ def test_workspace_contract(L):
     assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 64) == 8 * 2 * 128 * 16
     assert binding.workspace_bytes(1, 3, 4, 16, 48, 1024, 64) == 0        # N in {128, 256} only
     assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 16) == 0         # K in {32, 64, 128} only
-    assert binding.workspace_bytes(1, 5, 4, 16, 48, 256, 64) == 0
+    # per-shape dispatch: the workspace of the variant it picks
+    assert binding.workspace_bytes(1, 5, 4, 16, 48, 256, 64) == 0                         # fused
+    assert binding.workspace_bytes(1, 5, 4, 16, 200, 256, 64) == 8 * 2 * 128 * 16         # CGEMM + iFFT
+    assert binding.workspace_bytes(1, 5, 2, 3, 4, 2048, 100) == binding.workspace_bytes(1, 1, 2, 3, 4, 2048, 100)
+    assert binding.workspace_bytes(1, 6, 4, 16, 48, 256, 64) == 0
     assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)

@@ -126,6 +126,21 @@ def test_1d_partially_fused_variants(gpu, oracle_mod, shape, fn):
     check(run_gpu(gpu, fn, x, W, K), want, fn)
 
 
+# per-shape dispatch: CGEMM + iFFT variant (C_out > 128 where it exists), fused kernel, staged path
+AUTO_1D = [(2, 16, 256, 256, 64), (3, 20, 130, 128, 32), (2, 16, 64, 256, 64), (2, 9, 200, 1024, 128),
+           (2, 4, 4, 2048, 100), (2, 5, 3, 256, 48), (2, 40, 300, 256, 128)]
+
+
+@pytest.mark.parametrize("shape", AUTO_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_auto_dispatch(gpu, oracle_mod, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] spectral_conv1d_auto {shape}")
+    x = inputs.make_x(600 + N + K, B, Ci, (N,))
+    W = inputs.make_W(600 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    check(run_gpu(gpu, "spectral_conv1d_auto", x, W, K), want, "auto")
+
+
 def test_1d_pruned_unsupported_shapes(gpu):
     torch, binding = gpu
     for (N, K) in [(512, 64), (1024, 32), (256, 48), (64, 8), (2048, 128)]:
