@@ -126,12 +126,15 @@ def cpu_baseline(w):
     x = np.stack([inputs.make_x_element(w.seed, b, w.C_in, w.spatial) for b in range(nb)])
     W = inputs.make_W(w.seed, w.C_in, w.C_out)
     fn = oracle.spectral_conv1d if w.dims == 1 else oracle.spectral_conv2d
+    reps = 0
     t0 = time.perf_counter()
-    _, used = fn(x, W, w.K)
-    dt = time.perf_counter() - t0
+    while reps < 3 or (time.perf_counter() - t0 < 1.0 and reps < 20):    # about 15-30 core-seconds in all
+        _, used = fn(x, W, w.K)
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
     return {"value": (nb / w.B) / dt, "unit": "layers/s", "cores": int(used), "kind": "oracle",
-            "sample": f"{nb} of {w.B} batch elements of {w.name}, float64, {dt:.2f} s wall; "
-                      f"layers/s scaled by {nb}/{w.B}"}
+            "sample": f"{nb} of {w.B} batch elements of {w.name}, float64, mean of {reps} passes, {dt:.2f} s wall "
+                      f"each on {int(used)} threads; layers/s scaled by {nb}/{w.B}"}
 
 
 def main():
@@ -140,6 +143,8 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--variant", default="fused", choices=["fused", "staged", "pruned", "fft_gemm", "gemm_ifft", "auto"],
+                    help="entry point timed as the main measurement (1-D workloads; default: the fused kernel)")
     ap.add_argument("--ramp", type=float, default=RAMP_SECONDS,
                     help="seconds of untimed calls before the warm-up steps that bring the engine clock from idle to "
                          "its sustained value (0 for counter-collection runs, where every launch is slow)")
@@ -195,7 +200,8 @@ def main():
         return
 
     w = pick_config(args.config)
-    wall, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp)
+    vid = ["fused", "staged", "pruned", "fft_gemm", "gemm_ifft", "auto"].index(args.variant)
+    wall, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp, variant=vid)
     ms_per_step = wall / args.steps * 1e3
     layers_per_s = args.steps / wall
     alg_bytes = w.compulsory_bytes
@@ -222,7 +228,8 @@ def main():
         "buffer_sets": buffer_sets(w),
         "clock_ramp_s": args.ramp,
         "config": {"workload": w.name, "dims": w.dims, "B": w.B, "C_in": w.C_in, "C_out": w.C_out,
-                   "N": w.N, "K": w.K, "seed": w.seed, "entry_point": "tfno_spectral_conv%dd" % w.dims},
+                   "N": w.N, "K": w.K, "seed": w.seed,
+                   "entry_point": "tfno_spectral_conv%dd" % w.dims + VARIANT_SUFFIX[vid]},
         "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
         "effective_hbm_frac_of_peak": alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "contraction_TFLOPs": flops_of(w) / dev / 1e12,

@@ -87,6 +87,9 @@ struct FusedCfg {
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
     static_assert(TPW * 32 <= 128, "accumulators must fit the register file");
     static constexpr bool FITS = LDS_BYTES <= 160 * 1024;           // LDS budget of one gfx950 CU
+    // Two workgroups per CU (two waves per SIMD, 256 registers each) wherever the accumulators leave room and LDS
+    // allows: left to itself the compiler takes more than 256 registers for TPW = 2 and halves the occupancy.
+    static constexpr int MIN_WG_PER_CU = (TPW <= 2 && LDS_BYTES <= 80 * 1024) ? 2 : 1;
 };
 
 // Orders this wave's LDS traffic (all lanes) without a workgroup barrier.
@@ -101,7 +104,7 @@ __device__ __forceinline__ void wave_sync()
 // MODE 0: fully fused.  MODE 1: FFT + CGEMM (Sec. 4.1), the accumulators leave as the truncated output spectrum
 // a.Yh.  MODE 2: CGEMM + iFFT (Sec. 4.2), the operand tiles come from the truncated input spectrum a.Xh.
 template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, (FusedCfg<N, K, OT, BF>::MIN_WG_PER_CU))
 k_fused1d(Fused1dArgs a)
 {
     using C = FusedCfg<N, K, OT, BF>;
@@ -216,11 +219,28 @@ k_fused1d(Fused1dArgs a)
             const int j = item / P, p = item % P;
             const c64 *zcol = Zw + j * ZS + p * ZROW;
             c64 xo[Q];
-            dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
-                constexpr int tt = decltype(ttc)::value;
-                if constexpr (tt == 0) return zcol[0];
-                else return cmul(zcol[tt], TW[tt * P + p]);
-            }, xo);
+            if constexpr (T <= 16 && C::TPW <= 1) {
+                // all LDS reads of the column are issued before the first use: left alone, the compiler reads,
+                // waits and multiplies one pair at a time (T exposed LDS round trips per column)
+                c64 zc[T], tw[T];
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt) {
+                    zc[tt] = zcol[tt];
+                    if (tt != 0) tw[tt] = TW[tt * P + p];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
+                    constexpr int tt = decltype(ttc)::value;
+                    if constexpr (tt == 0) return zc[0];
+                    else return cmul(zc[tt], tw[tt]);
+                }, xo);
+            } else {
+                dft_prune_out<T, Q, -1>([&](auto ttc) __attribute__((always_inline)) {
+                    constexpr int tt = decltype(ttc)::value;
+                    if constexpr (tt == 0) return zcol[0];
+                    else return cmul(zcol[tt], TW[tt * P + p]);
+                }, xo);
+            }
             const int jg = wave * PPW + j;
 #pragma unroll
             for (int q = 0; q < Q; ++q) put_operand(XHb, jg, p + P * q, xo[q]);
