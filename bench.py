@@ -263,6 +263,17 @@ def main():
                                            "kernel": "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)",
                                            "algorithmic_bytes_per_launch": w4.compulsory_bytes,
                                            "avg_launch_ms": dev4 * 1e3}}
+            # the remaining configurations, fused entry point only: the two small 1-D shapes and the twelve cells
+            # of the hidden-dimension sweep (all variants of the sweep: --sweep)
+            from paper_2504_11681_amd import inputs
+            others = []
+            for wo in [pick_config("cfg1"), pick_config("cfg2")] + list(inputs.sweep_configs()):
+                _, devo = measure(wo, torch, binding, max(50, args.steps // 4), max(10, args.warmup // 4), ramp=args.ramp / 3)
+                others.append({"workload": wo.name, "us_per_layer": devo * 1e6, "layers_per_s": 1.0 / devo,
+                               "effective_hbm_GBps": wo.compulsory_bytes / devo / 1e9,
+                               "hbm_frac": wo.compulsory_bytes / devo / 1e9 / HBM_PEAK_GBPS,
+                               "contraction_TFLOPs": flops_of(wo) / devo / 1e12})
+            out["other_configs"] = others
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
 
