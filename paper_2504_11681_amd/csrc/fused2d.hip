@@ -18,6 +18,15 @@ size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K)
 hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,
                               hipStream_t s)
 {
+    if (!contraction_forced_f32() && C_in <= 64) {
+        // one block of W: the straight-line kernel, two mode tiles per workgroup
+        const dim3 g2((unsigned)((tiles + 1) / 2), (unsigned)((C_out + 63) / 64));
+        if (C_in <= 32)
+            hipLaunchKernelGGL(k_cgemm_modes_small<4>, g2, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, scale, tiles);
+        else
+            hipLaunchKernelGGL(k_cgemm_modes_small<8>, g2, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, scale, tiles);
+        return hipGetLastError();
+    }
     // about two workgroups per CU, each walking several mode tiles
     const int tpw = tiles >= 1024 ? (int)(tiles / 512 > 16 ? 16 : tiles / 512) : 1;
     const dim3 ggrid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64));
