@@ -63,6 +63,25 @@ TFNO_HD c64 mac_tw(c64 acc, c64 a)
     }
 }
 
+// lo = e + w o, hi = e - w o with w = exp(DIR * 2 pi i * M / L).  For a general twiddle the product is folded into
+// the sum (4 FMAs) and hi = 2 e - lo (2 FMAs): 6 instructions instead of 8.
+template <int L, int DIR, int M>
+TFNO_HD void butterfly_tw(c64 e, c64 o, c64 &lo, c64 &hi)
+{
+    constexpr int m = (((M % L) + L) % L) * (32 / L);
+    if constexpr (m % 8 == 0) {
+        const c64 t = mul_tw<L, DIR, M>(o);
+        lo = cadd(e, t);
+        hi = csub(e, t);
+    } else {
+        constexpr float c = cos32(m), s = DIR * sin32(m);
+        lo.x = fmaf(-o.y, s, fmaf(o.x, c, e.x));
+        lo.y = fmaf(o.x, s, fmaf(o.y, c, e.y));
+        hi.x = fmaf(2.f, e.x, -lo.x);
+        hi.y = fmaf(2.f, e.y, -lo.y);
+    }
+}
+
 // Recursive radix-2 decimation in time on registers.  in[i * STRIDE], i < L  ->  out[k], k < L.
 template <int L, int DIR, int STRIDE = 1>
 struct RegFFT {
@@ -73,9 +92,7 @@ struct RegFFT {
         RegFFT<L / 2, DIR, 2 * STRIDE>::run(in + STRIDE, o);
         static_for<0, L / 2>([&](auto kc) {
             constexpr int k = decltype(kc)::value;
-            c64 t = mul_tw<L, DIR, k>(o[k]);
-            out[k] = cadd(e[k], t);
-            out[k + L / 2] = csub(e[k], t);
+            butterfly_tw<L, DIR, k>(e[k], o[k], out[k], out[k + L / 2]);
         });
     }
 };
