@@ -75,6 +75,19 @@ def time_calls(torch, fn, steps: int, warmup: int, ramp: float = RAMP_SECONDS):
     return wall, dev
 
 
+def per_call_stats(torch, fn, n: int = 100):
+    """Median and minimum device time of single calls (seconds), each bracketed by its own pair of HIP events on the
+    launch stream; run right after the timed region, so the clock is still at its sustained value."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) * 1e-3 for a, b in ev)
+    return t[len(t) // 2], t[0]
+
+
 def flops_of(w):
     """Contraction flops on the retained modes (8 real flops per complex MAC)."""
     return 8.0 * w.B * (w.K ** w.dims) * w.C_in * w.C_out
@@ -91,7 +104,8 @@ def buffer_sets(w):
 VARIANT_SUFFIX = ("", "_staged", "_pruned", "_fft_gemm", "_gemm_ifft", "_auto")
 
 
-def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=RAMP_SECONDS, variant=None):
+def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=RAMP_SECONDS, variant=None,
+            stats=None):
     """variant: 0 fused, 1 staged (five kernels), 2 pruned (three kernels), 3 FFT+CGEMM fused, 4 CGEMM+iFFT fused,
     5 per-shape dispatch."""
     xd, Wd, yd = device_inputs(w, torch)
@@ -110,6 +124,8 @@ def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=R
         fn(xi, Wd, yi, w.K, stream)
 
     wall, dev = time_calls(torch, call, steps, warmup, ramp)
+    if stats is not None:
+        stats["median_s"], stats["min_s"] = per_call_stats(torch, call)
     del xd, Wd, yd, sets
     torch.cuda.empty_cache()
     return wall, dev
@@ -201,7 +217,8 @@ def main():
 
     w = pick_config(args.config)
     vid = ["fused", "staged", "pruned", "fft_gemm", "gemm_ifft", "auto"].index(args.variant)
-    wall, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp, variant=vid)
+    st = {}
+    wall, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp, variant=vid, stats=st)
     ms_per_step = wall / args.steps * 1e3
     layers_per_s = args.steps / wall
     alg_bytes = w.compulsory_bytes
@@ -236,7 +253,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "fused 1-D kernel (k_fused1d_sym for N = 1024, K in {64, 128}; k_fused1d_ws / k_fused1d otherwise)" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
-                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": dev * 1e3},
+                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": dev * 1e3,
+                     "median_launch_ms": st["median_s"] * 1e3, "min_launch_ms": st["min_s"] * 1e3},
     }
 
     if not args.no_extras:

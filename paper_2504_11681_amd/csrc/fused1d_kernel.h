@@ -36,10 +36,8 @@
 #include "bf16x3.h"
 
 #ifndef TFNO_STAMP
-#define TFNO_STAMP(i)   // phase-timestamp hooks of the development harness; empty in the library
-#endif
-#ifndef TFNO_STEP_STAMP
-#define TFNO_STEP_STAMP(it, i)
+#define TFNO_STAMP(i)   // four phase-timestamp hooks (start, after prologue, after k-loop, end) that a timing
+                        // harness may define before including this header; empty in the library
 #endif
 
 namespace tfno {
@@ -305,23 +303,17 @@ k_fused1d(Fused1dArgs a)
         constexpr bool DO_B = decltype(do_b)::value, DO_A = decltype(do_a)::value, DO_LOAD = decltype(do_load)::value;
         const int cur = it & 1;
         c64 wn[NWV];
-        TFNO_STEP_STAMP(it, 0);
         if constexpr (DO_B) load_w(wn, (it + 1) * PPI);
         if constexpr (ALLT) mfma_block(cur);
         else if (has_tiles) mfma_block(cur);
-        TFNO_STEP_STAMP(it, 1);
         if constexpr (DO_B) { stage_b(cur ^ 1); wave_sync(); }
-        TFNO_STEP_STAMP(it, 2);
         if constexpr (DO_A) { stage_a(); wave_sync(); }
-        TFNO_STEP_STAMP(it, 3);
         if constexpr (DO_LOAD) load_pencil((it + 3) * PPI);
-        TFNO_STEP_STAMP(it, 4);
         if constexpr (DO_B) {
 #pragma unroll
             for (int jc = 0; jc < NWV; ++jc) wv[jc] = wn[jc];
             __syncthreads();
         }
-        TFNO_STEP_STAMP(it, 5);
     };
     const std::true_type yes{};
     const std::false_type no{};

@@ -80,10 +80,6 @@ k_fused1d_sym(Fused1dArgs a)
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
 
     TFNO_STAMP(0);
-#ifdef TFNO_DBG_SKEW
-    // timing experiment: start the workgroups of an XCD in four phases a fraction of an iteration apart
-    for (int i = 0; i < (int)((blockIdx.x >> 3) & 3); ++i) __builtin_amdgcn_s_sleep(TFNO_DBG_SKEW);
-#endif
     const int n_it = (a.C_in + PPI - 1) / PPI;
     c64 *patch = patch_all + wave * C::PATCH;
     const int p = lane;                                 // row-stage identity

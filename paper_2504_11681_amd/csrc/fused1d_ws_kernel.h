@@ -34,9 +34,6 @@
 #include "fused1d_kernel.h"
 #include "bf16x3.h"
 
-#ifndef TFNO_WS_STAMP
-#define TFNO_WS_STAMP(role, it, i)   // development hook, empty in the library
-#endif
 
 #include <type_traits>
 
@@ -74,11 +71,7 @@ k_fused1d_ws(Fused1dArgs a)
     __shared__ c64 TW[N];                                                     // [t][p]: w_N^(t p)
 
     const int tid = threadIdx.x;
-#ifdef TFNO_DBG_M_FIRST
-    const int lane = tid & 63, wave = (tid >> 6) ^ 4;       // hardware waves 0-3 take the M role
-#else
     const int lane = tid & 63, wave = tid >> 6;
-#endif
     const int bb = blockIdx.x;
     const int o_base = blockIdx.y * 128;
 
@@ -192,14 +185,9 @@ k_fused1d_ws(Fused1dArgs a)
         TFNO_STAMP(1);
         int it = 0;
         for (; it + 2 < n_it; ++it) {                       // blocks 1 .. n_it - 2, each refilling v with its successor
-            TFNO_WS_STAMP(0, it, 0);
-#ifndef TFNO_DBG_NO_F
             row_stage(refill, (it + 2) * PPI);
             col_stage((it + 1) & 1);
-#endif
-            TFNO_WS_STAMP(0, it, 1);
             __syncthreads();
-            TFNO_WS_STAMP(0, it, 2);
         }
         if (it + 1 < n_it) {                                // the last block: nothing left to load
             row_stage(last, 0);
@@ -228,9 +216,6 @@ k_fused1d_ws(Fused1dArgs a)
 
     // ====================================================================== M waves: column stage + matrix pipe
     const int m = wave - 4;
-#ifdef TFNO_DBG_M_PRIO
-    __builtin_amdgcn_s_setprio(TFNO_DBG_M_PRIO);
-#endif
     const int o_lane = o_base + 32 * m + p;     // the output channel whose W this lane feeds
     const int ztile = (m * 2 + h) * ZS + p * 32;            // row p of the tile = column p of the pencil
     floatx16 acc_re[Q], acc_im[Q];
@@ -300,17 +285,11 @@ k_fused1d_ws(Fused1dArgs a)
     __syncthreads();                                        // P2: XS[0] holds block 0
     for (int it = 0; it < n_it; ++it) {
         const bool more = it + 1 < n_it;
-        TFNO_WS_STAMP(1, it, 0);
         if (more) load_w((it + 1) * PPI);
-#ifndef TFNO_DBG_NO_MFMA
         mfma_block(it & 1);
-#endif
-        TFNO_WS_STAMP(1, it, 1);
         if (more) {
             split_w();
-            TFNO_WS_STAMP(1, it, 3);
             __syncthreads();
-            TFNO_WS_STAMP(1, it, 4);
         }
     }
 
