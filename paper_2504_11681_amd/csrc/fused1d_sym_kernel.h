@@ -73,7 +73,7 @@ k_fused1d_sym(Fused1dArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int bb = blockIdx.x;
+    const int bb = (int)xcd_contiguous(blockIdx.x, gridDim.x);
     const int o_base = blockIdx.y * 128;
     const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;

@@ -72,7 +72,7 @@ k_fused1d_ws(Fused1dArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int bb = blockIdx.x;
+    const int bb = (int)xcd_contiguous(blockIdx.x, gridDim.x);
     const int o_base = blockIdx.y * 128;
 
     const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
