@@ -141,6 +141,30 @@ def test_1d_auto_dispatch(gpu, oracle_mod, shape):
     check(run_gpu(gpu, "spectral_conv1d_auto", x, W, K), want, "auto")
 
 
+def random_shapes(seed, count):
+    """Seeded random shapes (B, C_in, C_out, N, K) that every 1-D entry point accepts, small enough for the oracle."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        N = int(rng.choice([128, 256]))
+        K = int(rng.choice([k for k in (32, 64, 128) if k <= N]))
+        out.append((int(rng.integers(1, 6)), int(rng.integers(1, 80)), int(rng.integers(1, 300)), N, K))
+    return out
+
+
+@pytest.mark.parametrize("shape", random_shapes(2025, 12), ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_random_shapes_all_entry_points(gpu, oracle_mod, shape):
+    """Every 1-D entry point on the same random shape (odd channel counts exercise all the masks)."""
+    B, Ci, Co, N, K = shape
+    x = inputs.make_x(700 + Ci + Co, B, Ci, (N,))
+    W = inputs.make_W(700 + Ci + Co, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    for fn in ("spectral_conv1d", "spectral_conv1d_auto", "spectral_conv1d_pruned", "spectral_conv1d_fft_gemm",
+               "spectral_conv1d_gemm_ifft", "spectral_conv1d_staged"):
+        say(f"[case] {fn} random {shape}")
+        check(run_gpu(gpu, fn, x, W, K), want, fn)
+
+
 def test_1d_pruned_unsupported_shapes(gpu):
     torch, binding = gpu
     for (N, K) in [(512, 64), (1024, 32), (256, 48), (64, 8), (2048, 128)]:
