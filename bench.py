@@ -131,6 +131,33 @@ def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=R
     return wall, dev
 
 
+def pytorch_baseline(w, torch, binding, steps, ramp):
+    """The layer as PyTorch composes it from library calls (the structure the paper measures against, Sec. 1 and 5):
+    full FFT, slice, complex matmul over channels, zero pad, full inverse FFT -- rocFFT and the BLAS library under
+    torch.  Timed like the other legs; its result is compared with the fused kernel's once."""
+    xd, Wd, yd = device_inputs(w, torch)
+    dims = tuple(range(2, 2 + w.dims))
+    sl = (Ellipsis,) + (slice(0, w.K),) * w.dims
+    pad = []
+    for _ in range(w.dims):
+        pad += [0, w.N - w.K]
+
+    def layer():
+        Xh = torch.fft.fftn(xd, dim=dims)[sl]
+        Yh = torch.einsum("bc...,co->bo...", Xh, Wd)
+        return torch.fft.ifftn(torch.nn.functional.pad(Yh, pad), dim=dims)
+
+    ref = layer()
+    getattr(binding, "spectral_conv%dd" % w.dims)(xd, Wd, yd, w.K)
+    torch.cuda.synchronize()
+    diff = float((ref - yd).abs().max() / yd.abs().max())
+    del ref
+    wall, dev = time_calls(torch, layer, steps, 2, ramp)
+    del xd, Wd, yd
+    torch.cuda.empty_cache()
+    return wall, dev, diff
+
+
 def cpu_baseline(w):
     """The float64 oracle, as it stands, timed on the host cores over the whole workload (1-D) or
     over a bounded sample of batch elements (2-D)."""
@@ -263,6 +290,12 @@ def main():
         out["staged"] = {"ms_per_step": swall / s_steps * 1e3, "layers_per_s": s_steps / swall,
                          "variant": "five kernels: full FFT, truncate copy, CGEMM, pad copy, full iFFT",
                          "fused_speedup": (swall / s_steps) / (wall / args.steps)}
+        p_steps = max(5, args.steps // 20)
+        pwall, pdev, pdiff = pytorch_baseline(w, torch, binding, p_steps, args.ramp)
+        out["pytorch"] = {"ms_per_step": pwall / p_steps * 1e3, "layers_per_s": p_steps / pwall,
+                          "variant": "torch.fft.fftn, slice, einsum, pad, torch.fft.ifftn (library kernels)",
+                          "fused_speedup": (pwall / p_steps) / (wall / args.steps),
+                          "max_abs_diff_vs_fused_over_max": pdiff}
         if w.name.startswith("cfg3"):
             w4 = pick_config("cfg4")
             steps4 = max(10, args.steps // 4)
