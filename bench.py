@@ -277,6 +277,7 @@ def main():
         "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
         "effective_hbm_frac_of_peak": alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "contraction_TFLOPs": flops_of(w) / dev / 1e12,
+        "contraction_frac_of_fp32_mfma_peak": flops_of(w) / dev / 1e12 / FP32_MFMA_PEAK_TFLOPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "fused 1-D kernel (k_fused1d_sym for N = 1024, K in {64, 128}; k_fused1d_ws / k_fused1d otherwise)" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
@@ -323,7 +324,8 @@ def main():
                 others.append({"workload": wo.name, "us_per_layer": devo * 1e6, "layers_per_s": 1.0 / devo,
                                "effective_hbm_GBps": wo.compulsory_bytes / devo / 1e9,
                                "hbm_frac": wo.compulsory_bytes / devo / 1e9 / HBM_PEAK_GBPS,
-                               "contraction_TFLOPs": flops_of(wo) / devo / 1e12})
+                               "contraction_TFLOPs": flops_of(wo) / devo / 1e12,
+                               "contraction_frac_of_fp32_mfma_peak": flops_of(wo) / devo / 1e12 / FP32_MFMA_PEAK_TFLOPS})
             out["other_configs"] = others
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
