@@ -149,7 +149,7 @@ tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
 // sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels
 // (C_out <= 128); above that every 128-output slab repeats the forward transform of its batch row, and the
-// CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins by 3-11 %.
+// CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins by 2-11 %.
 Variant choose_variant(int N, int K, int C_out)
 {
     if (C_out > 128 && fused1d_partial_supported(N, K)) return GEMM_IFFT;
