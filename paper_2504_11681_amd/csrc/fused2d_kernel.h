@@ -152,7 +152,7 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
         const c64 *src = img + (long long)(r + S * s) * N + p;
         if (row_on) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] = src[LPR * j];
+            for (int j = 0; j < 16; ++j) v[j] = load_nt(src + LPR * j);
         }
     };
     // Row transforms of the sweep held in v.  The first butterfly level consumes v, so the loads of the next
