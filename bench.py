@@ -322,6 +322,9 @@ def main():
             for wo in [pick_config("cfg1"), pick_config("cfg2")] + list(inputs.sweep_configs()):
                 _, devo = measure(wo, torch, binding, max(50, args.steps // 4), max(10, args.warmup // 4), ramp=args.ramp / 3)
                 others.append({"workload": wo.name, "us_per_layer": devo * 1e6, "layers_per_s": 1.0 / devo,
+                               # a layer whose bytes would take under 5 us at the HBM peak is bound by launch and
+                               # pipeline latency, not by bandwidth
+                               "bound": "latency" if wo.compulsory_bytes / (HBM_PEAK_GBPS * 1e9) < 5e-6 else "hbm",
                                "effective_hbm_GBps": wo.compulsory_bytes / devo / 1e9,
                                "hbm_frac": wo.compulsory_bytes / devo / 1e9 / HBM_PEAK_GBPS,
                                "contraction_TFLOPs": flops_of(wo) / devo / 1e12,
