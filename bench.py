@@ -101,6 +101,43 @@ def buffer_sets(w):
     return max(2, min(64, -(-(1 << 30) // pair)))
 
 
+def graph_time(w, torch, binding, launches=50, replays=40):
+    """Device time per layer when `launches` fused calls are captured once in a HIP graph and the graph is replayed:
+    what a launch-bound shape costs inside a captured loop.  Every replay is checked against the eager result."""
+    xd, Wd, yd = device_inputs(w, torch)
+    fn = getattr(binding, "spectral_conv%dd" % w.dims)
+    binding.ensure_workspace(binding.workspace_bytes(w.dims, 0, w.B, w.C_in, w.C_out, w.N, w.K), xd.device)
+    fn(xd, Wd, yd, w.K)                                   # eager: first-call setup happens outside the capture
+    torch.cuda.synchronize()
+    want = yd.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        fn(xd, Wd, yd, w.K, side.cuda_stream)
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(launches):
+                fn(xd, Wd, yd, w.K, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    ok = True
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(5):
+        yd.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        ok = ok and bool(torch.equal(yd, want))
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    dt = e0.elapsed_time(e1) * 1e-3 / (replays * launches)
+    del g, xd, Wd, yd, want
+    torch.cuda.empty_cache()
+    return dt, ok
+
+
 VARIANT_SUFFIX = ("", "_staged", "_pruned", "_fft_gemm", "_gemm_ifft", "_auto")
 
 
@@ -329,6 +366,10 @@ def main():
                                "hbm_frac": wo.compulsory_bytes / devo / 1e9 / HBM_PEAK_GBPS,
                                "contraction_TFLOPs": flops_of(wo) / devo / 1e12,
                                "contraction_frac_of_fp32_mfma_peak": flops_of(wo) / devo / 1e12 / FP32_MFMA_PEAK_TFLOPS})
+                if others[-1]["bound"] == "latency":
+                    gdt, gok = graph_time(wo, torch, binding)
+                    others[-1]["us_per_layer_in_hip_graph"] = gdt * 1e6
+                    others[-1]["hip_graph_replays_match_eager"] = gok
             out["other_configs"] = others
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
