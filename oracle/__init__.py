@@ -39,6 +39,8 @@ def _load():
             fn = getattr(lib, name)
             fn.restype = c_int
             fn.argtypes = [c_void, c_void, c_void] + [c_int] * 6
+        lib.oracle_spectral_conv2d_rect.restype = c_int
+        lib.oracle_spectral_conv2d_rect.argtypes = [c_void, c_void, c_void] + [c_int] * 8
         lib.oracle_forward_spectrum1d.restype = c_int
         lib.oracle_forward_spectrum1d.argtypes = [c_void, c_void, c_int, c_int]
         for name in ("oracle_fft_c128", "oracle_fft_radix2_c128", "oracle_dft_direct_c128"):
@@ -84,6 +86,20 @@ def spectral_conv2d(x: np.ndarray, W: np.ndarray, K: int, threads: int = 0):
                                           B, C_in, C_out, N, K, threads)
     if used < 0:
         raise ValueError("oracle_spectral_conv2d: bad arguments")
+    return y, used
+
+
+def spectral_conv2d_rect(x: np.ndarray, W: np.ndarray, K1: int, K2: int, threads: int = 0):
+    """y[B,C_out,N1,N2] (complex128) for x[B,C_in,N1,N2], W[C_in,C_out] (complex64); modes k1 < K1, k2 < K2."""
+    x, W = _c64(x), _c64(W)
+    B, C_in, N1, N2 = x.shape
+    C_in2, C_out = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N1, N2), dtype=np.complex128)
+    used = _load().oracle_spectral_conv2d_rect(x.ctypes.data, W.ctypes.data, y.ctypes.data,
+                                               B, C_in, C_out, N1, N2, K1, K2, threads)
+    if used < 0:
+        raise ValueError("oracle_spectral_conv2d_rect: bad arguments")
     return y, used
 
 

@@ -19,7 +19,9 @@
  *   Yh[b,o,k] = sum_c  Xh[b,c,k] W[c,o]
  *   y [b,o,n] = (1/N) sum_{k<K} Yh[b,o,k] exp(+2 pi i k n / N)   n = 0..N-1
  *
- * and in 2-D the same with (n1,n2), (k1,k2) in [0,K)x[0,K), scale 1/N^2.
+ * and in 2-D the same with (n1,n2), (k1,k2) in [0,K)x[0,K), scale 1/N^2; for a
+ * non-square grid N1 x N2 each axis keeps its own first K1 / K2 bins, scale
+ * 1/(N1 N2).
  *
  * Readings taken where the paper is silent: forward exponent negative, inverse
  * positive and scaled by 1/N per axis (the cuFFT/PyTorch convention the paper
@@ -179,38 +181,42 @@ int oracle_forward_spectrum1d(const float *x, double *Xh, int C, int N)
 
 /* ------------------------------------------------------------------ 2-D -- */
 
-/* In-place full 2-D transform of an N x N row-major image (no scaling):
- * every row along the last axis, then every column along the first. */
-static void fft2_inplace(cplx *img, int N, int sign, cplx *line, cplx *scr)
+/* In-place full 2-D transform of an N1 x N2 row-major image (no scaling):
+ * every row along the last axis (length N2), then every column along the
+ * first (length N1).  line and scr hold max(N1, N2) values. */
+static void fft2_inplace(cplx *img, int N1, int N2, int sign, cplx *line, cplx *scr)
 {
-    for (int r = 0; r < N; ++r) {
-        oracle_fft(img + (size_t)r * N, 1, line, N, sign, scr);
-        memcpy(img + (size_t)r * N, line, sizeof(cplx) * N);
+    for (int r = 0; r < N1; ++r) {
+        oracle_fft(img + (size_t)r * N2, 1, line, N2, sign, scr);
+        memcpy(img + (size_t)r * N2, line, sizeof(cplx) * N2);
     }
-    for (int c = 0; c < N; ++c) {
-        oracle_fft(img + c, N, line, N, sign, scr);
-        for (int r = 0; r < N; ++r) img[(size_t)r * N + c] = line[r];
+    for (int c = 0; c < N2; ++c) {
+        oracle_fft(img + c, N2, line, N1, sign, scr);
+        for (int r = 0; r < N1; ++r) img[(size_t)r * N2 + c] = line[r];
     }
 }
 
-/* One batch element.  x: [C_in, N, N] c64;  y: [C_out, N, N] complex double. */
+/* One batch element.  x: [C_in, N1, N2] c64;  y: [C_out, N1, N2] complex double.
+ * Each transformed axis keeps its own first K_i of N_i bins (Sec. 3.2 / 3.3: the
+ * 2-D transform is separable and truncation / padding act per axis). */
 static void conv2d_one(const float *x, const float *W, cplx *y,
-                       int C_in, int C_out, int N, int K)
+                       int C_in, int C_out, int N1, int N2, int K1, int K2)
 {
-    size_t NN = (size_t)N * N, KK = (size_t)K * K;
+    size_t NN = (size_t)N1 * N2, KK = (size_t)K1 * K2;
+    int NL = N1 > N2 ? N1 : N2;
     cplx *img = malloc(sizeof(cplx) * NN);
-    cplx *line = malloc(sizeof(cplx) * N), *scr = malloc(sizeof(cplx) * N);
+    cplx *line = malloc(sizeof(cplx) * NL), *scr = malloc(sizeof(cplx) * NL);
     cplx *Xh = malloc(sizeof(cplx) * C_in * KK);
     cplx *Yh = malloc(sizeof(cplx) * C_out * KK);
 
     for (int c = 0; c < C_in; ++c) {
         const float *xc = x + 2 * (size_t)c * NN;
         for (size_t i = 0; i < NN; ++i) img[i] = (double)xc[2 * i] + I * (double)xc[2 * i + 1];
-        fft2_inplace(img, N, -1, line, scr);
-        /* keep the single low corner [0,K) x [0,K) */
-        for (int k1 = 0; k1 < K; ++k1)
-            for (int k2 = 0; k2 < K; ++k2)
-                Xh[c * KK + (size_t)k1 * K + k2] = img[(size_t)k1 * N + k2];
+        fft2_inplace(img, N1, N2, -1, line, scr);
+        /* keep the single low corner [0,K1) x [0,K2) */
+        for (int k1 = 0; k1 < K1; ++k1)
+            for (int k2 = 0; k2 < K2; ++k2)
+                Xh[c * KK + (size_t)k1 * K2 + k2] = img[(size_t)k1 * N2 + k2];
     }
     for (int o = 0; o < C_out; ++o)
         for (size_t m = 0; m < KK; ++m) {
@@ -221,26 +227,29 @@ static void conv2d_one(const float *x, const float *W, cplx *y,
             }
             Yh[o * KK + m] = acc;
         }
-    double scale = 1.0 / ((double)N * (double)N);
+    double scale = 1.0 / ((double)N1 * (double)N2);
     for (int o = 0; o < C_out; ++o) {
         for (size_t i = 0; i < NN; ++i) img[i] = 0.0;
-        for (int k1 = 0; k1 < K; ++k1)
-            for (int k2 = 0; k2 < K; ++k2)
-                img[(size_t)k1 * N + k2] = Yh[o * KK + (size_t)k1 * K + k2];
-        fft2_inplace(img, N, +1, line, scr);
+        for (int k1 = 0; k1 < K1; ++k1)
+            for (int k2 = 0; k2 < K2; ++k2)
+                img[(size_t)k1 * N2 + k2] = Yh[o * KK + (size_t)k1 * K2 + k2];
+        fft2_inplace(img, N1, N2, +1, line, scr);
         cplx *yo = y + (size_t)o * NN;
         for (size_t i = 0; i < NN; ++i) yo[i] = img[i] * scale;
     }
     free(img); free(line); free(scr); free(Xh); free(Yh);
 }
 
-/* x: [B, C_in, N, N] c64;  W: [C_in, C_out] c64;  y: [B, C_out, N, N] complex128. */
-int oracle_spectral_conv2d(const float *x, const float *W, double *y,
-                           int B, int C_in, int C_out, int N, int K, int threads)
+/* x: [B, C_in, N1, N2] c64;  W: [C_in, C_out] c64;  y: [B, C_out, N1, N2] complex128.
+ * Modes kept: k1 < K1 along the first axis, k2 < K2 along the last. */
+int oracle_spectral_conv2d_rect(const float *x, const float *W, double *y, int B, int C_in, int C_out,
+                                int N1, int N2, int K1, int K2, int threads)
 {
-    if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N <= 0 || K <= 0 || K > N) return -1;
+    if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N1 <= 0 || N2 <= 0 || K1 <= 0 || K2 <= 0 ||
+        K1 > N1 || K2 > N2)
+        return -1;
     int used = 1;
-    size_t NN = (size_t)N * N;
+    size_t NN = (size_t)N1 * N2;
 #ifdef _OPENMP
     if (threads > 0) omp_set_num_threads(threads);
     #pragma omp parallel
@@ -250,15 +259,22 @@ int oracle_spectral_conv2d(const float *x, const float *W, double *y,
         #pragma omp for schedule(dynamic, 1)
         for (int b = 0; b < B; ++b)
             conv2d_one(x + 2 * (size_t)b * C_in * NN, W, (cplx *)y + (size_t)b * C_out * NN,
-                       C_in, C_out, N, K);
+                       C_in, C_out, N1, N2, K1, K2);
     }
 #else
     (void)threads;
     for (int b = 0; b < B; ++b)
         conv2d_one(x + 2 * (size_t)b * C_in * NN, W, (cplx *)y + (size_t)b * C_out * NN,
-                   C_in, C_out, N, K);
+                   C_in, C_out, N1, N2, K1, K2);
 #endif
     return used;
+}
+
+/* The square case the paper evaluates (Sec. 5): N x N points, K x K modes. */
+int oracle_spectral_conv2d(const float *x, const float *W, double *y,
+                           int B, int C_in, int C_out, int N, int K, int threads)
+{
+    return oracle_spectral_conv2d_rect(x, W, y, B, C_in, C_out, N, N, K, K, threads);
 }
 
 /* Thin complex128 entry points for the pin tests (buffers interleaved doubles). */

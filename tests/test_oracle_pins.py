@@ -233,6 +233,58 @@ def test_2d_transposed_image_gives_transposed_result(oracle_mod):
     assert np.max(np.abs(yt.transpose(0, 1, 3, 2) - y)) < 1e-12
 
 
+# ------------------------------------------------- 2-D op on a non-square grid --
+
+@pytest.mark.parametrize("N1,N2,K1,K2", [(32, 64, 8, 16), (64, 32, 16, 4), (16, 128, 16, 32), (12, 20, 5, 3)])
+def test_rect_matches_numpy_fft2(oracle_mod, N1, N2, K1, K2):
+    B, Ci, Co = 2, 3, 2
+    x = crandn(B, Ci, N1, N2)
+    W = crandn(Ci, Co)
+    y, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    Xh = np.fft.fft2(x.astype(np.complex128))[..., :K1, :K2]
+    pad = np.zeros((B, Co, N1, N2), dtype=np.complex128)
+    pad[..., :K1, :K2] = np.einsum("bcxy,co->boxy", Xh, W.astype(np.complex128))
+    assert np.max(np.abs(np.fft.ifft2(pad) - y)) < 1e-12
+
+
+def test_rect_single_exponential_keeps_each_axis_own_modes(oracle_mod):
+    """A plane wave (k1, k2) survives iff k1 < K1 AND k2 < K2: catches swapped axis lengths or swapped mode counts."""
+    N1, N2, K1, K2 = 16, 64, 4, 24
+    W = crandn(1, 1)
+    n1, n2 = np.meshgrid(np.arange(N1), np.arange(N2), indexing="ij")
+    for (k1, k2), keep in [((0, 0), True), ((K1 - 1, K2 - 1), True), ((2, 20), True), ((K1, 0), False),
+                           ((0, K2), False), ((3, K2), False), ((K1, K2 - 1), False), ((N1 - 1, N2 - 1), False)]:
+        x = np.exp(2j * np.pi * (k1 * n1 / N1 + k2 * n2 / N2))[None, None].astype(np.complex64)
+        y, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+        if keep:
+            assert np.max(np.abs(y[0, 0] - W[0, 0].astype(np.complex128) * x[0, 0])) < 5e-6
+        else:
+            assert np.max(np.abs(y)) < 5e-6
+
+
+def test_rect_transpose_swaps_axes_and_square_case_is_the_square_function(oracle_mod):
+    N1, N2, K1, K2 = 32, 16, 8, 2
+    x = crandn(1, 2, N1, N2)
+    W = crandn(2, 3)
+    y, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    yt, _ = oracle_mod.spectral_conv2d_rect(np.ascontiguousarray(x.transpose(0, 1, 3, 2)), W, K2, K1)
+    assert np.max(np.abs(yt.transpose(0, 1, 3, 2) - y)) < 1e-12
+    xs = crandn(1, 2, 32, 32)
+    a, _ = oracle_mod.spectral_conv2d_rect(xs, W, 8, 8)
+    b, _ = oracle_mod.spectral_conv2d(xs, W, 8)
+    assert np.array_equal(a, b)
+
+
+def test_rect_with_one_row_is_the_1d_operator(oracle_mod):
+    """N1 = K1 = 1 reduces the 2-D operator to the 1-D one along the last axis."""
+    B, Ci, Co, N, K = 2, 3, 2, 64, 16
+    x = crandn(B, Ci, 1, N)
+    W = crandn(Ci, Co)
+    y2, _ = oracle_mod.spectral_conv2d_rect(x, W, 1, K)
+    y1, _ = oracle_mod.spectral_conv1d(np.ascontiguousarray(x[:, :, 0, :]), W, K)
+    assert np.max(np.abs(y2[:, :, 0, :] - y1)) < 1e-13
+
+
 # ------------------------------------------------------ facts the paper prints --
 
 def _needed_ops_radix2(N, kept):
