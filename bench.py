@@ -168,6 +168,32 @@ def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=R
     return wall, dev
 
 
+def measure_rect(torch, binding, B, C, N1, N2, K1, K2, steps, warmup, ramp):
+    """Device seconds per layer of the non-square 2-D entry point on seeded inputs of the usual recipe."""
+    from paper_2504_11681_amd import inputs
+    seed = 6
+    xd = torch.empty((B, C, N1, N2), dtype=torch.complex64, device="cuda")
+    for b in range(B):
+        xd[b] = torch.from_numpy(inputs.make_x_element(seed, b, C, (N1, N2))).cuda()
+    Wd = torch.from_numpy(inputs.make_W(seed, C, C)).cuda()
+    pair = 16 * B * C * N1 * N2
+    nsets = max(2, min(64, -(-(1 << 30) // pair)))
+    sets = [(xd, torch.zeros_like(xd))] + [(xd.clone(), torch.zeros_like(xd)) for _ in range(nsets - 1)]
+    binding.ensure_workspace(binding.workspace_bytes_2d(0, B, C, C, N1, N2, K1, K2), xd.device)
+    stream = torch.cuda.current_stream().cuda_stream
+    turn = [0]
+
+    def call():
+        xi, yi = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        binding.spectral_conv2d_rect(xi, Wd, yi, K1, K2, stream)
+
+    _, dev = time_calls(torch, call, steps, warmup, ramp)
+    del xd, Wd, sets
+    torch.cuda.empty_cache()
+    return dev
+
+
 def pytorch_baseline(w, torch, binding, steps, ramp):
     """The layer as PyTorch composes it from library calls (the structure the paper measures against, Sec. 1 and 5):
     full FFT, slice, complex matmul over channels, zero pad, full inverse FFT -- rocFFT and the BLAS library under
@@ -371,6 +397,16 @@ def main():
                     others[-1]["us_per_layer_in_hip_graph"] = gdt * 1e6
                     others[-1]["hip_graph_replays_match_eager"] = gok
             out["other_configs"] = others
+            # non-square 2-D grids (same image kernels, each axis with its own length and mode count)
+            rect = []
+            for (Br, Cr, N1, N2, K1, K2) in [(32, 64, 128, 256, 32, 64), (32, 64, 256, 128, 64, 32), (64, 64, 64, 256, 16, 64)]:
+                devr = measure_rect(torch, binding, Br, Cr, N1, N2, K1, K2, max(50, args.steps // 4),
+                                    max(10, args.warmup // 4), args.ramp / 3)
+                nbytes = 16 * Br * Cr * N1 * N2
+                rect.append({"workload": f"rect_2d_B{Br}_C{Cr}_N{N1}x{N2}_K{K1}x{K2}", "us_per_layer": devr * 1e6,
+                             "layers_per_s": 1.0 / devr, "bound": "hbm", "effective_hbm_GBps": nbytes / devr / 1e9,
+                             "hbm_frac": nbytes / devr / 1e9 / HBM_PEAK_GBPS})
+            out["rect_2d"] = rect
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
 

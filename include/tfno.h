@@ -98,6 +98,26 @@ tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y,
                                         int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
+ * 2-D spectral convolution on a non-square grid (the separable pipeline of Sec. 3.2 / 3.3 with each axis keeping
+ * its own modes; the paper evaluates the square case):
+ *
+ *   y[b,o] = iFFT2( pad_N1xN2( sum_c trunc_K1xK2( FFT2(x[b,c]) ) * W[c,o] ) )      (iFFT2 scaled by 1 / (N1 N2))
+ *
+ * x is [B, C_in, N1, N2] and y [B, C_out, N1, N2], row-major with N2 contiguous; the modes kept are k1 < K1 along
+ * the first spatial axis and k2 < K2 along the last.  N1, N2 powers of two in [2, 4096], 1 <= K1 <= N1,
+ * 1 <= K2 <= N2.  N1, N2 in {64,128,256} with K1, K2 in {16,32,64} run the image kernels of
+ * tfno_spectral_conv2d (workspace 8 B K1 K2 (C_in + C_out) bytes); other shapes whose last axis (N2, K2) the fused
+ * 1-D kernel supports run the strip pipeline (workspace 8 B K1 N2 (C_in + C_out) bytes); the rest return
+ * TFNO_ERR_UNSUPPORTED from the fused entry point.  The staged twin accepts every valid shape.  Pointer, aliasing,
+ * stream and error rules as for tfno_spectral_conv2d; with N1 = N2 and K1 = K2 the calls are identical to
+ * tfno_spectral_conv2d / tfno_spectral_conv2d_staged.  Workspace sizes: tfno_workspace_bytes_2d.
+ */
+tfno_status tfno_spectral_conv2d_rect(const void *x, const void *W, void *y, int B, int C_in, int C_out,
+                                      int N1, int N2, int K1, int K2, void *stream);
+tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out,
+                                             int N1, int N2, int K1, int K2, void *stream);
+
+/*
  * 1-D spectral convolution as three launches with truncation, zero padding and butterfly pruning built into the
  * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and
@@ -143,6 +163,8 @@ tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y,
  * (tfno_spectral_conv1d_auto).  Returns 0 when none is needed or the arguments are invalid.
  */
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K);
+/* The same for the non-square 2-D entry points: variant = 0 (tfno_spectral_conv2d_rect) or 1 (its staged twin). */
+size_t tfno_workspace_bytes_2d(int variant, int B, int C_in, int C_out, int N1, int N2, int K1, int K2);
 
 /*
  * Registers a caller-owned device buffer as the library's workspace for all

@@ -23,13 +23,17 @@ EXPORTS = (
     "tfno_spectral_conv1d_fft_gemm",
     "tfno_spectral_conv1d_gemm_ifft",
     "tfno_spectral_conv1d_auto",
+    "tfno_spectral_conv2d_rect",
+    "tfno_spectral_conv2d_rect_staged",
     "tfno_workspace_bytes",
+    "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
     "tfno_status_string",
     "tfno_version",
 )
 
 CONV_EXPORTS = EXPORTS[:8]   # the entry points with the (x, W, y, B, C_in, C_out, N, K, stream) signature
+RECT_EXPORTS = EXPORTS[8:10]  # (x, W, y, B, C_in, C_out, N1, N2, K1, K2, stream)
 
 _lib = None
 _workspace = None     # the torch tensor currently registered as workspace (kept alive here)
@@ -54,8 +58,14 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        for name in RECT_EXPORTS:
+            fn = getattr(L, name)
+            fn.restype = ci
+            fn.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
         L.tfno_workspace_bytes.restype = ctypes.c_size_t
         L.tfno_workspace_bytes.argtypes = [ci] * 7
+        L.tfno_workspace_bytes_2d.restype = ctypes.c_size_t
+        L.tfno_workspace_bytes_2d.argtypes = [ci] * 8
         L.tfno_set_workspace.restype = ci
         L.tfno_set_workspace.argtypes = [vp, ctypes.c_size_t]
         L.tfno_status_string.restype = ctypes.c_char_p
@@ -78,6 +88,11 @@ def workspace_bytes(dims: int, variant, B: int, C_in: int, C_out: int, N: int, K
     """variant: 0 / False = fused entry point, 1 / True = staged twin, 2 = spectral_conv1d_pruned,
     3 = spectral_conv1d_fft_gemm, 4 = spectral_conv1d_gemm_ifft, 5 = spectral_conv1d_auto."""
     return lib().tfno_workspace_bytes(dims, int(variant), B, C_in, C_out, N, K)
+
+
+def workspace_bytes_2d(variant, B: int, C_in: int, C_out: int, N1: int, N2: int, K1: int, K2: int) -> int:
+    """Non-square 2-D entry points: variant 0 / False = spectral_conv2d_rect, 1 / True = its staged twin."""
+    return lib().tfno_workspace_bytes_2d(int(variant), B, C_in, C_out, N1, N2, K1, K2)
 
 
 def set_workspace(tensor) -> None:
@@ -151,3 +166,31 @@ def spectral_conv1d_gemm_ifft(x, W, y, K: int, stream=None):
 
 def spectral_conv1d_auto(x, W, y, K: int, stream=None):
     return _call("tfno_spectral_conv1d_auto", 1, 5, x, W, y, K, stream)
+
+
+def _call_rect(name: str, variant, x, W, y, K1: int, K2: int, stream):
+    import torch
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if t.dtype != torch.complex64 or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous complex64 device tensor")
+    if x.dim() != 4 or y.dim() != 4 or W.dim() != 2:
+        raise ValueError("x, y must be [B, C, N1, N2]; W must be [C_in, C_out]")
+    B, C_in, N1, N2 = x.shape
+    C_out = W.shape[1]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out, N1, N2):
+        raise ValueError("inconsistent tensor shapes")
+    ensure_workspace(workspace_bytes_2d(variant, B, C_in, C_out, N1, N2, K1, K2), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = getattr(lib(), name)(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N1, N2, K1, K2, stream)
+    if st != OK:
+        raise TfnoError(st, name)
+    return y
+
+
+def spectral_conv2d_rect(x, W, y, K1: int, K2: int, stream=None):
+    return _call_rect("tfno_spectral_conv2d_rect", False, x, W, y, K1, K2, stream)
+
+
+def spectral_conv2d_rect_staged(x, W, y, K1: int, K2: int, stream=None):
+    return _call_rect("tfno_spectral_conv2d_rect_staged", True, x, W, y, K1, K2, stream)

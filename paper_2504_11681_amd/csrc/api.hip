@@ -25,31 +25,51 @@ bool overlaps(const void *a, size_t abytes, const void *b, size_t bbytes)
     return a0 < b1 && b0 < a1;
 }
 
+// Transformed axes of a call: N1 x N2 points (N2 contiguous) keeping K1 x K2 modes; 1-D calls have N1 = K1 = 1.
+struct Shape {
+    int dims, N1, N2, K1, K2;
+    size_t pts() const { return (size_t)N1 * N2; }
+    size_t kpts() const { return (size_t)K1 * K2; }
+    bool image_kernels() const { return dims == 2 && fused2d_supported(N1, N2, K1, K2); }
+};
+Shape shape1d(int N, int K) { return Shape{1, 1, N, 1, K}; }
+Shape shape2d(int N1, int N2, int K1, int K2) { return Shape{2, N1, N2, K1, K2}; }
+
+bool axis_ok(int N, int K) { return N >= 2 && N <= 4096 && is_pow2(N) && K >= 1 && K <= N; }
+bool sizes_ok(const Shape &sh, int B, int C_in, int C_out)
+{
+    return B >= 0 && C_in >= 1 && C_out >= 1 && axis_ok(sh.N2, sh.K2) && (sh.dims == 1 || axis_ok(sh.N1, sh.K1));
+}
+
 // Everything that can be decided on the host.  *empty is set for a valid call with nothing to do.
-tfno_status validate(int dims, const void *x, const void *W, const void *y, int B, int C_in, int C_out, int N, int K,
+tfno_status validate(const Shape &sh, const void *x, const void *W, const void *y, int B, int C_in, int C_out,
                      bool *empty)
 {
     *empty = false;
-    if (B < 0 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N) return TFNO_ERR_SHAPE;
+    if (!sizes_ok(sh, B, C_in, C_out)) return TFNO_ERR_SHAPE;
     if (B == 0) { *empty = true; return TFNO_OK; }
     if (!x || !W || !y) return TFNO_ERR_NULL;
-    const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
+    const size_t pts = sh.pts();
     // element counts must stay below 2^40 (byte offsets then fit comfortably in 64 bits) and the
     // launch grids below 2^31 workgroups
     const long double in_elems = (long double)B * C_in * pts, out_elems = (long double)B * C_out * pts;
     if (in_elems >= 1099511627776.0L || out_elems >= 1099511627776.0L) return TFNO_ERR_SHAPE;
-    if ((long double)B * (C_in > C_out ? C_in : C_out) * (dims == 2 ? N : 1) >= 2147483647.0L) return TFNO_ERR_SHAPE;
+    if ((long double)B * (C_in > C_out ? C_in : C_out) * (sh.dims == 2 ? (sh.N1 > sh.N2 ? sh.N1 : sh.N2) : 1) >=
+        2147483647.0L)
+        return TFNO_ERR_SHAPE;
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
     return TFNO_OK;
 }
 
-// the strip pipeline keeps two [B, C, K, N] intermediates
-size_t strip2d_workspace_bytes(long long B, int C_in, int C_out, int N, int K)
+// the strip pipeline keeps two [B, C, K1, N2] intermediates
+size_t strip2d_workspace_bytes(long long B, int C_in, int C_out, int N2, int K1)
 {
-    return sizeof(c64) * (size_t)B * K * N * ((size_t)C_in + C_out);
+    return sizeof(c64) * (size_t)B * K1 * N2 * ((size_t)C_in + C_out);
 }
+
+size_t workspace_for(const Shape &sh, int variant, int B, int C_in, int C_out);
 
 tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W, size_t wb, const void *y, size_t yb,
                             void **ws)
@@ -65,26 +85,27 @@ tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W
 
 enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2, FFT_GEMM = 3, GEMM_IFFT = 4 };
 
-tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
-                int K, void *stream)
+tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out,
+                void *stream)
 {
+    const int dims = sh.dims, N = sh.N2, K = sh.K2;         // N, K: the last (contiguous) axis
     const bool staged = variant == STAGED;
     bool empty;
-    tfno_status st = validate(dims, x, W, y, B, C_in, C_out, N, K, &empty);
+    tfno_status st = validate(sh, x, W, y, B, C_in, C_out, &empty);
     if (st != TFNO_OK || empty) return st;
     if (variant == PRUNED) {
         if (dims != 1 || !pruned1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
     } else if (variant == FFT_GEMM || variant == GEMM_IFFT) {
         if (dims != 1 || !fused1d_partial_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
-    } else if (!staged && !(dims == 2 && fused2d_supported(N, K)) && !fused1d_supported(N, K)) {
+    } else if (!staged && !sh.image_kernels() && !fused1d_supported(N, K)) {
         return TFNO_ERR_UNSUPPORTED;
     }
 
-    const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
+    const size_t pts = sh.pts();
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     void *ws = nullptr;
-    st = check_workspace(tfno_workspace_bytes(dims, (int)variant, B, C_in, C_out, N, K), x, xb, W, wb, y, yb, &ws);
+    st = check_workspace(workspace_for(sh, (int)variant, B, C_in, C_out), x, xb, W, wb, y, yb, &ws);
     if (st != TFNO_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
@@ -93,7 +114,7 @@ tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y
     hipError_t e;
 
     if (staged) {
-        e = staged_conv(dims, xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
+        e = staged_conv(dims, xc, Wc, yc, B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2, (c64 *)ws, s);
     } else if (variant == PRUNED) {
         e = pruned1d_launch(xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
     } else if (variant == FFT_GEMM || variant == GEMM_IFFT) {
@@ -121,27 +142,29 @@ tfno_status run(int dims, Variant variant, const void *x, const void *W, void *y
         a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
         a.scale = 1.0f / (float)N;
         e = fused1d_launch(N, K, a, B, s);
-    } else if (fused2d_supported(N, K)) {
-        // image kernels: only the truncated K x K spectra cross global memory
-        e = fused2d_launch(xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
+    } else if (sh.image_kernels()) {
+        // image kernels: only the truncated K1 x K2 spectra cross global memory
+        e = fused2d_launch(xc, Wc, yc, B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2, (c64 *)ws, s);
     } else {
-        // strip pipeline (Sec. 3.2 / 3.3), for shapes the image kernels do not cover: truncated forward transform along the first axis, fused
-        // kernel along the last axis on the K retained rows, zero-padded inverse along the first axis.
-        c64 *T1 = (c64 *)ws;                                   // [B, C_in,  K, N]
-        c64 *T2 = T1 + (size_t)B * C_in * K * N;               // [B, C_out, K, N]
-        const long long NN = (long long)N * N, KN = (long long)K * N;
-        e = launch_axis_fft(-1, xc, T1, N, (long long)B * C_in * N, N, NN, KN, N, N, K, 1.f, s);
+        // strip pipeline (Sec. 3.2 / 3.3), for shapes the image kernels do not cover: truncated forward transform
+        // along the first axis, fused kernel along the last axis on the K1 retained rows, zero-padded inverse along
+        // the first axis.
+        const int N1 = sh.N1, K1 = sh.K1;
+        c64 *T1 = (c64 *)ws;                                   // [B, C_in,  K1, N]
+        c64 *T2 = T1 + (size_t)B * C_in * K1 * N;              // [B, C_out, K1, N]
+        const long long NN = (long long)N1 * N, KN = (long long)K1 * N;
+        e = launch_axis_fft(-1, xc, T1, N1, (long long)B * C_in * N, N, NN, KN, N, N1, K1, 1.f, s);
         if (e == hipSuccess) {
             Fused1dArgs a{};
             a.x = T1; a.W = Wc; a.y = T2; a.C_in = C_in; a.C_out = C_out;
-            a.inner_count = K;
+            a.inner_count = K1;
             a.x_outer_stride = (long long)C_in * KN;  a.x_inner_stride = N; a.x_chan_stride = KN;
             a.y_outer_stride = (long long)C_out * KN; a.y_inner_stride = N; a.y_chan_stride = KN;
-            a.scale = 1.0f / ((float)N * (float)N);
-            e = fused1d_launch(N, K, a, (long long)B * K, s);
+            a.scale = 1.0f / ((float)N1 * (float)N);
+            e = fused1d_launch(N, K, a, (long long)B * K1, s);
         }
         if (e == hipSuccess)
-            e = launch_axis_fft(+1, T2, yc, N, (long long)B * C_out * N, N, KN, NN, N, K, N, 1.f, s);
+            e = launch_axis_fft(+1, T2, yc, N1, (long long)B * C_out * N, N, KN, NN, N, K1, N1, 1.f, s);
     }
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
@@ -225,63 +248,15 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
 
 }  // namespace tfno
 
-extern "C" {
+namespace {
 
-tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
-                                 void *stream)
+size_t workspace_for(const Shape &sh, int variant, int B, int C_in, int C_out)
 {
-    return run(1, FUSED, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
-                                 void *stream)
-{
-    return run(2, FUSED, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
-                                        int K, void *stream)
-{
-    return run(1, PRUNED, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv1d_fft_gemm(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
-                                          int K, void *stream)
-{
-    return run(1, FFT_GEMM, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
-                                           int K, void *stream)
-{
-    return run(1, GEMM_IFFT, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
-                                      void *stream)
-{
-    return run(1, choose_variant(N, K, C_out), x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
-                                        int K, void *stream)
-{
-    return run(1, STAGED, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
-                                        int K, void *stream)
-{
-    return run(2, STAGED, x, W, y, B, C_in, C_out, N, K, stream);
-}
-
-size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K)
-{
+    const int dims = sh.dims, N = sh.N2, K = sh.K2;
     if (variant == 5) {
         if (dims != 1) return 0;
         variant = (int)choose_variant(N, K, C_out);
     }
-    const int staged = variant == 1;
     if (variant < 0 || variant > 4) return 0;
     if (variant == 2) {
         if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !pruned1d_supported(N, K)) return 0;
@@ -291,11 +266,86 @@ size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, i
         if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !fused1d_partial_supported(N, K)) return 0;
         return sizeof(c64) * pruned1d_spectrum_elems(B, variant == 3 ? C_out : C_in, K);
     }
-    if ((dims != 1 && dims != 2) || B < 1 || C_in < 1 || C_out < 1 || N < 2 || N > 4096 || !is_pow2(N) || K < 1 || K > N)
-        return 0;
-    if (staged) return staged_workspace_bytes(dims, B, C_in, C_out, N, K);
+    if (B < 1 || !sizes_ok(sh, B, C_in, C_out)) return 0;
+    if (variant == 1) return staged_workspace_bytes(B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2);
     if (dims == 1) return 0;
-    return fused2d_supported(N, K) ? fused2d_workspace_bytes(B, C_in, C_out, K) : strip2d_workspace_bytes(B, C_in, C_out, N, K);
+    return sh.image_kernels() ? fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2)
+                              : strip2d_workspace_bytes(B, C_in, C_out, sh.N2, sh.K1);
+}
+
+}  // namespace
+
+extern "C" {
+
+tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                 void *stream)
+{
+    return run(shape1d(N, K), FUSED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                 void *stream)
+{
+    return run(shape2d(N, N, K, K), FUSED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                        int K, void *stream)
+{
+    return run(shape1d(N, K), PRUNED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_fft_gemm(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                          int K, void *stream)
+{
+    return run(shape1d(N, K), FFT_GEMM, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                           int K, void *stream)
+{
+    return run(shape1d(N, K), GEMM_IFFT, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                      void *stream)
+{
+    return run(shape1d(N, K), choose_variant(N, K, C_out), x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                        int K, void *stream)
+{
+    return run(shape1d(N, K), STAGED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv2d_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                        int K, void *stream)
+{
+    return run(shape2d(N, N, K, K), STAGED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv2d_rect(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1,
+                                      int N2, int K1, int K2, void *stream)
+{
+    return run(shape2d(N1, N2, K1, K2), FUSED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1,
+                                             int N2, int K1, int K2, void *stream)
+{
+    return run(shape2d(N1, N2, K1, K2), STAGED, x, W, y, B, C_in, C_out, stream);
+}
+
+size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K)
+{
+    if (dims != 1 && dims != 2) return 0;
+    return workspace_for(dims == 1 ? shape1d(N, K) : shape2d(N, N, K, K), variant, B, C_in, C_out);
+}
+
+size_t tfno_workspace_bytes_2d(int variant, int B, int C_in, int C_out, int N1, int N2, int K1, int K2)
+{
+    return workspace_for(shape2d(N1, N2, K1, K2), variant, B, C_in, C_out);
 }
 
 tfno_status tfno_set_workspace(void *dev_ptr, size_t bytes)

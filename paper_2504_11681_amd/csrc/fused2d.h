@@ -4,13 +4,21 @@
 
 namespace tfno {
 
-// True when the image kernels exist for (N, K): N in {64, 128, 256}, K in {16, 32, 64}, K <= N.
-bool fused2d_supported(int N, int K);
-// Workspace for Xh[B, C_in, K, K] and Yh[B, C_out, K, K].
-size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K);
+// True when the image kernels exist for N1 x N2 images keeping K1 x K2 modes: N1, N2 in {64, 128, 256},
+// K1, K2 in {16, 32, 64}.
+bool fused2d_supported(int N1, int N2, int K1, int K2);
+// Workspace for Xh[B, C_in, K1, K2] and Yh[B, C_out, K1, K2].
+size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K1, int K2);
 // Enqueues forward transform, mode CGEMM and inverse transform on stream s.
-hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
-                          c64 *ws, hipStream_t s);
+hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N1, int N2,
+                          int K1, int K2, c64 *ws, hipStream_t s);
+// The two image kernels for one first-axis length (one translation unit each): forward x -> Xh, inverse Yh -> y.
+hipError_t fused2d_images_n64(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
+                              hipStream_t s);
+hipError_t fused2d_images_n128(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
+                               hipStream_t s);
+hipError_t fused2d_images_n256(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
+                               hipStream_t s);
 
 // Yh = Xh . (scale W) over `tiles` tiles of 128 modes; both spectra mode-tile major ([tile][channel][128]).
 hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,

@@ -1,18 +1,20 @@
-// Instantiations and launcher of the 2-D kernels.
-#include "fused2d_kernel.h"
+// Mode CGEMM instantiations and the launcher of the 2-D pipeline (the image kernels live in fused2d_n*.hip).
+#include "cgemm_modes_kernel.h"
 #include "fused2d.h"
 #include "fused1d.h"
 
 namespace tfno {
 
-bool fused2d_supported(int N, int K)
+bool fused2d_supported(int N1, int N2, int K1, int K2)
 {
-    return (N == 64 || N == 128 || N == 256) && (K == 16 || K == 32 || K == 64) && K <= N;
+    auto n_ok = [](int n) { return n == 64 || n == 128 || n == 256; };
+    auto k_ok = [](int k) { return k == 16 || k == 32 || k == 64; };
+    return n_ok(N1) && n_ok(N2) && k_ok(K1) && k_ok(K2);
 }
 
-size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K)
+size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K1, int K2)
 {
-    return sizeof(c64) * (size_t)B * K * K * ((size_t)C_in + C_out);
+    return sizeof(c64) * (size_t)B * K1 * K2 * ((size_t)C_in + C_out);
 }
 
 hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,
@@ -37,43 +39,18 @@ hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, in
     return hipGetLastError();
 }
 
-template <int N, int K>
-static hipError_t launch_nk(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
-                            hipStream_t s)
+hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N1, int N2,
+                          int K1, int K2, c64 *ws, hipStream_t s)
 {
-    const int M = K * K;
+    if (!fused2d_supported(N1, N2, K1, K2)) return hipErrorInvalidValue;
+    auto images = N1 == 64 ? fused2d_images_n64 : N1 == 128 ? fused2d_images_n128 : fused2d_images_n256;
+    const int M = K1 * K2;                                  // a multiple of 128
     c64 *Xh = ws, *Yh = ws + (size_t)B * C_in * M;
-    hipLaunchKernelGGL((k_fwd2d<N, K>), dim3((unsigned)(B * C_in)), dim3(256), 0, s, x, Xh, C_in);
-    hipError_t e = hipGetLastError();
+    hipError_t e = images(-1, x, Xh, B * C_in, C_in, N2, K1, K2, s);
     if (e != hipSuccess) return e;
-    if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / ((float)N * (float)N), B * (M / 128), s)) != hipSuccess)
-        return e;
-    hipLaunchKernelGGL((k_inv2d<N, K>), dim3((unsigned)(B * C_out)), dim3(256), 0, s, (const c64 *)Yh, y, C_out);
-    return hipGetLastError();
-}
-
-template <int N>
-static hipError_t launch_n(int K, const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, c64 *ws,
-                           hipStream_t s)
-{
-    switch (K) {
-    case 16: return launch_nk<N, 16>(x, W, y, B, C_in, C_out, ws, s);
-    case 32: return launch_nk<N, 32>(x, W, y, B, C_in, C_out, ws, s);
-    case 64: return launch_nk<N, 64>(x, W, y, B, C_in, C_out, ws, s);
-    default: return hipErrorInvalidValue;
-    }
-}
-
-hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
-                          c64 *ws, hipStream_t s)
-{
-    if (!fused2d_supported(N, K)) return hipErrorInvalidValue;
-    switch (N) {
-    case 64: return launch_n<64>(K, x, W, y, B, C_in, C_out, ws, s);
-    case 128: return launch_n<128>(K, x, W, y, B, C_in, C_out, ws, s);
-    case 256: return launch_n<256>(K, x, W, y, B, C_in, C_out, ws, s);
-    default: return hipErrorInvalidValue;
-    }
+    e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / ((float)N1 * (float)N2), B * (M / 128), s);
+    if (e != hipSuccess) return e;
+    return images(+1, Yh, y, B * C_out, C_out, N2, K1, K2, s);
 }
 
 }  // namespace tfno

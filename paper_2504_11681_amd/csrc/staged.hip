@@ -193,19 +193,18 @@ static unsigned copy_blocks(long long total)
     return (unsigned)b;
 }
 
-size_t staged_workspace_bytes(int dims, long long B, int C_in, int C_out, int N, int K)
+size_t staged_workspace_bytes(long long B, int C_in, int C_out, int N1, int N2, int K1, int K2)
 {
-    size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
-    size_t kpts = dims == 1 ? (size_t)K : (size_t)K * K;
+    const size_t pts = (size_t)N1 * N2, kpts = (size_t)K1 * K2;
     // full spectrum, truncated spectrum, contracted spectrum, padded spectrum
     return sizeof(c64) * (size_t)B * ((size_t)C_in * pts + (size_t)C_in * kpts + (size_t)C_out * kpts + (size_t)C_out * pts);
 }
 
 hipError_t staged_conv(int dims, const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out,
-                       int N, int K, c64 *ws, hipStream_t s)
+                       int N1, int N2, int K1, int K2, c64 *ws, hipStream_t s)
 {
-    const size_t pts = dims == 1 ? (size_t)N : (size_t)N * N;
-    const size_t kpts = dims == 1 ? (size_t)K : (size_t)K * K;
+    const int N = N2, K = K2;                  // the last (contiguous) axis; 1-D calls have N1 = K1 = 1
+    const size_t pts = (size_t)N1 * N2, kpts = (size_t)K1 * K2;
     c64 *S = ws;                               // [B, C_in, pts]   full spectrum
     c64 *T = S + (size_t)B * C_in * pts;       // [B, C_in, kpts]  truncated
     c64 *Yh = T + (size_t)B * C_in * kpts;     // [B, C_out, kpts] contracted
@@ -217,9 +216,9 @@ hipError_t staged_conv(int dims, const c64 *x, const c64 *W, c64 *y, long long B
         if ((e = launch_fft(-1, x, S, N, in_imgs, 1, N, 1, 1.f, s)) != hipSuccess) return e;
         hipLaunchKernelGGL(k_staged_truncate, dim3(copy_blocks(in_imgs * K)), dim3(256), 0, s, S, T, in_imgs, 1, N, 1, K);
     } else {
-        if ((e = launch_fft(-1, x, S, N, in_imgs * N, 1, N, 1, 1.f, s)) != hipSuccess) return e;
-        if ((e = launch_fft(-1, S, S, N, in_imgs * N, N, (long long)N * N, N, 1.f, s)) != hipSuccess) return e;
-        hipLaunchKernelGGL(k_staged_truncate, dim3(copy_blocks(in_imgs * kpts)), dim3(256), 0, s, S, T, in_imgs, N, N, K, K);
+        if ((e = launch_fft(-1, x, S, N, in_imgs * N1, 1, N, 1, 1.f, s)) != hipSuccess) return e;
+        if ((e = launch_fft(-1, S, S, N1, in_imgs * N, N, (long long)N1 * N, N, 1.f, s)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k_staged_truncate, dim3(copy_blocks(in_imgs * kpts)), dim3(256), 0, s, S, T, in_imgs, N1, N, K1, K);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
@@ -235,10 +234,10 @@ hipError_t staged_conv(int dims, const c64 *x, const c64 *W, c64 *y, long long B
         if ((e = hipGetLastError()) != hipSuccess) return e;
         return launch_fft(+1, P, y, N, out_imgs, 1, N, 1, 1.f / (float)N, s);
     }
-    hipLaunchKernelGGL(k_staged_pad, dim3(copy_blocks(out_imgs * pts)), dim3(256), 0, s, Yh, P, out_imgs, N, N, K, K);
+    hipLaunchKernelGGL(k_staged_pad, dim3(copy_blocks(out_imgs * pts)), dim3(256), 0, s, Yh, P, out_imgs, N1, N, K1, K);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_fft(+1, P, P, N, out_imgs * N, N, (long long)N * N, N, 1.f / (float)N, s)) != hipSuccess) return e;
-    return launch_fft(+1, P, y, N, out_imgs * N, 1, N, 1, 1.f / (float)N, s);
+    if ((e = launch_fft(+1, P, P, N1, out_imgs * N, N, (long long)N1 * N, N, 1.f / (float)N1, s)) != hipSuccess) return e;
+    return launch_fft(+1, P, y, N, out_imgs * N1, 1, N, 1, 1.f / (float)N, s);
 }
 
 }  // namespace tfno

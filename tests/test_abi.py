@@ -62,6 +62,43 @@ def test_argument_errors_are_caught_on_the_host(L, name):
     assert call(L, name, None, None, None, 0, 4, 4, 64, 16) == binding.OK
 
 
+@pytest.mark.parametrize("name", binding.RECT_EXPORTS)
+def test_rect_argument_errors_are_caught_on_the_host(L, name):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    fn = getattr(L, name)
+    good = (2, 4, 4, 64, 128, 16, 32)
+    assert fn(None, W, y, *good, None) == binding.ERR_NULL
+    assert fn(x, None, y, *good, None) == binding.ERR_NULL
+    assert fn(x, W, None, *good, None) == binding.ERR_NULL
+    for bad in [(-1, 4, 4, 64, 128, 16, 32), (2, 0, 4, 64, 128, 16, 32), (2, 4, 0, 64, 128, 16, 32),
+                (2, 4, 4, 48, 128, 16, 32), (2, 4, 4, 64, 96, 16, 32), (2, 4, 4, 64, 128, 0, 32),
+                (2, 4, 4, 64, 128, 16, 0), (2, 4, 4, 64, 128, 65, 32), (2, 4, 4, 64, 128, 16, 129),
+                (2, 4, 4, 1, 128, 1, 32), (2, 4, 4, 64, 8192, 16, 32), (2, 4, 4, 128, 64, 16, 128)]:
+        assert fn(x, W, y, *bad, None) == binding.ERR_SHAPE, bad
+    assert fn(x, W, x, *good, None) == binding.ERR_ALIAS
+    assert fn(x, W, W, *good, None) == binding.ERR_ALIAS
+    assert fn(None, None, None, 0, 4, 4, 64, 128, 16, 32, None) == binding.OK
+
+
+def test_rect_workspace_and_unsupported_shapes(L):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    # image kernels: truncated K1 x K2 spectra of input and output
+    assert binding.workspace_bytes_2d(0, 2, 3, 5, 64, 256, 16, 64) == 8 * 2 * 16 * 64 * (3 + 5)
+    # strip pipeline (K1 = 8 is not an image-kernel mode count): two [B, C, K1, N2] strips
+    assert binding.workspace_bytes_2d(0, 2, 3, 5, 32, 256, 8, 64) == 8 * 2 * 8 * 256 * (3 + 5)
+    assert binding.workspace_bytes_2d(1, 2, 3, 5, 32, 64, 8, 16) == 8 * 2 * (3 * 2048 + 3 * 128 + 5 * 128 + 5 * 2048)
+    # the square case is the square entry point's
+    assert binding.workspace_bytes_2d(0, 2, 3, 5, 64, 64, 16, 16) == binding.workspace_bytes(2, 0, 2, 3, 5, 64, 16)
+    assert binding.workspace_bytes_2d(1, 2, 3, 5, 64, 64, 16, 16) == binding.workspace_bytes(2, 1, 2, 3, 5, 64, 16)
+    assert binding.workspace_bytes_2d(0, 2, 3, 5, 48, 64, 16, 16) == 0
+    assert binding.workspace_bytes_2d(2, 2, 3, 5, 64, 64, 16, 16) == 0        # the 1-D-only variants
+    assert L.tfno_set_workspace(None, 0) == binding.OK
+    assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 128, 16, 32, None) == binding.ERR_WORKSPACE
+    # last axis not covered by the fused 1-D kernel and not an image-kernel shape
+    assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 2048, 16, 32, None) == binding.ERR_UNSUPPORTED
+    assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 256, 16, 48, None) == binding.ERR_UNSUPPORTED
+
+
 def test_fused_entry_points_report_unsupported_shapes(L):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 2048, 128) == binding.ERR_UNSUPPORTED

@@ -215,6 +215,73 @@ def test_2d_staged_general_shape(gpu, oracle_mod):
     check(run_gpu(gpu, "spectral_conv2d_staged", x, W, K), want, "staged2d")
 
 
+def run_gpu_rect(gpu, fn_name, x, W, K1, K2):
+    torch, binding = gpu
+    xd = torch.from_numpy(x).cuda()
+    Wd = torch.from_numpy(W).cuda()
+    yd = torch.full((x.shape[0], W.shape[1]) + x.shape[2:], float("nan"), dtype=torch.complex64, device="cuda")
+    getattr(binding, fn_name)(xd, Wd, yd, K1, K2)
+    torch.cuda.synchronize()
+    return yd.cpu().numpy()
+
+
+# every (N1, N2, K1, K2) instantiation of the image kernels
+RECT_IMAGE = [(n1, n2, k1, k2) for n1 in (64, 128, 256) for n2 in (64, 128, 256) for k1 in (16, 32, 64)
+              for k2 in (16, 32, 64)]
+
+
+@pytest.mark.parametrize("shape", RECT_IMAGE, ids=lambda s: "N%dx%d_K%dx%d" % s)
+def test_2d_rect_image_kernels(gpu, oracle_mod, shape):
+    N1, N2, K1, K2 = shape
+    B, Ci, Co = 2, 3, 2
+    say(f"[case] spectral_conv2d_rect {shape}")
+    x = inputs.make_x(300 + N1 + 2 * N2 + K1 + 3 * K2, B, Ci, (N1, N2))
+    W = inputs.make_W(300 + N1 + 2 * N2 + K1 + 3 * K2, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    check(run_gpu_rect(gpu, "spectral_conv2d_rect", x, W, K1, K2), want, "rect")
+
+
+# (B, C_in, C_out, N1, N2, K1, K2): ragged channels on the image kernels, strip-pipeline shapes (first axis or mode
+# count outside the image kernels' set), and shapes only the staged twin takes
+RECT_MIXED = [(3, 7, 70, 64, 256, 16, 64), (2, 33, 5, 256, 64, 64, 16), (1, 66, 130, 128, 256, 32, 16),
+              (2, 3, 4, 32, 256, 8, 64), (1, 2, 3, 512, 64, 100, 16), (2, 3, 2, 16, 1024, 16, 128),
+              (1, 2, 2, 1024, 128, 64, 128), (2, 2, 3, 2, 64, 1, 8)]
+RECT_STAGED_ONLY = [(2, 3, 2, 8, 32, 3, 5), (1, 2, 2, 64, 16, 64, 16), (2, 2, 3, 128, 4, 7, 2), (1, 1, 1, 2, 2048, 2, 100)]
+
+
+@pytest.mark.parametrize("shape", RECT_MIXED, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
+@pytest.mark.parametrize("fn", ["spectral_conv2d_rect", "spectral_conv2d_rect_staged"])
+def test_2d_rect_mixed(gpu, oracle_mod, fn, shape):
+    B, Ci, Co, N1, N2, K1, K2 = shape
+    say(f"[case] {fn} {shape}")
+    x = inputs.make_x(400 + N1 + K2, B, Ci, (N1, N2))
+    W = inputs.make_W(400 + N1 + K2, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    check(run_gpu_rect(gpu, fn, x, W, K1, K2), want, fn)
+
+
+@pytest.mark.parametrize("shape", RECT_STAGED_ONLY, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
+def test_2d_rect_staged_general_shapes(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N1, N2, K1, K2 = shape
+    say(f"[case] staged rect {shape}")
+    x = inputs.make_x(500 + N1 + K2, B, Ci, (N1, N2))
+    W = inputs.make_W(500 + N1 + K2, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    check(run_gpu_rect(gpu, "spectral_conv2d_rect_staged", x, W, K1, K2), want, "staged rect")
+    with pytest.raises(binding.TfnoError) as e:
+        run_gpu_rect(gpu, "spectral_conv2d_rect", x, W, K1, K2)
+    assert e.value.status == binding.ERR_UNSUPPORTED
+
+
+def test_2d_rect_square_case_is_bitwise_the_square_entry_point(gpu):
+    x = inputs.make_x(77, 2, 5, (128, 128))
+    W = inputs.make_W(77, 5, 6)
+    a = run_gpu_rect(gpu, "spectral_conv2d_rect", x, W, 32, 32)
+    b = run_gpu(gpu, "spectral_conv2d", x, W, 32)
+    assert np.array_equal(a.view(np.float32), b.view(np.float32))
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
