@@ -122,7 +122,9 @@ tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void 
  * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and
  * same result as tfno_spectral_conv1d.  Shapes: N in {64,128,256} with K a multiple of 16 such that K/16 is a
- * power of two not above N/16, or N = 1024 with K in {64,128}; others TFNO_ERR_UNSUPPORTED.  Needs
+ * power of two not above N/16, N = 1024 with K in {64,128}, or long pencils N in {2048,4096} with K / (N/256) in
+ * {16,32,64,128,256} (the pencil is transformed as N/256 rows of 256 points, every row truncated to K / (N/256)
+ * bins); others TFNO_ERR_UNSUPPORTED.  Needs
  * tfno_workspace_bytes(1, 2, ...) bytes of workspace.  It is faster than a fused kernel whose contraction runs
  * on FP32 MFMA at hidden dimension 256 (the crossover Sec. 5.1 describes); against the default fused kernel
  * (BF16 matrix pipe) it is not.
@@ -150,7 +152,8 @@ tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y
  * Per-shape dispatch (variant "E" of Table 2, Sec. 5: the best of the variants for each shape), with the rule
  * measured on MI355X: the CGEMM + iFFT variant when C_out > 128 and that variant exists for (N, K) (the fully
  * fused kernel repeats the forward transform for every 128-output slab), else the fully fused kernel where one
- * exists, else the staged path.  Accepts every valid 1-D shape; same contract and same result as
+ * exists, else the three pruned kernels of tfno_spectral_conv1d_pruned where they exist (N = 2048, 4096), else the
+ * staged path.  Accepts every valid 1-D shape; same contract and same result as
  * tfno_spectral_conv1d.  Workspace: tfno_workspace_bytes(1, 5, ...) bytes (0 when the fused kernel is chosen).
  */
 tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y,

@@ -177,6 +177,9 @@ Variant choose_variant(int N, int K, int C_out)
 {
     if (C_out > 128 && fused1d_partial_supported(N, K)) return GEMM_IFFT;
     if (fused1d_supported(N, K)) return FUSED;
+    // long pencils (N = 2048, 4096) have no fused kernel: one workgroup cannot hold the K >= 128 retained modes of
+    // all its output channels; the three pruned kernels move only 4 K / N of the tensor bytes extra
+    if (pruned1d_supported(N, K)) return PRUNED;
     return STAGED;
 }
 

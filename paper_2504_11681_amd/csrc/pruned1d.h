@@ -4,7 +4,8 @@
 
 namespace tfno {
 
-// N in {64, 128, 256} with K a multiple of 16 such that K/16 divides N/16, or N = 1024 with K in {64, 128}.
+// N in {64, 128, 256} with K a multiple of 16 such that K/16 divides N/16, N = 1024 with K in {64, 128}, or
+// N in {2048, 4096} with K / (N / 256) in {16, 32, 64, 128, 256}.
 bool pruned1d_supported(int N, int K);
 // Workspace for the truncated spectra of input and output, padded to whole 128-mode tiles.
 size_t pruned1d_workspace_bytes(long long B, int C_in, int C_out, int K);

@@ -1,5 +1,6 @@
 // Instantiations and launcher of the unfused 1-D variant with pruned transforms.
 #include "pruned1d_kernel.h"
+#include "pruned1d_long_kernel.h"
 #include "fused2d.h"          // cgemm_modes_launch
 #include "pruned1d.h"
 
@@ -10,6 +11,13 @@ bool pruned1d_supported(int N, int K)
     if (K < 16 || K % 16 != 0 || K > N) return false;
     const int KH = K / 16;
     if (N == 1024) return KH == 4 || KH == 8;
+    if (N == 2048 || N == 4096) {
+        // long pencils: N1 = N / 256 rows of 256 points, each keeping K / N1 bins
+        const int N1 = N / 256;
+        if (K % N1) return false;
+        const int K2 = K / N1;
+        return K2 == 16 || K2 == 32 || K2 == 64 || K2 == 128 || K2 == 256;
+    }
     if (N != 64 && N != 128 && N != 256) return false;
     const int LPR = N / 16;
     return (KH & (KH - 1)) == 0 && KH <= LPR;
@@ -48,6 +56,43 @@ static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 
     return e;
 }
 
+template <int N1, int K2>
+static hipError_t launch_long(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
+                              int C_out, hipStream_t s)
+{
+    using Cf = CfgLong<N1, K2>;
+    const long long tiles = mode_tiles(B, Cf::K);
+    const long long pin = B * C_in, pout = B * C_out;
+    const long long sin = (pin + Cf::G - 1) / Cf::G, sout = (pout + Cf::G - 1) / Cf::G;
+    const unsigned gin = (unsigned)(sin < 2048 ? sin : 2048), gout = (unsigned)(sout < 2048 ? sout : 2048);
+    hipError_t e = hipSuccess;
+    if (stages & PRUNED_FWD) {
+        hipLaunchKernelGGL((k_fwd1d_long<N1, K2>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (stages & PRUNED_GEMM)
+        if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / (float)Cf::N, tiles, s)) != hipSuccess) return e;
+    if (stages & PRUNED_INV) {
+        hipLaunchKernelGGL((k_inv1d_long<N1, K2>), dim3(gout), dim3(256), 0, s, (const c64 *)Yh, y, C_out, pout);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+template <int N1>
+static hipError_t launch_long_n(int K2, int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B,
+                                int C_in, int C_out, hipStream_t s)
+{
+    switch (K2) {
+    case 16: return launch_long<N1, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 32: return launch_long<N1, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 64: return launch_long<N1, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 128: return launch_long<N1, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 256: return launch_long<N1, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 template <int N>
 static hipError_t launch_n(int K, int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B,
                            int C_in, int C_out, hipStream_t s)
@@ -75,6 +120,8 @@ hipError_t pruned1d_stages(int stages, const c64 *x, const c64 *W, c64 *y, c64 *
     case 1024:
         if (K == 64) return launch_nk<1024, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
         return launch_nk<1024, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 2048: return launch_long_n<8>(K / 8, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 4096: return launch_long_n<16>(K / 16, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
     default: return hipErrorInvalidValue;
     }
 }

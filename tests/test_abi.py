@@ -133,6 +133,9 @@ def test_workspace_contract(L):
     assert binding.workspace_bytes(1, 5, 4, 16, 48, 256, 64) == 0                         # fused
     assert binding.workspace_bytes(1, 5, 4, 16, 200, 256, 64) == 8 * 2 * 128 * 16         # CGEMM + iFFT
     assert binding.workspace_bytes(1, 5, 2, 3, 4, 2048, 100) == binding.workspace_bytes(1, 1, 2, 3, 4, 2048, 100)
+    assert binding.workspace_bytes(1, 5, 2, 3, 4, 4096, 512) == binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512)  # pruned
+    assert binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512) == 8 * 1024 * (3 + 4)
+    assert binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 64) == 0          # K / 8 below 16
     assert binding.workspace_bytes(1, 6, 4, 16, 48, 256, 64) == 0
     assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0

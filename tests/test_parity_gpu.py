@@ -96,7 +96,11 @@ def test_1d_small(gpu, oracle_mod, fn, shape):
 PRUNED_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 64), (2, 33, 40, 64, 32), (3, 9, 70, 128, 32), (2, 37, 17, 128, 128),
              (2, 5, 3, 128, 16), (64, 64, 64, 256, 64), (5, 19, 130, 256, 32), (2, 40, 33, 256, 16), (3, 24, 96, 256, 128),
              (2, 20, 40, 256, 256), (3, 13, 129, 1024, 128), (1, 1, 1, 1024, 64), (2, 20, 30, 1024, 64),
-             (7, 3, 2, 256, 16)]
+             (7, 3, 2, 256, 16),
+             # long pencils (N1 x 256 decomposition): odd pencil counts, K / N1 from 16 to 256, no truncation
+             (2, 5, 7, 2048, 128), (3, 3, 5, 2048, 256), (1, 1, 1, 2048, 2048), (2, 8, 8, 2048, 1024),
+             (2, 6, 9, 4096, 256), (1, 3, 2, 4096, 1024), (1, 2, 2, 4096, 4096), (2, 33, 70, 4096, 512),
+             (1, 4, 4, 2048, 512), (1, 2, 3, 4096, 2048)]
 
 
 @pytest.mark.parametrize("shape", PRUNED_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
@@ -126,9 +130,10 @@ def test_1d_partially_fused_variants(gpu, oracle_mod, shape, fn):
     check(run_gpu(gpu, fn, x, W, K), want, fn)
 
 
-# per-shape dispatch: CGEMM + iFFT variant (C_out > 128 where it exists), fused kernel, staged path
+# per-shape dispatch: CGEMM + iFFT variant (C_out > 128 where it exists), fused kernel, pruned kernels for long
+# pencils, staged path
 AUTO_1D = [(2, 16, 256, 256, 64), (3, 20, 130, 128, 32), (2, 16, 64, 256, 64), (2, 9, 200, 1024, 128),
-           (2, 4, 4, 2048, 100), (2, 5, 3, 256, 48), (2, 40, 300, 256, 128)]
+           (2, 4, 4, 2048, 100), (2, 5, 3, 256, 48), (2, 40, 300, 256, 128), (2, 9, 20, 4096, 512), (3, 5, 6, 2048, 256)]
 
 
 @pytest.mark.parametrize("shape", AUTO_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
@@ -167,7 +172,7 @@ def test_1d_random_shapes_all_entry_points(gpu, oracle_mod, shape):
 
 def test_1d_pruned_unsupported_shapes(gpu):
     torch, binding = gpu
-    for (N, K) in [(512, 64), (1024, 32), (256, 48), (64, 8), (2048, 128)]:
+    for (N, K) in [(512, 64), (1024, 32), (256, 48), (64, 8), (2048, 100), (2048, 64), (4096, 128), (4096, 768)]:
         x = torch.zeros((1, 2, N), dtype=torch.complex64, device="cuda")
         W = torch.zeros((2, 2), dtype=torch.complex64, device="cuda")
         y = torch.zeros((1, 2, N), dtype=torch.complex64, device="cuda")
