@@ -47,7 +47,7 @@ __device__ __forceinline__ void long_setup(c64 *TW, c64 *tw0, int tid)
 
 // x: [npencils, N] contiguous (pencil q = b * C + c).  Xh: mode-tile major over the joint mode index b K + m.
 template <int N1, int K2>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 3)
 k_fwd1d_long(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npencils)
 {
     using Cf = CfgLong<N1, K2>;
@@ -118,7 +118,7 @@ k_fwd1d_long(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long n
 
 // Yh: mode-tile major (joint mode index b K + k1 K2 + k2, C channels).  y: [npencils, N] contiguous.
 template <int N1, int K2>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 3)
 k_inv1d_long(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C, long long npencils)
 {
     using Cf = CfgLong<N1, K2>;
