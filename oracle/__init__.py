@@ -35,12 +35,14 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB)
         c_int, c_void = ctypes.c_int, ctypes.c_void_p
-        for name in ("oracle_spectral_conv1d", "oracle_spectral_conv2d"):
+        for name in ("oracle_spectral_conv1d", "oracle_spectral_conv2d", "oracle_spectral_conv1d_permode"):
             fn = getattr(lib, name)
             fn.restype = c_int
             fn.argtypes = [c_void, c_void, c_void] + [c_int] * 6
-        lib.oracle_spectral_conv2d_rect.restype = c_int
-        lib.oracle_spectral_conv2d_rect.argtypes = [c_void, c_void, c_void] + [c_int] * 8
+        for name in ("oracle_spectral_conv2d_rect", "oracle_spectral_conv2d_permode"):
+            fn = getattr(lib, name)
+            fn.restype = c_int
+            fn.argtypes = [c_void, c_void, c_void] + [c_int] * 8
         lib.oracle_forward_spectrum1d.restype = c_int
         lib.oracle_forward_spectrum1d.argtypes = [c_void, c_void, c_int, c_int]
         for name in ("oracle_fft_c128", "oracle_fft_radix2_c128", "oracle_dft_direct_c128"):
@@ -100,6 +102,34 @@ def spectral_conv2d_rect(x: np.ndarray, W: np.ndarray, K1: int, K2: int, threads
                                                B, C_in, C_out, N1, N2, K1, K2, threads)
     if used < 0:
         raise ValueError("oracle_spectral_conv2d_rect: bad arguments")
+    return y, used
+
+
+def spectral_conv1d_permode(x: np.ndarray, W: np.ndarray, threads: int = 0):
+    """y[B,C_out,N] for x[B,C_in,N] and an own weight matrix per retained mode, W[C_in,C_out,K] (complex64)."""
+    x, W = _c64(x), _c64(W)
+    B, C_in, N = x.shape
+    C_in2, C_out, K = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N), dtype=np.complex128)
+    used = _load().oracle_spectral_conv1d_permode(x.ctypes.data, W.ctypes.data, y.ctypes.data,
+                                                  B, C_in, C_out, N, K, threads)
+    if used < 0:
+        raise ValueError("oracle_spectral_conv1d_permode: bad arguments")
+    return y, used
+
+
+def spectral_conv2d_permode(x: np.ndarray, W: np.ndarray, threads: int = 0):
+    """y[B,C_out,N1,N2] for x[B,C_in,N1,N2] and per-mode weights W[C_in,C_out,K1,K2] (complex64)."""
+    x, W = _c64(x), _c64(W)
+    B, C_in, N1, N2 = x.shape
+    C_in2, C_out, K1, K2 = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N1, N2), dtype=np.complex128)
+    used = _load().oracle_spectral_conv2d_permode(x.ctypes.data, W.ctypes.data, y.ctypes.data,
+                                                  B, C_in, C_out, N1, N2, K1, K2, threads)
+    if used < 0:
+        raise ValueError("oracle_spectral_conv2d_permode: bad arguments")
     return y, used
 
 

@@ -98,11 +98,22 @@ void oracle_fft_radix2(const cplx *in, long istride, cplx *out, int N, int sign,
 
 /* ------------------------------------------------------------------ 1-D -- */
 
+/* Weight applied to mode m (of M retained modes) between input channel c and output channel o.
+ * per_mode = 0: one matrix W[C_in, C_out] shared by every mode, the GEMM of Sec. 3.1.
+ * per_mode = 1: W[C_in, C_out, M], an own matrix per retained mode, modes innermost -- the learned
+ * transformation of the Fourier layer as the FNO model the paper accelerates defines it (Sec. 1,
+ * Sec. 2.1 step 3); in 2-D the mode index is m = k1 K2 + k2. */
+static cplx weight(const float *W, int c, int o, int C_out, size_t m, size_t M, int per_mode)
+{
+    size_t idx = per_mode ? ((size_t)c * C_out + o) * M + m : (size_t)c * C_out + o;
+    return (double)W[2 * idx] + I * (double)W[2 * idx + 1];
+}
+
 /* One batch element.  x: [C_in, N] c64 (float pairs).  W: [C_in, C_out] c64.
  * y: [C_out, N] complex double.  Xh_full (optional, may be NULL): [C_in, N]
  * untruncated forward spectra, for the Parseval pin. */
 static void conv1d_one(const float *x, const float *W, cplx *y, cplx *Xh_full,
-                       int C_in, int C_out, int N, int K)
+                       int C_in, int C_out, int N, int K, int per_mode)
 {
     cplx *sig = malloc(sizeof(cplx) * N);
     cplx *spec = malloc(sizeof(cplx) * N);
@@ -118,14 +129,11 @@ static void conv1d_one(const float *x, const float *W, cplx *y, cplx *Xh_full,
         if (Xh_full) memcpy(Xh_full + (size_t)c * N, spec, sizeof(cplx) * N);
         for (int k = 0; k < K; ++k) Xh[(size_t)c * K + k] = spec[k];
     }
-    /* complex linear layer over the hidden dimension, same W for every mode (Sec. 3.1) */
+    /* complex linear layer over the hidden dimension (Sec. 3.1: the same W for every mode; per_mode: W[.,.,k]) */
     for (int o = 0; o < C_out; ++o)
         for (int k = 0; k < K; ++k) {
             cplx acc = 0.0;
-            for (int c = 0; c < C_in; ++c) {
-                cplx w = (double)W[2 * ((size_t)c * C_out + o)] + I * (double)W[2 * ((size_t)c * C_out + o) + 1];
-                acc += Xh[(size_t)c * K + k] * w;
-            }
+            for (int c = 0; c < C_in; ++c) acc += Xh[(size_t)c * K + k] * weight(W, c, o, C_out, (size_t)k, (size_t)K, per_mode);
             Yh[(size_t)o * K + k] = acc;
         }
     /* zero-pad to N, inverse transform, scale 1/N */
@@ -140,8 +148,8 @@ static void conv1d_one(const float *x, const float *W, cplx *y, cplx *Xh_full,
 /* x: [B, C_in, N] c64;  W: [C_in, C_out] c64;  y: [B, C_out, N] complex128.
  * Batch elements are independent and are spread over `threads` host threads.
  * Returns the number of threads actually used, or -1 on bad arguments. */
-int oracle_spectral_conv1d(const float *x, const float *W, double *y,
-                           int B, int C_in, int C_out, int N, int K, int threads)
+static int conv1d_batch(const float *x, const float *W, double *y,
+                        int B, int C_in, int C_out, int N, int K, int threads, int per_mode)
 {
     if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N <= 0 || K <= 0 || K > N) return -1;
     int used = 1;
@@ -154,15 +162,28 @@ int oracle_spectral_conv1d(const float *x, const float *W, double *y,
         #pragma omp for schedule(dynamic, 1)
         for (int b = 0; b < B; ++b)
             conv1d_one(x + 2 * (size_t)b * C_in * N, W, (cplx *)y + (size_t)b * C_out * N, NULL,
-                       C_in, C_out, N, K);
+                       C_in, C_out, N, K, per_mode);
     }
 #else
     (void)threads;
     for (int b = 0; b < B; ++b)
         conv1d_one(x + 2 * (size_t)b * C_in * N, W, (cplx *)y + (size_t)b * C_out * N, NULL,
-                   C_in, C_out, N, K);
+                   C_in, C_out, N, K, per_mode);
 #endif
     return used;
+}
+
+int oracle_spectral_conv1d(const float *x, const float *W, double *y,
+                           int B, int C_in, int C_out, int N, int K, int threads)
+{
+    return conv1d_batch(x, W, y, B, C_in, C_out, N, K, threads, 0);
+}
+
+/* The same with an own weight matrix per retained mode: W is [C_in, C_out, K]. */
+int oracle_spectral_conv1d_permode(const float *x, const float *W, double *y,
+                                   int B, int C_in, int C_out, int N, int K, int threads)
+{
+    return conv1d_batch(x, W, y, B, C_in, C_out, N, K, threads, 1);
 }
 
 /* Untruncated forward spectra of one [C, N] block (no scaling): Xh[c,k], k < N. */
@@ -200,7 +221,7 @@ static void fft2_inplace(cplx *img, int N1, int N2, int sign, cplx *line, cplx *
  * Each transformed axis keeps its own first K_i of N_i bins (Sec. 3.2 / 3.3: the
  * 2-D transform is separable and truncation / padding act per axis). */
 static void conv2d_one(const float *x, const float *W, cplx *y,
-                       int C_in, int C_out, int N1, int N2, int K1, int K2)
+                       int C_in, int C_out, int N1, int N2, int K1, int K2, int per_mode)
 {
     size_t NN = (size_t)N1 * N2, KK = (size_t)K1 * K2;
     int NL = N1 > N2 ? N1 : N2;
@@ -221,10 +242,7 @@ static void conv2d_one(const float *x, const float *W, cplx *y,
     for (int o = 0; o < C_out; ++o)
         for (size_t m = 0; m < KK; ++m) {
             cplx acc = 0.0;
-            for (int c = 0; c < C_in; ++c) {
-                cplx w = (double)W[2 * ((size_t)c * C_out + o)] + I * (double)W[2 * ((size_t)c * C_out + o) + 1];
-                acc += Xh[c * KK + m] * w;
-            }
+            for (int c = 0; c < C_in; ++c) acc += Xh[c * KK + m] * weight(W, c, o, C_out, m, KK, per_mode);
             Yh[o * KK + m] = acc;
         }
     double scale = 1.0 / ((double)N1 * (double)N2);
@@ -242,8 +260,8 @@ static void conv2d_one(const float *x, const float *W, cplx *y,
 
 /* x: [B, C_in, N1, N2] c64;  W: [C_in, C_out] c64;  y: [B, C_out, N1, N2] complex128.
  * Modes kept: k1 < K1 along the first axis, k2 < K2 along the last. */
-int oracle_spectral_conv2d_rect(const float *x, const float *W, double *y, int B, int C_in, int C_out,
-                                int N1, int N2, int K1, int K2, int threads)
+static int conv2d_batch(const float *x, const float *W, double *y, int B, int C_in, int C_out,
+                        int N1, int N2, int K1, int K2, int threads, int per_mode)
 {
     if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N1 <= 0 || N2 <= 0 || K1 <= 0 || K2 <= 0 ||
         K1 > N1 || K2 > N2)
@@ -259,15 +277,28 @@ int oracle_spectral_conv2d_rect(const float *x, const float *W, double *y, int B
         #pragma omp for schedule(dynamic, 1)
         for (int b = 0; b < B; ++b)
             conv2d_one(x + 2 * (size_t)b * C_in * NN, W, (cplx *)y + (size_t)b * C_out * NN,
-                       C_in, C_out, N1, N2, K1, K2);
+                       C_in, C_out, N1, N2, K1, K2, per_mode);
     }
 #else
     (void)threads;
     for (int b = 0; b < B; ++b)
         conv2d_one(x + 2 * (size_t)b * C_in * NN, W, (cplx *)y + (size_t)b * C_out * NN,
-                   C_in, C_out, N1, N2, K1, K2);
+                   C_in, C_out, N1, N2, K1, K2, per_mode);
 #endif
     return used;
+}
+
+int oracle_spectral_conv2d_rect(const float *x, const float *W, double *y, int B, int C_in, int C_out,
+                                int N1, int N2, int K1, int K2, int threads)
+{
+    return conv2d_batch(x, W, y, B, C_in, C_out, N1, N2, K1, K2, threads, 0);
+}
+
+/* The same with an own weight matrix per retained mode: W is [C_in, C_out, K1, K2]. */
+int oracle_spectral_conv2d_permode(const float *x, const float *W, double *y, int B, int C_in, int C_out,
+                                   int N1, int N2, int K1, int K2, int threads)
+{
+    return conv2d_batch(x, W, y, B, C_in, C_out, N1, N2, K1, K2, threads, 1);
 }
 
 /* The square case the paper evaluates (Sec. 5): N x N points, K x K modes. */

@@ -285,6 +285,63 @@ def test_rect_with_one_row_is_the_1d_operator(oracle_mod):
     assert np.max(np.abs(y2[:, :, 0, :] - y1)) < 1e-13
 
 
+# ------------------------------------------------------ per-mode weights --
+
+def test_permode_1d_matches_numpy_einsum(oracle_mod):
+    B, Ci, Co, N, K = 3, 4, 5, 64, 12
+    x = crandn(B, Ci, N)
+    W = crandn(Ci, Co, K)
+    y, _ = oracle_mod.spectral_conv1d_permode(x, W)
+    Xh = np.fft.fft(x.astype(np.complex128))[..., :K]
+    pad = np.zeros((B, Co, N), dtype=np.complex128)
+    pad[..., :K] = np.einsum("bik,iok->bok", Xh, W.astype(np.complex128))
+    assert np.max(np.abs(np.fft.ifft(pad) - y)) < 1e-12
+
+
+def test_permode_2d_matches_numpy_einsum(oracle_mod):
+    B, Ci, Co, N1, N2, K1, K2 = 2, 3, 2, 16, 32, 5, 7
+    x = crandn(B, Ci, N1, N2)
+    W = crandn(Ci, Co, K1, K2)
+    y, _ = oracle_mod.spectral_conv2d_permode(x, W)
+    Xh = np.fft.fft2(x.astype(np.complex128))[..., :K1, :K2]
+    pad = np.zeros((B, Co, N1, N2), dtype=np.complex128)
+    pad[..., :K1, :K2] = np.einsum("bixy,ioxy->boxy", Xh, W.astype(np.complex128))
+    assert np.max(np.abs(np.fft.ifft2(pad) - y)) < 1e-12
+
+
+def test_permode_with_equal_matrices_is_the_shared_weight_operator(oracle_mod):
+    x = crandn(2, 3, 32)
+    W = crandn(3, 4)
+    a, _ = oracle_mod.spectral_conv1d_permode(x, np.ascontiguousarray(np.repeat(W[:, :, None], 8, axis=2)))
+    b, _ = oracle_mod.spectral_conv1d(x, W, 8)
+    assert np.array_equal(a, b)
+    x2 = crandn(1, 3, 16, 8)
+    a, _ = oracle_mod.spectral_conv2d_permode(x2, np.ascontiguousarray(np.broadcast_to(W[:, :, None, None], (3, 4, 4, 2))))
+    b, _ = oracle_mod.spectral_conv2d_rect(x2, W, 4, 2)
+    assert np.array_equal(a, b)
+
+
+def test_permode_plane_wave_picks_its_own_matrix(oracle_mod):
+    """A plane wave of mode k is multiplied by W[:, :, k] and by no other matrix: catches a wrong mode index, a
+    transposed (k1, k2) and a wrong channel orientation."""
+    N, K = 32, 6
+    W = crandn(2, 3, K)
+    n = np.arange(N)
+    for k in range(K):
+        x = np.zeros((1, 2, N), dtype=np.complex64)
+        x[0, 1] = np.exp(2j * np.pi * k * n / N)
+        y, _ = oracle_mod.spectral_conv1d_permode(x, W)
+        want = W[1, :, k].astype(np.complex128)[:, None] * x[0, 1].astype(np.complex128)[None, :]
+        assert np.max(np.abs(y[0] - want)) < 5e-6
+    N1, N2, K1, K2 = 8, 16, 3, 5
+    W2 = crandn(1, 1, K1, K2)
+    n1, n2 = np.meshgrid(np.arange(N1), np.arange(N2), indexing="ij")
+    for (k1, k2) in [(0, 0), (2, 4), (1, 3), (2, 0), (0, 4)]:
+        x = np.exp(2j * np.pi * (k1 * n1 / N1 + k2 * n2 / N2))[None, None].astype(np.complex64)
+        y, _ = oracle_mod.spectral_conv2d_permode(x, W2)
+        assert np.max(np.abs(y[0, 0] - W2[0, 0, k1, k2].astype(np.complex128) * x[0, 0])) < 5e-6
+
+
 # ------------------------------------------------------ facts the paper prints --
 
 def _needed_ops_radix2(N, kept):
