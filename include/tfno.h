@@ -118,6 +118,28 @@ tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void 
                                              int N1, int N2, int K1, int K2, void *stream);
 
 /*
+ * Spectral convolution with an own weight matrix per retained mode -- the Fourier layer as the FNO model defines
+ * it (Sec. 1, Sec. 2.1 step 3: a learned linear transformation in the frequency domain); the entry points above
+ * take the single shared matrix of the paper's GEMM formulation (Sec. 3.1), which is the special case of equal
+ * matrices:
+ *
+ *   1-D  y[b,o,:] = iFFT_N ( pad_N    ( sum_c trunc_K    ( FFT_N (x[b,c,:]) )[k]     * W[c,o,k]     ) )
+ *   2-D  y[b,o]   = iFFT2  ( pad_N1xN2( sum_c trunc_K1xK2( FFT2  (x[b,c])   )[k1,k2] * W[c,o,k1,k2] ) )
+ *
+ * W is a device pointer to a contiguous row-major c64 tensor [C_in, C_out, K] (1-D) or [C_in, C_out, K1, K2]
+ * (2-D), modes innermost; x, y, stream, aliasing and error rules as for the other entry points.  Three launches:
+ * pruned forward transform with built-in truncation, per-mode contraction on the truncated spectra, pruned inverse
+ * with built-in zero padding (the transform kernels of tfno_spectral_conv1d_pruned and tfno_spectral_conv2d_rect).
+ * Shapes: 1-D those of tfno_spectral_conv1d_pruned with N <= 1024; 2-D N1, N2 in {64,128,256}, K1, K2 in
+ * {16,32,64}; others TFNO_ERR_UNSUPPORTED.  Workspace: tfno_workspace_bytes(1, 6, ...) and
+ * tfno_workspace_bytes_2d(6, ...) bytes.
+ */
+tfno_status tfno_spectral_conv1d_permode(const void *x, const void *W, void *y,
+                                         int B, int C_in, int C_out, int N, int K, void *stream);
+tfno_status tfno_spectral_conv2d_permode(const void *x, const void *W, void *y, int B, int C_in, int C_out,
+                                         int N1, int N2, int K1, int K2, void *stream);
+
+/*
  * 1-D spectral convolution as three launches with truncation, zero padding and butterfly pruning built into the
  * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and
@@ -162,11 +184,12 @@ tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y,
 /*
  * Workspace (device memory for intermediates) that an entry point needs for a
  * shape: dims = 1 or 2, variant = 0 (fused entry point), 1 (staged twin), 2
- * (tfno_spectral_conv1d_pruned), 3 (tfno_spectral_conv1d_fft_gemm), 4 (tfno_spectral_conv1d_gemm_ifft) or 5
- * (tfno_spectral_conv1d_auto).  Returns 0 when none is needed or the arguments are invalid.
+ * (tfno_spectral_conv1d_pruned), 3 (tfno_spectral_conv1d_fft_gemm), 4 (tfno_spectral_conv1d_gemm_ifft), 5
+ * (tfno_spectral_conv1d_auto) or 6 (tfno_spectral_conv1d_permode).  Returns 0 when none is needed or the arguments are invalid.
  */
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K);
-/* The same for the non-square 2-D entry points: variant = 0 (tfno_spectral_conv2d_rect) or 1 (its staged twin). */
+/* The same for the 2-D entry points that take N1, N2, K1, K2: variant = 0 (tfno_spectral_conv2d_rect), 1 (its
+ * staged twin) or 6 (tfno_spectral_conv2d_permode). */
 size_t tfno_workspace_bytes_2d(int variant, int B, int C_in, int C_out, int N1, int N2, int K1, int K2);
 
 /*

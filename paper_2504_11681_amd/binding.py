@@ -25,6 +25,8 @@ EXPORTS = (
     "tfno_spectral_conv1d_auto",
     "tfno_spectral_conv2d_rect",
     "tfno_spectral_conv2d_rect_staged",
+    "tfno_spectral_conv2d_permode",
+    "tfno_spectral_conv1d_permode",
     "tfno_workspace_bytes",
     "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
@@ -33,7 +35,7 @@ EXPORTS = (
 )
 
 CONV_EXPORTS = EXPORTS[:8]   # the entry points with the (x, W, y, B, C_in, C_out, N, K, stream) signature
-RECT_EXPORTS = EXPORTS[8:10]  # (x, W, y, B, C_in, C_out, N1, N2, K1, K2, stream)
+RECT_EXPORTS = EXPORTS[8:11]  # (x, W, y, B, C_in, C_out, N1, N2, K1, K2, stream)
 
 _lib = None
 _workspace = None     # the torch tensor currently registered as workspace (kept alive here)
@@ -54,7 +56,7 @@ def lib() -> ctypes.CDLL:
                                "(there is no fallback path)")
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
-        for name in CONV_EXPORTS:
+        for name in CONV_EXPORTS + ("tfno_spectral_conv1d_permode",):
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
@@ -86,12 +88,14 @@ def version() -> int:
 
 def workspace_bytes(dims: int, variant, B: int, C_in: int, C_out: int, N: int, K: int) -> int:
     """variant: 0 / False = fused entry point, 1 / True = staged twin, 2 = spectral_conv1d_pruned,
-    3 = spectral_conv1d_fft_gemm, 4 = spectral_conv1d_gemm_ifft, 5 = spectral_conv1d_auto."""
+    3 = spectral_conv1d_fft_gemm, 4 = spectral_conv1d_gemm_ifft, 5 = spectral_conv1d_auto,
+    6 = spectral_conv1d_permode."""
     return lib().tfno_workspace_bytes(dims, int(variant), B, C_in, C_out, N, K)
 
 
 def workspace_bytes_2d(variant, B: int, C_in: int, C_out: int, N1: int, N2: int, K1: int, K2: int) -> int:
-    """Non-square 2-D entry points: variant 0 / False = spectral_conv2d_rect, 1 / True = its staged twin."""
+    """2-D entry points with per-axis sizes: variant 0 / False = spectral_conv2d_rect, 1 / True = its staged
+    twin, 6 = spectral_conv2d_permode."""
     return lib().tfno_workspace_bytes_2d(int(variant), B, C_in, C_out, N1, N2, K1, K2)
 
 
@@ -194,3 +198,40 @@ def spectral_conv2d_rect(x, W, y, K1: int, K2: int, stream=None):
 
 def spectral_conv2d_rect_staged(x, W, y, K1: int, K2: int, stream=None):
     return _call_rect("tfno_spectral_conv2d_rect_staged", True, x, W, y, K1, K2, stream)
+
+
+def _call_permode(name: str, dims: int, x, W, y, stream):
+    import torch
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if t.dtype != torch.complex64 or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous complex64 device tensor")
+    if x.dim() != 2 + dims or y.dim() != 2 + dims or W.dim() != 2 + dims:
+        raise ValueError("x, y must be [B, C, spatial...]; W must be [C_in, C_out, modes...]")
+    B, C_in = x.shape[0], x.shape[1]
+    C_out = W.shape[1]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out) + tuple(x.shape[2:]):
+        raise ValueError("inconsistent tensor shapes")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    if dims == 1:
+        N, K = x.shape[2], W.shape[2]
+        ensure_workspace(workspace_bytes(1, 6, B, C_in, C_out, N, K), x.device)
+        st = lib().tfno_spectral_conv1d_permode(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, K, stream)
+    else:
+        N1, N2, K1, K2 = x.shape[2], x.shape[3], W.shape[2], W.shape[3]
+        ensure_workspace(workspace_bytes_2d(6, B, C_in, C_out, N1, N2, K1, K2), x.device)
+        st = lib().tfno_spectral_conv2d_permode(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N1, N2, K1, K2,
+                                                stream)
+    if st != OK:
+        raise TfnoError(st, name)
+    return y
+
+
+def spectral_conv1d_permode(x, W, y, stream=None):
+    """W: [C_in, C_out, K], an own weight matrix per retained mode."""
+    return _call_permode("tfno_spectral_conv1d_permode", 1, x, W, y, stream)
+
+
+def spectral_conv2d_permode(x, W, y, stream=None):
+    """W: [C_in, C_out, K1, K2]."""
+    return _call_permode("tfno_spectral_conv2d_permode", 2, x, W, y, stream)

@@ -43,7 +43,7 @@ bool sizes_ok(const Shape &sh, int B, int C_in, int C_out)
 
 // Everything that can be decided on the host.  *empty is set for a valid call with nothing to do.
 tfno_status validate(const Shape &sh, const void *x, const void *W, const void *y, int B, int C_in, int C_out,
-                     bool *empty)
+                     bool *empty, bool per_mode = false)
 {
     *empty = false;
     if (!sizes_ok(sh, B, C_in, C_out)) return TFNO_ERR_SHAPE;
@@ -58,7 +58,7 @@ tfno_status validate(const Shape &sh, const void *x, const void *W, const void *
         2147483647.0L)
         return TFNO_ERR_SHAPE;
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
-    const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out * (per_mode ? sh.kpts() : 1);
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
     return TFNO_OK;
 }
@@ -70,6 +70,12 @@ size_t strip2d_workspace_bytes(long long B, int C_in, int C_out, int N2, int K1)
 }
 
 size_t workspace_for(const Shape &sh, int variant, int B, int C_in, int C_out);
+
+// per-mode weights run as transform kernel, per-mode contraction, transform kernel on the truncated spectra
+bool permode_supported(const Shape &sh)
+{
+    return sh.dims == 1 ? (sh.N2 <= 1024 && pruned1d_supported(sh.N2, sh.K2)) : sh.image_kernels();
+}
 
 tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W, size_t wb, const void *y, size_t yb,
                             void **ws)
@@ -169,6 +175,41 @@ tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, 
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
 
+// W: [C_in, C_out, K] (1-D) or [C_in, C_out, K1, K2] (2-D), an own matrix per retained mode.
+tfno_status run_permode(const Shape &sh, const void *x, const void *W, void *y, int B, int C_in, int C_out, void *stream)
+{
+    bool empty;
+    tfno_status st = validate(sh, x, W, y, B, C_in, C_out, &empty, true);
+    if (st != TFNO_OK || empty) return st;
+    if (!permode_supported(sh)) return TFNO_ERR_UNSUPPORTED;
+    const size_t pts = sh.pts(), M = sh.kpts();
+    const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out * M;
+    void *wsp = nullptr;
+    st = check_workspace(workspace_for(sh, 6, B, C_in, C_out), x, xb, W, wb, y, yb, &wsp);
+    if (st != TFNO_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const c64 *xc = (const c64 *)x, *Wc = (const c64 *)W;
+    c64 *yc = (c64 *)y, *Xh = (c64 *)wsp;
+    const float scale = 1.0f / ((float)sh.N1 * (float)sh.N2);
+    hipError_t e;
+    if (sh.dims == 1) {
+        const int N = sh.N2, K = sh.K2;
+        c64 *Yh = Xh + pruned1d_spectrum_elems(B, C_in, K);
+        const long long tiles = ((long long)B * K + 127) / 128;
+        e = pruned1d_stages(PRUNED_FWD, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, s);
+        if (e == hipSuccess) e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, K, tiles, K >= 128 ? K / 128 : 1, scale, s);
+        if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, s);
+    } else {
+        c64 *Yh = Xh + (size_t)B * C_in * M;
+        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, s);
+        if (e == hipSuccess)
+            e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, (int)M, (long long)B * (long long)(M / 128), (int)(M / 128), scale, s);
+        if (e == hipSuccess) e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, s);
+    }
+    return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
+}
+
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
 // sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels
 // (C_out <= 128); above that every 128-output slab repeats the forward transform of its batch row, and the
@@ -260,6 +301,10 @@ size_t workspace_for(const Shape &sh, int variant, int B, int C_in, int C_out)
         if (dims != 1) return 0;
         variant = (int)choose_variant(N, K, C_out);
     }
+    if (variant == 6) {     // per-mode weights: the truncated spectra of input and output
+        if (B < 1 || !sizes_ok(sh, B, C_in, C_out) || !permode_supported(sh)) return 0;
+        return dims == 1 ? pruned1d_workspace_bytes(B, C_in, C_out, K) : fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2);
+    }
     if (variant < 0 || variant > 4) return 0;
     if (variant == 2) {
         if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !pruned1d_supported(N, K)) return 0;
@@ -338,6 +383,18 @@ tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void 
                                              int N2, int K1, int K2, void *stream)
 {
     return run(shape2d(N1, N2, K1, K2), STAGED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_permode(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
+                                         int K, void *stream)
+{
+    return run_permode(shape1d(N, K), x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv2d_permode(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1,
+                                         int N2, int K1, int K2, void *stream)
+{
+    return run_permode(shape2d(N1, N2, K1, K2), x, W, y, B, C_in, C_out, stream);
 }
 
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K)

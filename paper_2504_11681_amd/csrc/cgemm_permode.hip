@@ -1,0 +1,25 @@
+// Launcher of the per-mode-weight contraction.
+#include "cgemm_permode_kernel.h"
+#include "fused2d.h"
+
+namespace tfno {
+
+hipError_t cgemm_permode_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, int M, long long num_tiles,
+                                int TPI, float scale, hipStream_t s)
+{
+    if (num_tiles <= 0) return hipSuccess;
+    if (TPI < 1 || M < 1 || (long long)TPI * 128 > (long long)M + 127) return hipErrorInvalidValue;
+    const long long per = (num_tiles + TPI - 1) / TPI;      // tiles that hold the same modes
+    constexpr int OT = 8;
+    const unsigned gy = (unsigned)((C_out + 2 * OT - 1) / (2 * OT));
+    if (per >= 8) {
+        const dim3 grid((unsigned)(TPI * ((per + 7) / 8)), gy);
+        hipLaunchKernelGGL((k_cgemm_permode<8, OT>), grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale);
+    } else {
+        const dim3 grid((unsigned)(TPI * ((per + 1) / 2)), gy);
+        hipLaunchKernelGGL((k_cgemm_permode<2, OT>), grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace tfno

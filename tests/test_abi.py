@@ -45,7 +45,7 @@ def call(L, name, x, W, y, B, Ci, Co, N, K):
     return getattr(L, name)(x, W, y, B, Ci, Co, N, K, None)
 
 
-@pytest.mark.parametrize("name", binding.CONV_EXPORTS)
+@pytest.mark.parametrize("name", binding.CONV_EXPORTS + ("tfno_spectral_conv1d_permode",))
 def test_argument_errors_are_caught_on_the_host(L, name):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, name, None, W, y, 2, 4, 4, 64, 16) == binding.ERR_NULL
@@ -101,6 +101,11 @@ def test_rect_workspace_and_unsupported_shapes(L):
 
 def test_fused_entry_points_report_unsupported_shapes(L):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    assert call(L, "tfno_spectral_conv1d_permode", x, W, y, 2, 4, 4, 512, 64) == binding.ERR_UNSUPPORTED
+    assert call(L, "tfno_spectral_conv1d_permode", x, W, y, 2, 4, 4, 4096, 512) == binding.ERR_UNSUPPORTED
+    assert L.tfno_spectral_conv2d_permode(x, W, y, 2, 4, 4, 32, 256, 8, 64, None) == binding.ERR_UNSUPPORTED
+    # the per-mode weight tensor is C_in * C_out * K elements long: y inside its tail is an alias
+    assert call(L, "tfno_spectral_conv1d_permode", x, W, W + 8 * (4 * 4 * 16 - 1), 2, 4, 4, 64, 16) == binding.ERR_ALIAS
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 2048, 128) == binding.ERR_UNSUPPORTED
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 48) == binding.ERR_UNSUPPORTED
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 8) == binding.ERR_UNSUPPORTED
@@ -136,7 +141,12 @@ def test_workspace_contract(L):
     assert binding.workspace_bytes(1, 5, 2, 3, 4, 4096, 512) == binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512)  # pruned
     assert binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512) == 8 * 1024 * (3 + 4)
     assert binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 64) == 0          # K / 8 below 16
-    assert binding.workspace_bytes(1, 6, 4, 16, 48, 256, 64) == 0
+    # per-mode weights: the pruned variant's buffers (1-D), the image kernels' (2-D)
+    assert binding.workspace_bytes(1, 6, 4, 16, 48, 256, 64) == binding.workspace_bytes(1, 2, 4, 16, 48, 256, 64)
+    assert binding.workspace_bytes(1, 6, 4, 16, 48, 2048, 256) == 0       # N <= 1024 only
+    assert binding.workspace_bytes_2d(6, 2, 3, 5, 64, 256, 16, 64) == 8 * 2 * 16 * 64 * (3 + 5)
+    assert binding.workspace_bytes_2d(6, 2, 3, 5, 32, 256, 8, 64) == 0    # image-kernel shapes only
+    assert binding.workspace_bytes(1, 7, 4, 16, 48, 256, 64) == 0
     assert binding.workspace_bytes(3, True, 2, 3, 5, 64, 16) == 0
     assert binding.workspace_bytes(1, True, 2, 3, 5, 48, 16) == 0
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)

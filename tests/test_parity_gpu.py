@@ -287,6 +287,46 @@ def test_2d_rect_square_case_is_bitwise_the_square_entry_point(gpu):
     assert np.array_equal(a.view(np.float32), b.view(np.float32))
 
 
+# per-mode weights (B, C_in, C_out, N, K): several batch groups, ragged channels, K below / equal / above one tile
+PERMODE_1D = [(4, 16, 16, 64, 16), (19, 5, 7, 64, 64), (9, 33, 40, 128, 32), (3, 9, 70, 128, 128), (17, 6, 18, 256, 256),
+              (1, 1, 1, 256, 16), (2, 20, 30, 1024, 64), (11, 13, 17, 1024, 128), (8, 3, 2, 256, 128)]
+
+
+@pytest.mark.parametrize("shape", PERMODE_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_permode(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N, K = shape
+    say(f"[case] spectral_conv1d_permode {shape}")
+    x = inputs.make_x(700 + N + K, B, Ci, (N,))
+    W = np.ascontiguousarray(inputs.make_W(700 + N + K, Ci, Co * K).reshape(Ci, Co, K))
+    want, _ = oracle_mod.spectral_conv1d_permode(x, W)
+    xd, Wd = torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda()
+    yd = torch.full((B, Co, N), float("nan"), dtype=torch.complex64, device="cuda")
+    binding.spectral_conv1d_permode(xd, Wd, yd)
+    torch.cuda.synchronize()
+    check(yd.cpu().numpy(), want, "permode 1d")
+
+
+# (B, C_in, C_out, N1, N2, K1, K2)
+PERMODE_2D = [(2, 3, 5, 64, 64, 16, 16), (9, 5, 33, 128, 64, 32, 16), (1, 4, 3, 256, 256, 64, 64), (10, 2, 2, 64, 256, 16, 64),
+              (3, 17, 9, 128, 128, 64, 32)]
+
+
+@pytest.mark.parametrize("shape", PERMODE_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
+def test_2d_permode(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N1, N2, K1, K2 = shape
+    say(f"[case] spectral_conv2d_permode {shape}")
+    x = inputs.make_x(800 + N1 + K2, B, Ci, (N1, N2))
+    W = np.ascontiguousarray(inputs.make_W(800 + N1 + K2, Ci, Co * K1 * K2).reshape(Ci, Co, K1, K2))
+    want, _ = oracle_mod.spectral_conv2d_permode(x, W)
+    xd, Wd = torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda()
+    yd = torch.full((B, Co, N1, N2), float("nan"), dtype=torch.complex64, device="cuda")
+    binding.spectral_conv2d_permode(xd, Wd, yd)
+    torch.cuda.synchronize()
+    check(yd.cpu().numpy(), want, "permode 2d")
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
