@@ -194,6 +194,30 @@ def measure_rect(torch, binding, B, C, N1, N2, K1, K2, steps, warmup, ramp):
     return dev
 
 
+def measure_permode(torch, binding, w, steps, warmup, ramp):
+    """Device seconds per layer of the per-mode-weight entry point on workload w (W drawn per mode with the usual
+    recipe), and the bytes a layer must move (x, y and the weight tensor once)."""
+    from paper_2504_11681_amd import inputs
+    xd, _, yd = device_inputs(w, torch)
+    modes = w.K ** w.dims
+    Wd = torch.from_numpy(inputs.make_W(w.seed, w.C_in, w.C_out * modes)).cuda().reshape((w.C_in, w.C_out) + (w.K,) * w.dims)
+    sets = [(xd, yd)] + [(xd.clone(), torch.zeros_like(yd)) for _ in range(buffer_sets(w) - 1)]
+    fn = binding.spectral_conv1d_permode if w.dims == 1 else binding.spectral_conv2d_permode
+    stream = torch.cuda.current_stream().cuda_stream
+    turn = [0]
+
+    def call():
+        xi, yi = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        fn(xi, Wd, yi, stream)
+
+    _, dev = time_calls(torch, call, steps, warmup, ramp)
+    nbytes = 8 * w.B * (w.N ** w.dims) * (w.C_in + w.C_out) + 8 * w.C_in * w.C_out * modes
+    del xd, Wd, yd, sets
+    torch.cuda.empty_cache()
+    return dev, nbytes
+
+
 def pytorch_baseline(w, torch, binding, steps, ramp):
     """The layer as PyTorch composes it from library calls (the structure the paper measures against, Sec. 1 and 5):
     full FFT, slice, complex matmul over channels, zero pad, full inverse FFT -- rocFFT and the BLAS library under
@@ -407,6 +431,14 @@ def main():
                              "layers_per_s": 1.0 / devr, "bound": "hbm", "effective_hbm_GBps": nbytes / devr / 1e9,
                              "hbm_frac": nbytes / devr / 1e9 / HBM_PEAK_GBPS})
             out["rect_2d"] = rect
+            # an own weight matrix per retained mode (three kernels; the contraction is plain FP32 FMA work)
+            pm = []
+            for wp in (w, w4) if w.name.startswith("cfg3") else ():
+                devp, nb = measure_permode(torch, binding, wp, max(50, args.steps // 8), max(10, args.warmup // 8), args.ramp / 3)
+                pm.append({"workload": wp.name + "_permode", "us_per_layer": devp * 1e6, "layers_per_s": 1.0 / devp,
+                           "effective_hbm_GBps": nb / devp / 1e9, "hbm_frac": nb / devp / 1e9 / HBM_PEAK_GBPS,
+                           "contraction_TFLOPs": flops_of(wp) / devp / 1e12})
+            out["per_mode_weights"] = pm
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
 
