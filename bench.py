@@ -431,6 +431,17 @@ def main():
                              "layers_per_s": 1.0 / devr, "bound": "hbm", "effective_hbm_GBps": nbytes / devr / 1e9,
                              "hbm_frac": nbytes / devr / 1e9 / HBM_PEAK_GBPS})
             out["rect_2d"] = rect
+            # long pencils through the per-shape dispatch (three pruned kernels: no fused kernel for N >= 2048)
+            longp = []
+            for (Bl, Cl, Nl, Kl) in [(64, 128, 4096, 512), (128, 128, 2048, 256)]:
+                wl = inputs.Workload(f"long_1d_B{Bl}_C{Cl}_N{Nl}_K{Kl}", 1, Bl, Cl, Cl, Nl, Kl, 7)
+                _, devl = measure(wl, torch, binding, max(50, args.steps // 8), max(10, args.warmup // 8),
+                                  ramp=args.ramp / 3, variant=5)
+                longp.append({"workload": wl.name, "entry_point": "tfno_spectral_conv1d_auto", "us_per_layer": devl * 1e6,
+                              "layers_per_s": 1.0 / devl, "bound": "hbm",
+                              "effective_hbm_GBps": wl.compulsory_bytes / devl / 1e9,
+                              "hbm_frac": wl.compulsory_bytes / devl / 1e9 / HBM_PEAK_GBPS})
+            out["long_1d"] = longp
             # an own weight matrix per retained mode (three kernels; the contraction is plain FP32 FMA work)
             pm = []
             for wp in (w, w4) if w.name.startswith("cfg3") else ():
