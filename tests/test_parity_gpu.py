@@ -327,6 +327,89 @@ def test_2d_permode(gpu, oracle_mod, shape):
     check(yd.cpu().numpy(), want, "permode 2d")
 
 
+def test_large_batch_uses_64_bit_offsets(gpu, oracle_mod):
+    """B = 2^18 (1 GiB tensors, 2^18 workgroups): sampled batch elements against the oracle, including the last, whose
+    byte offset is past 2^31; the rest of the batch is filled on the device and only checked to be written."""
+    torch, binding = gpu
+    B, Ci, Co, N, K = 1 << 18, 8, 8, 64, 16
+    say(f"[case] large batch 1-D B={B}")
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    xd = torch.view_as_complex(torch.randn((B, Ci, N, 2), generator=gen, device="cuda", dtype=torch.float32))
+    Wn = inputs.make_W(5, Ci, Co)
+    sample = [0, 1, B // 2 + 3, B - 1]
+    for b in sample:
+        xd[b] = torch.from_numpy(inputs.make_x_element(5, b, Ci, (N,))).cuda()
+    Wd = torch.from_numpy(Wn).cuda()
+    for fn in ("spectral_conv1d", "spectral_conv1d_pruned"):
+        yd = torch.full((B, Co, N), float("nan"), dtype=torch.complex64, device="cuda")
+        getattr(binding, fn)(xd, Wd, yd, K)
+        torch.cuda.synchronize()
+        assert not torch.isnan(torch.view_as_real(yd)).any().item(), "some outputs were never written"
+        for b in sample:
+            want, _ = oracle_mod.spectral_conv1d(inputs.make_x_element(5, b, Ci, (N,))[None], Wn, K)
+            check(yd[b].cpu().numpy()[None], want, f"{fn} b={b}")
+        del yd
+    del xd
+    torch.cuda.empty_cache()
+
+
+def test_many_small_images_2d(gpu, oracle_mod):
+    """32768 images of 64 x 64 (1 GiB): sampled batch elements against the oracle."""
+    torch, binding = gpu
+    B, Ci, Co, N, K = 4096, 8, 8, 64, 16
+    say(f"[case] many images 2-D B={B}")
+    gen = torch.Generator(device="cuda").manual_seed(6)
+    xd = torch.view_as_complex(torch.randn((B, Ci, N, N, 2), generator=gen, device="cuda", dtype=torch.float32))
+    Wn = inputs.make_W(6, Ci, Co)
+    sample = [0, B // 3, B - 1]
+    for b in sample:
+        xd[b] = torch.from_numpy(inputs.make_x_element(6, b, Ci, (N, N))).cuda()
+    Wd = torch.from_numpy(Wn).cuda()
+    yd = torch.full((B, Co, N, N), float("nan"), dtype=torch.complex64, device="cuda")
+    binding.spectral_conv2d(xd, Wd, yd, K)
+    torch.cuda.synchronize()
+    assert not torch.isnan(torch.view_as_real(yd)).any().item(), "some outputs were never written"
+    for b in sample:
+        want, _ = oracle_mod.spectral_conv2d(inputs.make_x_element(6, b, Ci, (N, N))[None], Wn, K)
+        check(yd[b].cpu().numpy()[None], want, f"2d b={b}")
+    del xd, yd
+    torch.cuda.empty_cache()
+
+
+def test_entry_points_replay_from_a_hip_graph(gpu):
+    """The entry points only enqueue kernels on the caller's stream, so they can be captured once their first (eager)
+    call has been made: three replays, with eager work and synchronisation in between, each bitwise equal to eager."""
+    torch, binding = gpu
+    say("[case] HIP graph capture of the fused 1-D and the three-kernel 2-D entry points")
+    x1 = torch.from_numpy(inputs.make_x(11, 8, 24, (256,))).cuda()
+    W1 = torch.from_numpy(inputs.make_W(11, 24, 40)).cuda()
+    y1 = torch.zeros((8, 40, 256), dtype=torch.complex64, device="cuda")
+    x2 = torch.from_numpy(inputs.make_x(12, 2, 5, (64, 128))).cuda()
+    W2 = torch.from_numpy(inputs.make_W(12, 5, 6)).cuda()
+    y2 = torch.zeros((2, 6, 64, 128), dtype=torch.complex64, device="cuda")
+    binding.spectral_conv1d(x1, W1, y1, 64)
+    binding.spectral_conv2d_rect(x2, W2, y2, 16, 32)
+    torch.cuda.synchronize()
+    want1, want2 = y1.clone(), y2.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            st = torch.cuda.current_stream().cuda_stream
+            binding.spectral_conv1d(x1, W1, y1, 64, st)
+            binding.spectral_conv2d_rect(x2, W2, y2, 16, 32, st)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        y1.zero_()
+        y2.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(torch.view_as_real(y1), torch.view_as_real(want1))
+        assert torch.equal(torch.view_as_real(y2), torch.view_as_real(want2))
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
