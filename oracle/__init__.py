@@ -35,7 +35,8 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB)
         c_int, c_void = ctypes.c_int, ctypes.c_void_p
-        for name in ("oracle_spectral_conv1d", "oracle_spectral_conv2d", "oracle_spectral_conv1d_permode"):
+        for name in ("oracle_spectral_conv1d", "oracle_spectral_conv2d", "oracle_spectral_conv1d_permode",
+                     "oracle_spectral_conv1d_real"):
             fn = getattr(lib, name)
             fn.restype = c_int
             fn.argtypes = [c_void, c_void, c_void] + [c_int] * 6
@@ -130,6 +131,22 @@ def spectral_conv2d_permode(x: np.ndarray, W: np.ndarray, threads: int = 0):
                                                   B, C_in, C_out, N1, N2, K1, K2, threads)
     if used < 0:
         raise ValueError("oracle_spectral_conv2d_permode: bad arguments")
+    return y, used
+
+
+def spectral_conv1d_real(x: np.ndarray, W: np.ndarray, K: int, threads: int = 0):
+    """Real-valued layer: y[B,C_out,N] (float64) for REAL x[B,C_in,N] (float32), W[C_in,C_out] (complex64), K <= N/2."""
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.float32:
+        raise TypeError("the real-valued oracle takes float32 input (the bits the GPU also reads)")
+    W = _c64(W)
+    B, C_in, N = x.shape
+    C_in2, C_out = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N), dtype=np.float64)
+    used = _load().oracle_spectral_conv1d_real(x.ctypes.data, W.ctypes.data, y.ctypes.data, B, C_in, C_out, N, K, threads)
+    if used < 0:
+        raise ValueError("oracle_spectral_conv1d_real: bad arguments")
     return y, used
 
 

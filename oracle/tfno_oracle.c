@@ -186,6 +186,68 @@ int oracle_spectral_conv1d_permode(const float *x, const float *W, double *y,
     return conv1d_batch(x, W, y, B, C_in, C_out, N, K, threads, 1);
 }
 
+/* Real-valued variant (the R2C / C2R transforms FNO layers apply to real fields; Sec. 2.1 describes the same
+ * pipeline for the C2C case the paper measures).  x: [B, C_in, N] float32 REAL, W: [C_in, C_out] c64,
+ * y: [B, C_out, N] float64 REAL, K <= N/2:
+ *
+ *   Xh[b,c,k] = sum_n x[b,c,n] exp(-2 pi i k n / N),  k < K          (the first K bins of the R2C transform)
+ *   Yh[b,o,k] = sum_c Xh[b,c,k] W[c,o]
+ *   y[b,o,:]  = C2R_N(Yh padded with zeros to N/2 + 1 bins)
+ *
+ * where C2R is the inverse transform of the Hermitian extension: F[0] = Re Yh[0], F[k] = Yh[k] and
+ * F[N-k] = conj(Yh[k]) for 0 < k < K, zero elsewhere; y = (1/N) * inverse DFT of F, whose imaginary part
+ * vanishes and is dropped. */
+static void conv1d_real_one(const float *x, const float *W, double *y, int C_in, int C_out, int N, int K)
+{
+    cplx *sig = malloc(sizeof(cplx) * N), *spec = malloc(sizeof(cplx) * N), *scr = malloc(sizeof(cplx) * N);
+    cplx *Xh = malloc(sizeof(cplx) * (size_t)C_in * K), *Yh = malloc(sizeof(cplx) * (size_t)C_out * K);
+    for (int c = 0; c < C_in; ++c) {
+        for (int n = 0; n < N; ++n) sig[n] = (double)x[(size_t)c * N + n];
+        oracle_fft(sig, 1, spec, N, -1, scr);
+        for (int k = 0; k < K; ++k) Xh[(size_t)c * K + k] = spec[k];
+    }
+    for (int o = 0; o < C_out; ++o)
+        for (int k = 0; k < K; ++k) {
+            cplx acc = 0.0;
+            for (int c = 0; c < C_in; ++c) acc += Xh[(size_t)c * K + k] * weight(W, c, o, C_out, (size_t)k, (size_t)K, 0);
+            Yh[(size_t)o * K + k] = acc;
+        }
+    for (int o = 0; o < C_out; ++o) {
+        for (int k = 0; k < N; ++k) spec[k] = 0.0;
+        spec[0] = creal(Yh[(size_t)o * K]);
+        for (int k = 1; k < K; ++k) {
+            spec[k] = Yh[(size_t)o * K + k];
+            spec[N - k] = conj(Yh[(size_t)o * K + k]);
+        }
+        oracle_fft(spec, 1, sig, N, +1, scr);
+        for (int n = 0; n < N; ++n) y[(size_t)o * N + n] = creal(sig[n]) / (double)N;
+    }
+    free(sig); free(spec); free(scr); free(Xh); free(Yh);
+}
+
+int oracle_spectral_conv1d_real(const float *x, const float *W, double *y,
+                                int B, int C_in, int C_out, int N, int K, int threads)
+{
+    if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N <= 0 || K <= 0 || 2 * K > N) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+        #pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < B; ++b)
+            conv1d_real_one(x + (size_t)b * C_in * N, W, y + (size_t)b * C_out * N, C_in, C_out, N, K);
+    }
+#else
+    (void)threads;
+    for (int b = 0; b < B; ++b)
+        conv1d_real_one(x + (size_t)b * C_in * N, W, y + (size_t)b * C_out * N, C_in, C_out, N, K);
+#endif
+    return used;
+}
+
 /* Untruncated forward spectra of one [C, N] block (no scaling): Xh[c,k], k < N. */
 int oracle_forward_spectrum1d(const float *x, double *Xh, int C, int N)
 {

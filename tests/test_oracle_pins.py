@@ -342,6 +342,45 @@ def test_permode_plane_wave_picks_its_own_matrix(oracle_mod):
         assert np.max(np.abs(y[0, 0] - W2[0, 0, k1, k2].astype(np.complex128) * x[0, 0])) < 5e-6
 
 
+# ------------------------------------------------------ real-valued layer --
+
+@pytest.mark.parametrize("N,K", [(64, 16), (32, 16), (128, 1), (12, 5), (256, 64)])
+def test_real_matches_numpy_rfft_irfft(oracle_mod, N, K):
+    B, Ci, Co = 2, 3, 4
+    x = rng.standard_normal((B, Ci, N)).astype(np.float32)
+    W = crandn(Ci, Co)
+    y, _ = oracle_mod.spectral_conv1d_real(x, W, K)
+    half = np.zeros((B, Co, N // 2 + 1), dtype=np.complex128)
+    half[..., :K] = np.einsum("bck,co->bok", np.fft.rfft(x.astype(np.float64))[..., :K], W.astype(np.complex128))
+    assert np.max(np.abs(np.fft.irfft(half, n=N) - y)) < 1e-12
+
+
+def test_real_is_twice_the_real_part_of_the_complex_operator_minus_the_mean_term(oracle_mod):
+    """For real x: y_real = 2 Re(y_c2c) - Re(mean term), the identity a C2C-based kernel uses (bin 0 counted once)."""
+    B, Ci, Co, N, K = 2, 3, 2, 64, 12
+    x = rng.standard_normal((B, Ci, N)).astype(np.float32)
+    W = crandn(Ci, Co)
+    yr, _ = oracle_mod.spectral_conv1d_real(x, W, K)
+    yc, _ = oracle_mod.spectral_conv1d(x.astype(np.complex64), W, K)
+    y0, _ = oracle_mod.spectral_conv1d(x.astype(np.complex64), W, 1)          # the k = 0 term alone
+    assert np.max(np.abs(yr - (2 * yc.real - y0.real))) < 1e-12
+
+
+def test_real_cosine_closed_form(oracle_mod):
+    """x = cos(2 pi k n / N) with k < K and real w gives w x; with k >= K it gives 0; a constant passes with Re(w)."""
+    N, K = 64, 8
+    n = np.arange(N)
+    W = np.array([[0.75 - 0.5j]], dtype=np.complex64)
+    for k, keep in [(3, True), (7, True), (8, False), (20, False)]:
+        x = np.cos(2 * np.pi * k * n / N)[None, None].astype(np.float32)
+        y, _ = oracle_mod.spectral_conv1d_real(x, W, K)
+        # W X[k] e^{i t} + conj(W X[k]) e^{-i t} with X[k] = N/2: |W| cos(t + arg W)
+        want = np.abs(W[0, 0]) * np.cos(2 * np.pi * k * n / N + np.angle(W[0, 0])) if keep else np.zeros(N)
+        assert np.max(np.abs(y[0, 0] - want)) < 5e-6
+    y, _ = oracle_mod.spectral_conv1d_real(np.ones((1, 1, N), dtype=np.float32), W, K)
+    assert np.max(np.abs(y - 0.75)) < 1e-12
+
+
 # ------------------------------------------------------ facts the paper prints --
 
 def _needed_ops_radix2(N, kept):
