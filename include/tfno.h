@@ -140,6 +140,22 @@ tfno_status tfno_spectral_conv2d_permode(const void *x, const void *W, void *y, 
                                          int N1, int N2, int K1, int K2, void *stream);
 
 /*
+ * Real-valued 1-D layer (the R2C / C2R transforms FNO layers apply to real fields; the pipeline of Sec. 2.1 with
+ * real input and output):
+ *
+ *   y[b,o,:] = C2R_N( pad( sum_c R2C_N(x[b,c,:])[k] * W[c,o],  k < K ) )
+ *
+ * x [B, C_in, N] and y [B, C_out, N] are device pointers to contiguous float32 tensors, W [C_in, C_out] to c64;
+ * K <= N/2.  One launch of the fully fused kernel: the pencils are read as 4-byte reals, bin 0 enters the
+ * contraction with weight 1/2 and the epilogue stores 2/N times the real part of the zero-padded inverse -- the
+ * C2R transform of the Hermitian extension -- so the layer moves half the bytes of the complex one.  Shapes: N in
+ * {64,128,256,512,1024}, K a power of two with K <= N/2 and K >= 8 (N = 64), 16 (N = 128, 256), 32 (N = 512,
+ * 1024); others TFNO_ERR_UNSUPPORTED.  Needs no workspace.  Pointer, aliasing, stream and error rules as above.
+ */
+tfno_status tfno_spectral_conv1d_real(const void *x, const void *W, void *y,
+                                      int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
  * 1-D spectral convolution as three launches with truncation, zero padding and butterfly pruning built into the
  * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and

@@ -27,6 +27,7 @@ EXPORTS = (
     "tfno_spectral_conv2d_rect_staged",
     "tfno_spectral_conv2d_permode",
     "tfno_spectral_conv1d_permode",
+    "tfno_spectral_conv1d_real",
     "tfno_workspace_bytes",
     "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
@@ -56,7 +57,7 @@ def lib() -> ctypes.CDLL:
                                "(there is no fallback path)")
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
-        for name in CONV_EXPORTS + ("tfno_spectral_conv1d_permode",):
+        for name in CONV_EXPORTS + ("tfno_spectral_conv1d_permode", "tfno_spectral_conv1d_real"):
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
@@ -235,3 +236,25 @@ def spectral_conv1d_permode(x, W, y, stream=None):
 def spectral_conv2d_permode(x, W, y, stream=None):
     """W: [C_in, C_out, K1, K2]."""
     return _call_permode("tfno_spectral_conv2d_permode", 2, x, W, y, stream)
+
+
+def spectral_conv1d_real(x, W, y, K: int, stream=None):
+    """Real-valued layer: x [B, C_in, N] and y [B, C_out, N] float32 device tensors, W [C_in, C_out] complex64."""
+    import torch
+    if x.dtype != torch.float32 or y.dtype != torch.float32 or W.dtype != torch.complex64:
+        raise TypeError("x, y must be float32 and W complex64")
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous device tensor")
+    if x.dim() != 3 or y.dim() != 3 or W.dim() != 2:
+        raise ValueError("x, y must be [B, C, N]; W must be [C_in, C_out]")
+    B, C_in, N = x.shape
+    C_out = W.shape[1]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out, N):
+        raise ValueError("inconsistent tensor shapes")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = lib().tfno_spectral_conv1d_real(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, K, stream)
+    if st != OK:
+        raise TfnoError(st, "tfno_spectral_conv1d_real")
+    return y

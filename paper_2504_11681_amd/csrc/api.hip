@@ -210,6 +210,28 @@ tfno_status run_permode(const Shape &sh, const void *x, const void *W, void *y, 
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
 
+// Real-valued 1-D layer: x [B, C_in, N] and y [B, C_out, N] float32, W [C_in, C_out] c64, K <= N / 2.
+tfno_status run_real1d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K, void *stream)
+{
+    if (B < 0 || C_in < 1 || C_out < 1 || !axis_ok(N, K) || 2 * K > N) return TFNO_ERR_SHAPE;
+    if (B == 0) return TFNO_OK;
+    if (!x || !W || !y) return TFNO_ERR_NULL;
+    if ((long double)B * C_in * N >= 1099511627776.0L || (long double)B * C_out * N >= 1099511627776.0L ||
+        (long double)B * (C_in > C_out ? C_in : C_out) >= 2147483647.0L)
+        return TFNO_ERR_SHAPE;
+    const size_t xb = sizeof(float) * (size_t)B * C_in * N, yb = sizeof(float) * (size_t)B * C_out * N;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
+    if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!fused1d_real_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+    Fused1dArgs a{};
+    a.x = (const c64 *)x; a.W = (const c64 *)W; a.y = (c64 *)y; a.C_in = C_in; a.C_out = C_out;   // x, y: float tensors
+    a.inner_count = 1;
+    a.x_outer_stride = (long long)C_in * N;  a.x_inner_stride = 0; a.x_chan_stride = N;            // in floats
+    a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
+    a.scale = 2.0f / (float)N;
+    return fused1d_real_launch(N, K, a, B, (hipStream_t)stream) == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
+}
+
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
 // sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels
 // (C_out <= 128); above that every 128-output slab repeats the forward transform of its batch row, and the
@@ -238,6 +260,29 @@ bool fused1d_supported(int N, int K)
     case 512: return K >= 32 && K <= 256;
     case 1024: return K >= 32 && K <= 256;
     default: return false;
+    }
+}
+
+bool fused1d_real_supported(int N, int K)
+{
+    if (!is_pow2(K) || 2 * K > N) return false;
+    switch (N) {
+    case 64: return K >= 8;
+    case 128: case 256: return K >= 16;
+    case 512: case 1024: return K >= 32;
+    default: return false;
+    }
+}
+
+hipError_t fused1d_real_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    if (!fused1d_real_supported(N, K)) return hipErrorInvalidValue;
+    switch (N) {
+    case 64: return fused1d_real_launch_n64(K, a, rows, s);
+    case 128: return fused1d_real_launch_n128(K, a, rows, s);
+    case 256: return fused1d_real_launch_n256(K, a, rows, s);
+    case 512: return fused1d_real_launch_n512(K, a, rows, s);
+    default: return fused1d_real_launch_n1024(K, a, rows, s);
     }
 }
 
@@ -383,6 +428,12 @@ tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void 
                                              int N2, int K1, int K2, void *stream)
 {
     return run(shape2d(N1, N2, K1, K2), STAGED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv1d_real(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                      void *stream)
+{
+    return run_real1d(x, W, y, B, C_in, C_out, N, K, stream);
 }
 
 tfno_status tfno_spectral_conv1d_permode(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,

@@ -43,6 +43,15 @@ hipError_t fused1d_sym_launch(int N, int K, const Fused1dArgs &a, long long rows
 // spectrum a.Yh; mode 2 = CGEMM + iFFT in one kernel, reads the truncated input spectrum a.Xh.  Built for
 // N in {128, 256}, K in {32, 64, 128}; the contraction always runs on the BF16 matrix pipe.
 bool fused1d_partial_supported(int N, int K);
+// Real-valued layer (a.x, a.y: float32 tensors, strides in floats; a.scale = 2 / N): the fused kernel's shapes with
+// K <= N / 2.
+bool fused1d_real_supported(int N, int K);
+hipError_t fused1d_real_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_real_launch_n64(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_real_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_real_launch_n256(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_real_launch_n512(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_real_launch_n1024(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 hipError_t fused1d_partial_launch(int mode, int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 hipError_t fused1d_fftgemm_launch_n128(int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 hipError_t fused1d_fftgemm_launch_n256(int K, const Fused1dArgs &a, long long rows, hipStream_t s);

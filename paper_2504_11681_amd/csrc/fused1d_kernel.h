@@ -101,7 +101,11 @@ __device__ __forceinline__ void wave_sync()
 // EVEN: C_in is a multiple of PPI and C_out a multiple of 32 OT, so no load or store needs a mask.
 // MODE 0: fully fused.  MODE 1: FFT + CGEMM (Sec. 4.1), the accumulators leave as the truncated output spectrum
 // a.Yh.  MODE 2: CGEMM + iFFT (Sec. 4.2), the operand tiles come from the truncated input spectrum a.Xh.
-template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0>
+// REAL (MODE 0 only): the real-valued layer.  a.x and a.y point to float32 tensors (strides in floats); the forward
+// transform of a real pencil is the complex one with a zero imaginary part, whose first K bins are the R2C bins;
+// the C2R inverse of the zero-padded half spectrum is (2/N) Re( sum_k Y'[k] e^(+2 pi i k n / N) ) with Y'[0] = Y[0]/2,
+// so bin 0 is halved on its way into the operand tile, the caller passes scale = 2/N, and only real parts are stored.
+template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0, bool REAL = false>
 __global__ void __launch_bounds__(256, (FusedCfg<N, K, OT, BF>::MIN_WG_PER_CU))
 k_fused1d(Fused1dArgs a)
 {
@@ -127,8 +131,14 @@ k_fused1d(Fused1dArgs a)
     const int o_base = blockIdx.y * (32 * OT);
 
     const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
-    const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
-    c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
+    using XT = std::conditional_t<REAL, float, c64>;        // element type of x and y in global memory
+    static_assert(!REAL || MODE == 0, "the real-valued layer exists for the fully fused kernel only");
+    const XT *__restrict__ xb = reinterpret_cast<const XT *>(a.x) + bo * a.x_outer_stride + bi * a.x_inner_stride;
+    XT *__restrict__ yb = reinterpret_cast<XT *>(a.y) + bo * a.y_outer_stride + bi * a.y_inner_stride;
+    auto widen = [](XT e) __attribute__((always_inline)) {
+        if constexpr (REAL) return make_float2(e, 0.f);
+        else return e;
+    };
 
     TFNO_STAMP(0);
     // stage-A identity of this lane; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [t][p]
@@ -164,15 +174,15 @@ k_fused1d(Fused1dArgs a)
     auto load_pencil = [&](int c0) __attribute__((always_inline)) {
         const int c = c0 + ja;
         if constexpr (EVEN) {
-            const c64 *src = xb + (long long)c * a.x_chan_stride + t;
+            const XT *src = xb + (long long)c * a.x_chan_stride + t;
 #pragma unroll
-            for (int jj = 0; jj < P; ++jj) v[jj] = src[T * jj];
+            for (int jj = 0; jj < P; ++jj) v[jj] = widen(src[T * jj]);
         } else {
             const bool ok = c < a.C_in;
-            const c64 *src = xb + (long long)(ok ? c : 0) * a.x_chan_stride + t;
+            const XT *src = xb + (long long)(ok ? c : 0) * a.x_chan_stride + t;
 #pragma unroll
             for (int jj = 0; jj < P; ++jj) {
-                c64 val = src[T * jj];
+                c64 val = widen(src[T * jj]);
                 v[jj] = ok ? val : make_float2(0.f, 0.f);
             }
         }
@@ -192,6 +202,10 @@ k_fused1d(Fused1dArgs a)
     };
     // spectrum value of (channel slot jg of the block, mode k) into an operand tile
     auto put_operand = [&](float *XHb, int jg, int k, c64 val) __attribute__((always_inline)) {
+        if constexpr (REAL) {
+            const float h = k == 0 ? 0.5f : 1.0f;           // exact: the split below sees the halved value
+            val = make_float2(val.x * h, val.y * h);
+        }
         if constexpr (BF) {
             unsigned *d = reinterpret_cast<unsigned *>(XHb) + (jg >> 2) * (KT * 128) + (jg & 3) + (k >> 5) * 128 + (k & 31) * 4;
             const Split3 re = split3(val.x), im = split3(val.y);
@@ -441,9 +455,12 @@ k_fused1d(Fused1dArgs a)
         for (int p = 0; p < P; ++p) z[p] = Zw[jw * ZS + p * ZROW + t];
         RegFFT<P, +1, 1>::run(z, r);
         if (EVEN || o < a.C_out) {
-            c64 *dst = yb + (long long)o * a.y_chan_stride + t;
+            XT *dst = yb + (long long)o * a.y_chan_stride + t;
 #pragma unroll
-            for (int jj = 0; jj < P; ++jj) store_nt(dst + T * jj, r[jj]);
+            for (int jj = 0; jj < P; ++jj) {
+                if constexpr (REAL) __builtin_nontemporal_store(r[jj].x, dst + T * jj);
+                else store_nt(dst + T * jj, r[jj]);
+            }
         }
     };
 
@@ -513,16 +530,16 @@ k_fused1d(Fused1dArgs a)
     TFNO_STAMP(3);
 }
 
-template <int N, int K, int OT, bool BF, int MODE = 0>
+template <int N, int K, int OT, bool BF, int MODE = 0, bool REAL = false>
 hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
     using C = FusedCfg<N, K, OT, BF>;
     static bool attr_done = false;   // benign race: every thread sets the same value
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -530,10 +547,30 @@ hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipSt
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
     // unmasked kernel only when every workgroup's slab of 32 OT outputs exists in full
     if (a.C_in % C::PPI == 0 && a.C_out % (32 * OT) == 0)
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE, REAL>), grid, dim3(256), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE, REAL>), grid, dim3(256), C::LDS_DYN, s, a);
     return hipGetLastError();
+}
+
+// Real-valued layer: fully fused kernel, output slab (32 OT channels, OT <= MAXOT) chosen by C_out as for the
+// complex kernel; BF16x3 contraction wherever the packed operand tile fits.
+template <int N, int K, int OT>
+hipError_t launch_fused1d_real_ot(const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    if constexpr (FusedCfg<N, K, OT, true>::FITS) {
+        if (!contraction_forced_f32()) return launch_fused1d_impl<N, K, OT, true, 0, true>(a, rows, s);
+    }
+    return launch_fused1d_impl<N, K, OT, false, 0, true>(a, rows, s);
+}
+template <int N, int K, int MAXOT>
+hipError_t launch_fused1d_real(const Fused1dArgs &a, long long rows, hipStream_t s)
+{
+    if constexpr (MAXOT >= 4) {
+        if (a.C_out > 64) return launch_fused1d_real_ot<N, K, 4>(a, rows, s);
+    }
+    if (a.C_out > 32) return launch_fused1d_real_ot<N, K, 2>(a, rows, s);
+    return launch_fused1d_real_ot<N, K, 1>(a, rows, s);
 }
 
 // Partially fused variant MODE (1 or 2) for every K built, workgroup slab chosen by C_out as for the fused kernel

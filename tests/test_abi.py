@@ -99,6 +99,22 @@ def test_rect_workspace_and_unsupported_shapes(L):
     assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 256, 16, 48, None) == binding.ERR_UNSUPPORTED
 
 
+def test_real_layer_argument_checks(L):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    f = L.tfno_spectral_conv1d_real
+    assert f(None, W, y, 2, 4, 4, 64, 16, None) == binding.ERR_NULL
+    assert f(x, W, y, 2, 4, 4, 64, 64, None) == binding.ERR_SHAPE          # K <= N / 2
+    assert f(x, W, y, 2, 4, 4, 64, 33, None) == binding.ERR_SHAPE
+    assert f(x, W, y, 2, 4, 4, 48, 16, None) == binding.ERR_SHAPE
+    assert f(x, W, y, 2, 4, 4, 2048, 128, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, y, 2, 4, 4, 256, 24, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, y, 2, 4, 4, 256, 8, None) == binding.ERR_UNSUPPORTED
+    # float tensors: y right behind x (4 B per element) does not overlap, y inside x does
+    assert f(x, W, x + 4 * 2 * 4 * 64 - 4, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
+    assert f(x, W, W, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
+    assert f(None, None, None, 0, 4, 4, 64, 16, None) == binding.OK
+
+
 def test_fused_entry_points_report_unsupported_shapes(L):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, "tfno_spectral_conv1d_permode", x, W, y, 2, 4, 4, 512, 64) == binding.ERR_UNSUPPORTED

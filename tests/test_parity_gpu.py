@@ -410,6 +410,32 @@ def test_entry_points_replay_from_a_hip_graph(gpu):
         assert torch.equal(torch.view_as_real(y2), torch.view_as_real(want2))
 
 
+# real-valued layer (B, C_in, C_out, N, K): every N of the fused kernel, ragged channels, K = N/2
+REAL_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 8), (2, 33, 40, 64, 32), (3, 9, 70, 128, 32), (2, 37, 17, 128, 64),
+           (64, 64, 64, 256, 64), (5, 19, 130, 256, 32), (2, 40, 33, 256, 16), (3, 24, 96, 256, 128), (2, 17, 9, 512, 32),
+           (2, 8, 40, 512, 256), (3, 13, 129, 1024, 128), (1, 1, 1, 1024, 64), (2, 20, 30, 1024, 32), (2, 16, 64, 1024, 256),
+           (2, 128, 128, 1024, 128)]
+
+
+@pytest.mark.parametrize("shape", REAL_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_real_layer(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N, K = shape
+    say(f"[case] spectral_conv1d_real {shape}")
+    x = np.ascontiguousarray(inputs.make_x(900 + N + K, B, Ci, (N,)).real)          # float32, N(0, 1)
+    W = inputs.make_W(900 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d_real(x, W, K)
+    xd, Wd = torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda()
+    yd = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+    binding.spectral_conv1d_real(xd, Wd, yd, K)
+    torch.cuda.synchronize()
+    got = yd.cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm((got - want).ravel()) / np.linalg.norm(want.ravel())
+    mx = np.max(np.abs(got - want)) / np.max(np.abs(want))
+    say(f"   real: rel_l2={rel:.3e} max_abs/max|y|={mx:.3e}")
+    assert rel <= REL_L2 and mx <= MAX_ABS
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
