@@ -218,6 +218,30 @@ def measure_permode(torch, binding, w, steps, warmup, ramp):
     return dev, nbytes
 
 
+def measure_real(torch, binding, w, steps, warmup, ramp):
+    """Device seconds per layer of the real-valued entry point on the shape of workload w (x = real parts of the
+    seeded inputs), and its compulsory bytes (float32 x and y once)."""
+    xd, Wd, yd = device_inputs(w, torch)
+    xr = xd.real.contiguous()
+    yr = torch.zeros(yd.shape, dtype=torch.float32, device="cuda")
+    del xd, yd
+    pair = 4 * w.B * (w.C_in + w.C_out) * w.N
+    nsets = max(2, min(64, -(-(1 << 30) // pair)))
+    sets = [(xr, yr)] + [(xr.clone(), torch.zeros_like(yr)) for _ in range(nsets - 1)]
+    stream = torch.cuda.current_stream().cuda_stream
+    turn = [0]
+
+    def call():
+        xi, yi = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        binding.spectral_conv1d_real(xi, Wd, yi, w.K, stream)
+
+    _, dev = time_calls(torch, call, steps, warmup, ramp)
+    del xr, yr, Wd, sets
+    torch.cuda.empty_cache()
+    return dev, pair + 8 * w.C_in * w.C_out
+
+
 def pytorch_baseline(w, torch, binding, steps, ramp):
     """The layer as PyTorch composes it from library calls (the structure the paper measures against, Sec. 1 and 5):
     full FFT, slice, complex matmul over channels, zero pad, full inverse FFT -- rocFFT and the BLAS library under
@@ -450,6 +474,11 @@ def main():
                            "effective_hbm_GBps": nb / devp / 1e9, "hbm_frac": nb / devp / 1e9 / HBM_PEAK_GBPS,
                            "contraction_TFLOPs": flops_of(wp) / devp / 1e12})
             out["per_mode_weights"] = pm
+            # real-valued layer (R2C / C2R semantics): half the bytes of the complex layer
+            if w.name.startswith("cfg3"):
+                devr, nbr = measure_real(torch, binding, w, max(50, args.steps // 4), max(10, args.warmup // 4), args.ramp / 3)
+                out["real_1d"] = [{"workload": w.name + "_real", "us_per_layer": devr * 1e6, "layers_per_s": 1.0 / devr,
+                                   "effective_hbm_GBps": nbr / devr / 1e9, "hbm_frac": nbr / devr / 1e9 / HBM_PEAK_GBPS}]
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)
 
