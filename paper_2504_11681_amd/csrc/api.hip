@@ -77,6 +77,41 @@ bool permode_supported(const Shape &sh)
     return sh.dims == 1 ? (sh.N2 <= 1024 && pruned1d_supported(sh.N2, sh.K2)) : sh.image_kernels();
 }
 
+// Mode counts between the built kernel sizes: the request runs on the next power of two K' >= K for which a kernel
+// exists and the forward side zeroes bins K .. K'-1 before the contraction (exactly the truncation to K).
+template <class Pred>
+int round_modes(int N, int K, Pred pred)
+{
+    for (int k = 1; k <= N; k <<= 1)
+        if (k >= K && pred(N, k)) return k;
+    return 0;
+}
+bool image_modes(int, int k) { return k == 16 || k == 32 || k == 64; }
+
+// Shape the kernels of `variant` run for the request `req` (its K1, K2 replaced by built sizes); false: no kernel.
+bool kernel_shape(const Shape &req, int variant, Shape *ks)
+{
+    *ks = req;
+    if (variant == 1) return true;                          // the staged pipeline takes every K
+    if (req.dims == 1) {
+        const int k = variant == 2 ? round_modes(req.N2, req.K2, pruned1d_supported)
+                    : (variant == 3 || variant == 4) ? round_modes(req.N2, req.K2, fused1d_partial_supported)
+                    : round_modes(req.N2, req.K2, fused1d_supported);
+        ks->K2 = k;
+        return k != 0;
+    }
+    if (variant != 0) return false;
+    const int k1 = round_modes(req.N1, req.K1, image_modes), k2 = round_modes(req.N2, req.K2, image_modes);
+    if (k1 && k2 && fused2d_supported(req.N1, req.N2, k1, k2)) {
+        ks->K1 = k1;
+        ks->K2 = k2;
+        return true;
+    }
+    const int k = round_modes(req.N2, req.K2, fused1d_supported);    // strip pipeline: the first axis takes any K1
+    ks->K2 = k;
+    return k != 0;
+}
+
 tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W, size_t wb, const void *y, size_t yb,
                             void **ws)
 {
@@ -91,27 +126,23 @@ tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W
 
 enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2, FFT_GEMM = 3, GEMM_IFFT = 4 };
 
-tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out,
+tfno_status run(const Shape &req, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out,
                 void *stream)
 {
-    const int dims = sh.dims, N = sh.N2, K = sh.K2;         // N, K: the last (contiguous) axis
     const bool staged = variant == STAGED;
     bool empty;
-    tfno_status st = validate(sh, x, W, y, B, C_in, C_out, &empty);
+    tfno_status st = validate(req, x, W, y, B, C_in, C_out, &empty);
     if (st != TFNO_OK || empty) return st;
-    if (variant == PRUNED) {
-        if (dims != 1 || !pruned1d_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
-    } else if (variant == FFT_GEMM || variant == GEMM_IFFT) {
-        if (dims != 1 || !fused1d_partial_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
-    } else if (!staged && !sh.image_kernels() && !fused1d_supported(N, K)) {
-        return TFNO_ERR_UNSUPPORTED;
-    }
+    Shape sh;                                               // the kernels' shape: req with K rounded up to a built size
+    if (!kernel_shape(req, (int)variant, &sh)) return TFNO_ERR_UNSUPPORTED;
+    const int dims = sh.dims, N = sh.N2, K = sh.K2;         // N, K: the last (contiguous) axis
+    const int keep1 = req.K1, keep2 = req.K2;               // modes actually kept
 
     const size_t pts = sh.pts();
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     void *ws = nullptr;
-    st = check_workspace(workspace_for(sh, (int)variant, B, C_in, C_out), x, xb, W, wb, y, yb, &ws);
+    st = check_workspace(workspace_for(req, (int)variant, B, C_in, C_out), x, xb, W, wb, y, yb, &ws);
     if (st != TFNO_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
@@ -122,7 +153,7 @@ tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, 
     if (staged) {
         e = staged_conv(dims, xc, Wc, yc, B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2, (c64 *)ws, s);
     } else if (variant == PRUNED) {
-        e = pruned1d_launch(xc, Wc, yc, B, C_in, C_out, N, K, (c64 *)ws, s);
+        e = pruned1d_launch(xc, Wc, yc, B, C_in, C_out, N, K, keep2, (c64 *)ws, s);
     } else if (variant == FFT_GEMM || variant == GEMM_IFFT) {
         // the workspace holds one truncated spectrum: the output's (FFT + CGEMM kernel, then the pruned inverse
         // kernel) or the input's (pruned forward kernel, then the CGEMM + iFFT kernel)
@@ -132,12 +163,13 @@ tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, 
         a.x_outer_stride = (long long)C_in * N;  a.x_inner_stride = 0; a.x_chan_stride = N;
         a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
         a.scale = 1.0f / (float)N;
+        a.K_keep = keep2;
         a.Xh = (const c64 *)ws; a.Yh = (c64 *)ws;
         if (variant == FFT_GEMM) {
             e = fused1d_partial_launch(1, N, K, a, B, s);
-            if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, Wc, yc, nullptr, (c64 *)ws, B, C_in, C_out, N, K, s);
+            if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, Wc, yc, nullptr, (c64 *)ws, B, C_in, C_out, N, K, keep2, s);
         } else {
-            e = pruned1d_stages(PRUNED_FWD, xc, Wc, yc, (c64 *)ws, nullptr, B, C_in, C_out, N, K, s);
+            e = pruned1d_stages(PRUNED_FWD, xc, Wc, yc, (c64 *)ws, nullptr, B, C_in, C_out, N, K, keep2, s);
             if (e == hipSuccess) e = fused1d_partial_launch(2, N, K, a, B, s);
         }
     } else if (dims == 1) {
@@ -147,10 +179,11 @@ tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, 
         a.x_outer_stride = (long long)C_in * N;  a.x_inner_stride = 0; a.x_chan_stride = N;
         a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
         a.scale = 1.0f / (float)N;
+        a.K_keep = keep2;
         e = fused1d_launch(N, K, a, B, s);
     } else if (sh.image_kernels()) {
         // image kernels: only the truncated K1 x K2 spectra cross global memory
-        e = fused2d_launch(xc, Wc, yc, B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2, (c64 *)ws, s);
+        e = fused2d_launch(xc, Wc, yc, B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2, keep1, keep2, (c64 *)ws, s);
     } else {
         // strip pipeline (Sec. 3.2 / 3.3), for shapes the image kernels do not cover: truncated forward transform
         // along the first axis, fused kernel along the last axis on the K1 retained rows, zero-padded inverse along
@@ -167,6 +200,7 @@ tfno_status run(const Shape &sh, Variant variant, const void *x, const void *W, 
             a.x_outer_stride = (long long)C_in * KN;  a.x_inner_stride = N; a.x_chan_stride = KN;
             a.y_outer_stride = (long long)C_out * KN; a.y_inner_stride = N; a.y_chan_stride = KN;
             a.scale = 1.0f / ((float)N1 * (float)N);
+            a.K_keep = keep2;
             e = fused1d_launch(N, K, a, (long long)B * K1, s);
         }
         if (e == hipSuccess)
@@ -197,15 +231,15 @@ tfno_status run_permode(const Shape &sh, const void *x, const void *W, void *y, 
         const int N = sh.N2, K = sh.K2;
         c64 *Yh = Xh + pruned1d_spectrum_elems(B, C_in, K);
         const long long tiles = ((long long)B * K + 127) / 128;
-        e = pruned1d_stages(PRUNED_FWD, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, s);
+        e = pruned1d_stages(PRUNED_FWD, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, K, s);
         if (e == hipSuccess) e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, K, tiles, K >= 128 ? K / 128 : 1, scale, s);
-        if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, s);
+        if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, K, s);
     } else {
         c64 *Yh = Xh + (size_t)B * C_in * M;
-        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, s);
+        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, s);
         if (e == hipSuccess)
             e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, (int)M, (long long)B * (long long)(M / 128), (int)(M / 128), scale, s);
-        if (e == hipSuccess) e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, s);
+        if (e == hipSuccess) e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, s);
     }
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
@@ -222,14 +256,16 @@ tfno_status run_real1d(const void *x, const void *W, void *y, int B, int C_in, i
     const size_t xb = sizeof(float) * (size_t)B * C_in * N, yb = sizeof(float) * (size_t)B * C_out * N;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
-    if (!fused1d_real_supported(N, K)) return TFNO_ERR_UNSUPPORTED;
+    const int Kk = round_modes(N, K, fused1d_real_supported);       // the kernel's K; bins K .. Kk-1 are zeroed
+    if (!Kk) return TFNO_ERR_UNSUPPORTED;
     Fused1dArgs a{};
     a.x = (const c64 *)x; a.W = (const c64 *)W; a.y = (c64 *)y; a.C_in = C_in; a.C_out = C_out;   // x, y: float tensors
+    a.K_keep = K;
     a.inner_count = 1;
     a.x_outer_stride = (long long)C_in * N;  a.x_inner_stride = 0; a.x_chan_stride = N;            // in floats
     a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
     a.scale = 2.0f / (float)N;
-    return fused1d_real_launch(N, K, a, B, (hipStream_t)stream) == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
+    return fused1d_real_launch(N, Kk, a, B, (hipStream_t)stream) == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
 
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
@@ -238,11 +274,11 @@ tfno_status run_real1d(const void *x, const void *W, void *y, int B, int C_in, i
 // CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins by 2-11 %.
 Variant choose_variant(int N, int K, int C_out)
 {
-    if (C_out > 128 && fused1d_partial_supported(N, K)) return GEMM_IFFT;
-    if (fused1d_supported(N, K)) return FUSED;
+    if (C_out > 128 && round_modes(N, K, fused1d_partial_supported)) return GEMM_IFFT;
+    if (round_modes(N, K, fused1d_supported)) return FUSED;
     // long pencils (N = 2048, 4096) have no fused kernel: one workgroup cannot hold the K >= 128 retained modes of
     // all its output channels; the three pruned kernels move only 4 K / N of the tensor bytes extra
-    if (pruned1d_supported(N, K)) return PRUNED;
+    if (round_modes(N, K, pruned1d_supported)) return PRUNED;
     return STAGED;
 }
 
@@ -322,8 +358,10 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
             if (e && e[0] == 'g' && e[1] == 'e' && e[2] == 'n') return 2;
             return 0;
         }();
-        if (which == 0 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
-        if (which != 2 && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
+        // (they have no mode mask: a request for fewer modes than the kernel's K runs on the four-wave kernel)
+        const bool exact = a.K_keep == 0 || a.K_keep == K;
+        if (exact && which == 0 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
+        if (exact && which != 2 && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
     }
     switch (N) {
     case 64: return fused1d_launch_n64(K, a, rows, s);
@@ -339,29 +377,25 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
 
 namespace {
 
-size_t workspace_for(const Shape &sh, int variant, int B, int C_in, int C_out)
+size_t workspace_for(const Shape &req, int variant, int B, int C_in, int C_out)
 {
-    const int dims = sh.dims, N = sh.N2, K = sh.K2;
+    if (B < 1 || !sizes_ok(req, B, C_in, C_out)) return 0;
     if (variant == 5) {
-        if (dims != 1) return 0;
-        variant = (int)choose_variant(N, K, C_out);
+        if (req.dims != 1) return 0;
+        variant = (int)choose_variant(req.N2, req.K2, C_out);
     }
     if (variant == 6) {     // per-mode weights: the truncated spectra of input and output
-        if (B < 1 || !sizes_ok(sh, B, C_in, C_out) || !permode_supported(sh)) return 0;
-        return dims == 1 ? pruned1d_workspace_bytes(B, C_in, C_out, K) : fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2);
+        if (!permode_supported(req)) return 0;
+        return req.dims == 1 ? pruned1d_workspace_bytes(B, C_in, C_out, req.K2)
+                             : fused2d_workspace_bytes(B, C_in, C_out, req.K1, req.K2);
     }
-    if (variant < 0 || variant > 4) return 0;
-    if (variant == 2) {
-        if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !pruned1d_supported(N, K)) return 0;
-        return pruned1d_workspace_bytes(B, C_in, C_out, K);
-    }
-    if (variant == 3 || variant == 4) {
-        if (dims != 1 || B < 1 || C_in < 1 || C_out < 1 || !fused1d_partial_supported(N, K)) return 0;
-        return sizeof(c64) * pruned1d_spectrum_elems(B, variant == 3 ? C_out : C_in, K);
-    }
-    if (B < 1 || !sizes_ok(sh, B, C_in, C_out)) return 0;
-    if (variant == 1) return staged_workspace_bytes(B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2);
-    if (dims == 1) return 0;
+    if (variant < 0 || variant > 4 || (variant >= 2 && req.dims != 1)) return 0;
+    Shape sh;                                               // the kernels' shape (K rounded up to a built size)
+    if (!kernel_shape(req, variant, &sh)) return 0;
+    if (variant == 2) return pruned1d_workspace_bytes(B, C_in, C_out, sh.K2);
+    if (variant == 3 || variant == 4) return sizeof(c64) * pruned1d_spectrum_elems(B, variant == 3 ? C_out : C_in, sh.K2);
+    if (variant == 1) return staged_workspace_bytes(B, C_in, C_out, req.N1, req.N2, req.K1, req.K2);
+    if (sh.dims == 1) return 0;
     return sh.image_kernels() ? fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2)
                               : strip2d_workspace_bytes(B, C_in, C_out, sh.N2, sh.K1);
 }

@@ -17,6 +17,8 @@ struct Fused1dArgs {
     long long x_outer_stride, x_inner_stride, x_chan_stride;
     long long y_outer_stride, y_inner_stride, y_chan_stride;
     float scale;    // folded into W (1/N for 1-D; the 2-D pipeline passes its full 1/N^2 here)
+    int K_keep;     // modes actually kept, 1 <= K_keep <= K (0 = all K): bins K_keep .. K-1 of the kernel's K enter
+                    // the contraction as zeros, which is how mode counts between the built K are served
     // Partially fused variants only (inner_count = 1): truncated spectra in the mode-tile-major layout of the
     // unfused pruned variant, joint mode m = row * K + k at ((m / 128) * C + c) * 128 + m % 128.
     const c64 *Xh;  // read instead of x by the CGEMM + iFFT kernel

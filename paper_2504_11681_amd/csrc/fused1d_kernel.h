@@ -201,6 +201,7 @@ k_fused1d(Fused1dArgs a)
         }
     };
     // spectrum value of (channel slot jg of the block, mode k) into an operand tile
+    const int k_keep = a.K_keep > 0 ? a.K_keep : K;
     auto put_operand = [&](float *XHb, int jg, int k, c64 val) __attribute__((always_inline)) {
         if constexpr (REAL) {
             const float h = k == 0 ? 0.5f : 1.0f;           // exact: the split below sees the halved value
@@ -258,6 +259,13 @@ k_fused1d(Fused1dArgs a)
             const int jg = wave * PPW + j;
 #pragma unroll
             for (int q = 0; q < Q; ++q) put_operand(XHb, jg, p + P * q, xo[q]);
+            // truncation finer than the kernel's K: the surplus bins enter the contraction as zeros.  (A uniform
+            // branch that overwrites them; masking every value costs the full-K case 3-5 %.)
+            if (k_keep < K) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    if (p + P * q >= k_keep) put_operand(XHb, jg, p + P * q, make_float2(0.f, 0.f));
+            }
         }
     };
     // complex MAC on the matrix cores (channels past C_in carry zero spectra and zero weights)

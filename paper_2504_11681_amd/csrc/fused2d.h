@@ -11,17 +11,18 @@ bool fused2d_supported(int N1, int N2, int K1, int K2);
 size_t fused2d_workspace_bytes(long long B, int C_in, int C_out, int K1, int K2);
 // Enqueues forward transform, mode CGEMM and inverse transform on stream s.
 hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N1, int N2,
-                          int K1, int K2, c64 *ws, hipStream_t s);
+                          int K1, int K2, int k1_keep, int k2_keep, c64 *ws, hipStream_t s);
 // One of the two image kernels: dir < 0 forward x[images, N1, N2] -> Xh (C = C_in), dir > 0 inverse Yh -> y (C = C_out).
+// k1_keep, k2_keep (forward only): modes at or past them are written as zeros.
 hipError_t fused2d_images(int dir, const c64 *in, c64 *out, long long images, int C, int N1, int N2, int K1, int K2,
-                          hipStream_t s);
+                          int k1_keep, int k2_keep, hipStream_t s);
 // The two image kernels for one first-axis length (one translation unit each): forward x -> Xh, inverse Yh -> y.
 hipError_t fused2d_images_n64(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
-                              hipStream_t s);
+                              int k1_keep, int k2_keep, hipStream_t s);
 hipError_t fused2d_images_n128(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
-                               hipStream_t s);
+                               int k1_keep, int k2_keep, hipStream_t s);
 hipError_t fused2d_images_n256(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
-                               hipStream_t s);
+                               int k1_keep, int k2_keep, hipStream_t s);
 
 // Yh = Xh . (scale W) over `tiles` tiles of 128 modes; both spectra mode-tile major ([tile][channel][128]).
 hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,

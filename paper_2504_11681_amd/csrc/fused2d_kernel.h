@@ -118,7 +118,7 @@ __device__ __forceinline__ long long spec_index(long long b, int c, int C, int m
 
 template <int N1, int N2, int K1, int K2>
 __global__ void __launch_bounds__(256, 3)
-k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
+k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, int K2_keep)
 {
     using C = Cfg2d<N1, N2, K1, K2, N2 == 256>;
     constexpr int LPR = C::LPR, RPS = C::RPS, S = C::S, SWEEPS = C::SWEEPS, KH = C::KH, CPL = C::CPL;
@@ -257,7 +257,10 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in)
 #pragma unroll
             for (int ka = 0; ka < RPL; ++ka) {
                 const int k1 = ka + RPL * kb + RP * m;
-                if (k1 < K1) Xh[spec_index(b, c, C_in, k1 * K2 + k2, K1 * K2)] = acc[m * RPL + ka];
+                // (modes at or past K1_keep x K2_keep are written as zeros: truncation finer than the kernel's)
+                if (k1 < K1)
+                    Xh[spec_index(b, c, C_in, k1 * K2 + k2, K1 * K2)] =
+                        (k1 < K1_keep && k2 < K2_keep) ? acc[m * RPL + ka] : make_float2(0.f, 0.f);
             }
     }
 }

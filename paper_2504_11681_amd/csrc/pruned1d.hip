@@ -34,7 +34,7 @@ size_t pruned1d_spectrum_elems(long long B, int C, int K) { return (size_t)mode_
 
 template <int N, int K>
 static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
-                            int C_out, hipStream_t s)
+                            int C_out, int K_keep, hipStream_t s)
 {
     using Cf = CfgP1<N, K>;
     const long long tiles = mode_tiles(B, K);
@@ -44,7 +44,7 @@ static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 
     const unsigned gin = (unsigned)(sin < 1024 ? sin : 1024), gout = (unsigned)(sout < 1024 ? sout : 1024);
     hipError_t e = hipSuccess;
     if (stages & PRUNED_FWD) {
-        hipLaunchKernelGGL((k_fwd1d<N, K>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin);
+        hipLaunchKernelGGL((k_fwd1d<N, K>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin, K_keep);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (stages & PRUNED_GEMM)
@@ -58,7 +58,7 @@ static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 
 
 template <int N1, int K2>
 static hipError_t launch_long(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
-                              int C_out, hipStream_t s)
+                              int C_out, int K_keep, hipStream_t s)
 {
     using Cf = CfgLong<N1, K2>;
     const long long tiles = mode_tiles(B, Cf::K);
@@ -67,7 +67,7 @@ static hipError_t launch_long(int stages, const c64 *x, const c64 *W, c64 *y, c6
     const unsigned gin = (unsigned)(sin < 2048 ? sin : 2048), gout = (unsigned)(sout < 2048 ? sout : 2048);
     hipError_t e = hipSuccess;
     if (stages & PRUNED_FWD) {
-        hipLaunchKernelGGL((k_fwd1d_long<N1, K2>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin);
+        hipLaunchKernelGGL((k_fwd1d_long<N1, K2>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin, K_keep);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (stages & PRUNED_GEMM)
@@ -81,56 +81,56 @@ static hipError_t launch_long(int stages, const c64 *x, const c64 *W, c64 *y, c6
 
 template <int N1>
 static hipError_t launch_long_n(int K2, int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B,
-                                int C_in, int C_out, hipStream_t s)
+                                int C_in, int C_out, int K_keep, hipStream_t s)
 {
     switch (K2) {
-    case 16: return launch_long<N1, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 32: return launch_long<N1, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 64: return launch_long<N1, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 128: return launch_long<N1, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 256: return launch_long<N1, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 16: return launch_long<N1, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 32: return launch_long<N1, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 64: return launch_long<N1, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 128: return launch_long<N1, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 256: return launch_long<N1, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
     default: return hipErrorInvalidValue;
     }
 }
 
 template <int N>
 static hipError_t launch_n(int K, int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B,
-                           int C_in, int C_out, hipStream_t s)
+                           int C_in, int C_out, int K_keep, hipStream_t s)
 {
     constexpr int LPR = N / 16;
     switch (K) {
-    case 16: return launch_nk<N, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
-    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
-    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
-    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s); break;
+    case 16: return launch_nk<N, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
     default: break;
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t pruned1d_stages(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
-                           int C_out, int N, int K, hipStream_t s)
+                           int C_out, int N, int K, int K_keep, hipStream_t s)
 {
-    if (!pruned1d_supported(N, K)) return hipErrorInvalidValue;
+    if (!pruned1d_supported(N, K) || K_keep < 1 || K_keep > K) return hipErrorInvalidValue;
     switch (N) {
-    case 64: return launch_n<64>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 128: return launch_n<128>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 256: return launch_n<256>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+    case 64: return launch_n<64>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 128: return launch_n<128>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 256: return launch_n<256>(K, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
     case 1024:
-        if (K == 64) return launch_nk<1024, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-        return launch_nk<1024, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 2048: return launch_long_n<8>(K / 8, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
-    case 4096: return launch_long_n<16>(K / 16, stages, x, W, y, Xh, Yh, B, C_in, C_out, s);
+        if (K == 64) return launch_nk<1024, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+        return launch_nk<1024, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 2048: return launch_long_n<8>(K / 8, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 4096: return launch_long_n<16>(K / 16, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
     default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t pruned1d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N, int K,
-                           c64 *ws, hipStream_t s)
+                           int K_keep, c64 *ws, hipStream_t s)
 {
     return pruned1d_stages(PRUNED_FWD | PRUNED_GEMM | PRUNED_INV, x, W, y, ws, ws + pruned1d_spectrum_elems(B, C_in, K),
-                           B, C_in, C_out, N, K, s);
+                           B, C_in, C_out, N, K, K_keep, s);
 }
 
 }  // namespace tfno

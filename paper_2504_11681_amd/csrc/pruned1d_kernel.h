@@ -86,7 +86,7 @@ __device__ __forceinline__ int p1_slot(int c, int p)
 // x: [npencils, N] contiguous (pencil q = b * C + c).  Xh: mode-tile major, joint mode m = b K + k.
 template <int N, int K>
 __global__ void __launch_bounds__(256)
-k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npencils)
+k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npencils, int K_keep)
 {
     using Cf = CfgP1<N, K>;
     constexpr int LPR = Cf::LPR, PPS = Cf::PPS, KH = Cf::KH, CPL = Cf::CPL, OPL = Cf::OPL;
@@ -142,7 +142,8 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
                 }, xo);
                 if (ok) {
 #pragma unroll
-                    for (int kh = 0; kh < KH; ++kh) Xh[spec1d_index(b * K + kl + 16 * kh, ch, C)] = xo[kh];
+                    for (int kh = 0; kh < KH; ++kh)        // bins K_keep .. K-1: truncation finer than the kernel's K
+                        Xh[spec1d_index(b * K + kl + 16 * kh, ch, C)] = kl + 16 * kh < K_keep ? xo[kh] : make_float2(0.f, 0.f);
                 }
             }
         } else {
@@ -174,7 +175,8 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
             if (ok) {
 #pragma unroll
                 for (int i = 0; i < OPL; ++i)
-                    Xh[spec1d_index(b * K + kl_w + 16 * (OPL * qa + i), ch, C)] = O[i];
+                    Xh[spec1d_index(b * K + kl_w + 16 * (OPL * qa + i), ch, C)] =
+                        kl_w + 16 * (OPL * qa + i) < K_keep ? O[i] : make_float2(0.f, 0.f);
             }
         }
     };

@@ -48,7 +48,7 @@ __device__ __forceinline__ void long_setup(c64 *TW, c64 *tw0, int tid)
 // x: [npencils, N] contiguous (pencil q = b * C + c).  Xh: mode-tile major over the joint mode index b K + m.
 template <int N1, int K2>
 __global__ void __launch_bounds__(256, 3)
-k_fwd1d_long(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npencils)
+k_fwd1d_long(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npencils, int K_keep)
 {
     using Cf = CfgLong<N1, K2>;
     constexpr int N = Cf::N, K = Cf::K, G = Cf::G, KH = Cf::KH, RS = Cf::RS;
@@ -106,7 +106,9 @@ k_fwd1d_long(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long n
             const long long b = q / C;
             const int ch = (int)(q % C);
 #pragma unroll
-            for (int kh = 0; kh < KH; ++kh) Xh[spec1d_index(b * K + k1 * K2 + p + 16 * kh, ch, C)] = xo[kh];
+            for (int kh = 0; kh < KH; ++kh)                // true bin k1 + N1 k2 at or past K_keep: finer truncation
+                Xh[spec1d_index(b * K + k1 * K2 + p + 16 * kh, ch, C)] =
+                    k1 + N1 * (p + 16 * kh) < K_keep ? xo[kh] : make_float2(0.f, 0.f);
         }
     };
 

@@ -86,6 +86,7 @@ def test_rect_workspace_and_unsupported_shapes(L):
     assert binding.workspace_bytes_2d(0, 2, 3, 5, 64, 256, 16, 64) == 8 * 2 * 16 * 64 * (3 + 5)
     # strip pipeline (K1 = 8 is not an image-kernel mode count): two [B, C, K1, N2] strips
     assert binding.workspace_bytes_2d(0, 2, 3, 5, 32, 256, 8, 64) == 8 * 2 * 8 * 256 * (3 + 5)
+    assert binding.workspace_bytes_2d(0, 2, 3, 5, 64, 256, 12, 40) == 8 * 2 * 16 * 64 * (3 + 5)   # runs as 16 x 64
     assert binding.workspace_bytes_2d(1, 2, 3, 5, 32, 64, 8, 16) == 8 * 2 * (3 * 2048 + 3 * 128 + 5 * 128 + 5 * 2048)
     # the square case is the square entry point's
     assert binding.workspace_bytes_2d(0, 2, 3, 5, 64, 64, 16, 16) == binding.workspace_bytes(2, 0, 2, 3, 5, 64, 16)
@@ -96,7 +97,7 @@ def test_rect_workspace_and_unsupported_shapes(L):
     assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 128, 16, 32, None) == binding.ERR_WORKSPACE
     # last axis not covered by the fused 1-D kernel and not an image-kernel shape
     assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 2048, 16, 32, None) == binding.ERR_UNSUPPORTED
-    assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 256, 16, 48, None) == binding.ERR_UNSUPPORTED
+    assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 32, 16, 8, None) == binding.ERR_UNSUPPORTED
 
 
 def test_real_layer_argument_checks(L):
@@ -107,8 +108,7 @@ def test_real_layer_argument_checks(L):
     assert f(x, W, y, 2, 4, 4, 64, 33, None) == binding.ERR_SHAPE
     assert f(x, W, y, 2, 4, 4, 48, 16, None) == binding.ERR_SHAPE
     assert f(x, W, y, 2, 4, 4, 2048, 128, None) == binding.ERR_UNSUPPORTED
-    assert f(x, W, y, 2, 4, 4, 256, 24, None) == binding.ERR_UNSUPPORTED
-    assert f(x, W, y, 2, 4, 4, 256, 8, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, y, 2, 4, 4, 32, 8, None) == binding.ERR_UNSUPPORTED
     # float tensors: y right behind x (4 B per element) does not overlap, y inside x does
     assert f(x, W, x + 4 * 2 * 4 * 64 - 4, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
     assert f(x, W, W, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
@@ -123,12 +123,13 @@ def test_fused_entry_points_report_unsupported_shapes(L):
     # the per-mode weight tensor is C_in * C_out * K elements long: y inside its tail is an alias
     assert call(L, "tfno_spectral_conv1d_permode", x, W, W + 8 * (4 * 4 * 16 - 1), 2, 4, 4, 64, 16) == binding.ERR_ALIAS
     assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 2048, 128) == binding.ERR_UNSUPPORTED
-    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 48) == binding.ERR_UNSUPPORTED
-    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 256, 8) == binding.ERR_UNSUPPORTED
+    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 32, 8) == binding.ERR_UNSUPPORTED
+    assert call(L, "tfno_spectral_conv1d", x, W, y, 2, 4, 4, 1024, 300) == binding.ERR_UNSUPPORTED     # K' = 512 > 256
+    assert call(L, "tfno_spectral_conv1d_pruned", x, W, y, 2, 4, 4, 512, 64) == binding.ERR_UNSUPPORTED
     assert call(L, "tfno_spectral_conv2d", x, W, y, 2, 4, 4, 32, 8) == binding.ERR_UNSUPPORTED
     for name in ("tfno_spectral_conv1d_fft_gemm", "tfno_spectral_conv1d_gemm_ifft"):
         assert call(L, name, x, W, y, 2, 4, 4, 1024, 128) == binding.ERR_UNSUPPORTED
-        assert call(L, name, x, W, y, 2, 4, 4, 256, 16) == binding.ERR_UNSUPPORTED
+        assert call(L, name, x, W, y, 2, 4, 4, 256, 200) == binding.ERR_UNSUPPORTED                   # K' = 256
         assert call(L, name, x, W, y, 2, 4, 4, 64, 32) == binding.ERR_UNSUPPORTED
 
 
@@ -138,25 +139,30 @@ def test_workspace_contract(L):
     # 2-D image kernels keep the truncated K x K spectra of input and output; the strip pipeline (shapes the
     # image kernels do not cover, here K = 8) keeps two [B, C, K, N] strips
     assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 16) == 8 * 2 * 16 * 16 * (3 + 5)
-    assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 8) == 8 * 2 * 8 * 64 * (3 + 5)
+    assert binding.workspace_bytes(2, False, 2, 3, 5, 64, 8) == 8 * 2 * 16 * 16 * (3 + 5)      # K = 8 runs as 16
+    assert binding.workspace_bytes(2, False, 2, 3, 5, 512, 64) == 8 * 2 * 64 * 512 * (3 + 5)   # strip pipeline
     assert binding.workspace_bytes(2, True, 2, 3, 5, 64, 16) == 8 * 2 * (3 * 4096 + 3 * 256 + 5 * 256 + 5 * 4096)
     # pruned 1-D variant: truncated spectra of input and output, joint mode index padded to 128-mode tiles
     assert binding.workspace_bytes(1, 2, 4, 16, 16, 64, 16) == 8 * 128 * (16 + 16)
     assert binding.workspace_bytes(1, 2, 256, 128, 128, 1024, 128) == 8 * 256 * 128 * (128 + 128)
-    assert binding.workspace_bytes(1, 2, 4, 16, 16, 64, 48) == 0          # K/16 not a power of two
+    # mode counts between the built sizes run on the next built size: K = 48 -> 64
+    assert binding.workspace_bytes(1, 2, 4, 16, 16, 64, 48) == binding.workspace_bytes(1, 2, 4, 16, 16, 64, 64)
+    assert binding.workspace_bytes(1, 2, 4, 16, 16, 512, 64) == 0         # no pruned kernels for N = 512
     assert binding.workspace_bytes(2, 2, 4, 16, 16, 64, 16) == 0          # 1-D only
     # partially fused variants: one truncated spectrum, the output's (3: FFT + CGEMM) or the input's (4: CGEMM + iFFT)
     assert binding.workspace_bytes(1, 3, 4, 16, 48, 256, 64) == 8 * 2 * 128 * 48
     assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 64) == 8 * 2 * 128 * 16
     assert binding.workspace_bytes(1, 3, 4, 16, 48, 1024, 64) == 0        # N in {128, 256} only
-    assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 16) == 0         # K in {32, 64, 128} only
+    assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 16) == binding.workspace_bytes(1, 4, 4, 16, 48, 256, 32)
+    assert binding.workspace_bytes(1, 4, 4, 16, 48, 256, 200) == 0        # K in (128, 256]: no partially fused kernel
     # per-shape dispatch: the workspace of the variant it picks
     assert binding.workspace_bytes(1, 5, 4, 16, 48, 256, 64) == 0                         # fused
     assert binding.workspace_bytes(1, 5, 4, 16, 200, 256, 64) == 8 * 2 * 128 * 16         # CGEMM + iFFT
-    assert binding.workspace_bytes(1, 5, 2, 3, 4, 2048, 100) == binding.workspace_bytes(1, 1, 2, 3, 4, 2048, 100)
+    assert binding.workspace_bytes(1, 5, 2, 3, 4, 2048, 100) == binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 128)  # pruned, K' = 128
+    assert binding.workspace_bytes(1, 5, 2, 3, 4, 32, 5) == binding.workspace_bytes(1, 1, 2, 3, 4, 32, 5)          # staged
     assert binding.workspace_bytes(1, 5, 2, 3, 4, 4096, 512) == binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512)  # pruned
     assert binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512) == 8 * 1024 * (3 + 4)
-    assert binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 64) == 0          # K / 8 below 16
+    assert binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 64) == binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 128)
     # per-mode weights: the pruned variant's buffers (1-D), the image kernels' (2-D)
     assert binding.workspace_bytes(1, 6, 4, 16, 48, 256, 64) == binding.workspace_bytes(1, 2, 4, 16, 48, 256, 64)
     assert binding.workspace_bytes(1, 6, 4, 16, 48, 2048, 256) == 0       # N <= 1024 only

@@ -172,7 +172,7 @@ def test_1d_random_shapes_all_entry_points(gpu, oracle_mod, shape):
 
 def test_1d_pruned_unsupported_shapes(gpu):
     torch, binding = gpu
-    for (N, K) in [(512, 64), (1024, 32), (256, 48), (64, 8), (2048, 100), (2048, 64), (4096, 128), (4096, 768)]:
+    for (N, K) in [(512, 64), (32, 8), (1024, 200), (16, 16)]:
         x = torch.zeros((1, 2, N), dtype=torch.complex64, device="cuda")
         W = torch.zeros((2, 2), dtype=torch.complex64, device="cuda")
         y = torch.zeros((1, 2, N), dtype=torch.complex64, device="cuda")
@@ -434,6 +434,64 @@ def test_1d_real_layer(gpu, oracle_mod, shape):
     mx = np.max(np.abs(got - want)) / np.max(np.abs(want))
     say(f"   real: rel_l2={rel:.3e} max_abs/max|y|={mx:.3e}")
     assert rel <= REL_L2 and mx <= MAX_ABS
+
+
+# mode counts between the built kernel sizes (the FNO literature uses 12, 20, 24, 48 ...): the kernels run the next
+# built size and zero the surplus bins before the contraction.  (B, C_in, C_out, N, K)
+ANY_K_1D = [(3, 5, 7, 64, 12), (2, 16, 40, 128, 20), (2, 33, 17, 256, 48), (3, 9, 70, 256, 100), (2, 8, 8, 256, 1),
+            (2, 12, 20, 512, 40), (2, 24, 130, 1024, 24), (2, 32, 128, 1024, 100), (1, 3, 200, 256, 33), (2, 4, 4, 64, 5)]
+
+
+@pytest.mark.parametrize("shape", ANY_K_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_1d_any_mode_count(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N, K = shape
+    x = inputs.make_x(1000 + N + K, B, Ci, (N,))
+    W = inputs.make_W(1000 + N + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    fns = ["spectral_conv1d", "spectral_conv1d_auto", "spectral_conv1d_staged"]
+    if binding.workspace_bytes(1, 2, B, Ci, Co, N, K):
+        fns.append("spectral_conv1d_pruned")
+    if binding.workspace_bytes(1, 3, B, Ci, Co, N, K):
+        fns += ["spectral_conv1d_fft_gemm", "spectral_conv1d_gemm_ifft"]
+    for fn in fns:
+        say(f"[case] {fn} {shape}")
+        check(run_gpu(gpu, fn, x, W, K), want, fn)
+    if 2 * K <= N:
+        xr = np.ascontiguousarray(x.real)
+        wantr, _ = oracle_mod.spectral_conv1d_real(xr, W, K)
+        yd = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+        binding.spectral_conv1d_real(torch.from_numpy(xr).cuda(), torch.from_numpy(W).cuda(), yd, K)
+        torch.cuda.synchronize()
+        got = yd.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm((got - wantr).ravel()) / np.linalg.norm(wantr.ravel()) <= REL_L2
+        assert np.max(np.abs(got - wantr)) / np.max(np.abs(wantr)) <= MAX_ABS
+
+
+# (B, C_in, C_out, N1, N2, K1, K2): image kernels with rounded mode counts, strip pipeline with a rounded last axis,
+# long pencils
+ANY_K_2D = [(2, 3, 5, 64, 64, 12, 12), (1, 5, 33, 128, 256, 20, 48), (2, 4, 3, 256, 128, 64, 33), (1, 2, 2, 64, 256, 1, 5),
+            (2, 3, 4, 32, 256, 8, 40), (1, 2, 3, 512, 64, 100, 12)]
+
+
+@pytest.mark.parametrize("shape", ANY_K_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
+def test_2d_any_mode_count(gpu, oracle_mod, shape):
+    B, Ci, Co, N1, N2, K1, K2 = shape
+    say(f"[case] spectral_conv2d_rect {shape}")
+    x = inputs.make_x(1100 + N1 + K2, B, Ci, (N1, N2))
+    W = inputs.make_W(1100 + N1 + K2, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    check(run_gpu_rect(gpu, "spectral_conv2d_rect", x, W, K1, K2), want, "rect any K")
+
+
+def test_long_pencils_any_mode_count(gpu, oracle_mod):
+    for (B, Ci, Co, N, K) in [(2, 5, 7, 2048, 100), (1, 3, 4, 4096, 300), (2, 4, 4, 4096, 17)]:
+        say(f"[case] long pencils any K {(B, Ci, Co, N, K)}")
+        x = inputs.make_x(1200 + N + K, B, Ci, (N,))
+        W = inputs.make_W(1200 + N + K, Ci, Co)
+        want, _ = oracle_mod.spectral_conv1d(x, W, K)
+        for fn in ("spectral_conv1d_pruned", "spectral_conv1d_auto"):
+            check(run_gpu(gpu, fn, x, W, K), want, fn)
 
 
 def test_round_trip_identity_and_determinism(gpu):
