@@ -34,8 +34,7 @@
  *  - Mode counts: the kernels are built for the power-of-two K that each entry point lists.  Every other K, down
  *    to 1, runs on the next built size K' >= K: the forward transform zeroes bins K .. K'-1 before the contraction,
  *    which is exactly the truncation to K (Sec. 3.3), so e.g. K = 12, 20 or 48 are served by the fused kernels; a
- *    call is TFNO_ERR_UNSUPPORTED only when no built size >= K exists for its N.  Workspace sizes follow K'.  The
- *    per-mode-weight entry points are the exception: their K must be a built size.
+ *    call is TFNO_ERR_UNSUPPORTED only when no built size >= K exists for its N.  Workspace sizes follow K'.
  *  - Thread safety: entry points may be called concurrently from several host
  *    threads; tfno_set_workspace must not race with calls that use the workspace.
  */

@@ -71,11 +71,6 @@ size_t strip2d_workspace_bytes(long long B, int C_in, int C_out, int N2, int K1)
 
 size_t workspace_for(const Shape &sh, int variant, int B, int C_in, int C_out);
 
-// per-mode weights run as transform kernel, per-mode contraction, transform kernel on the truncated spectra
-bool permode_supported(const Shape &sh)
-{
-    return sh.dims == 1 ? (sh.N2 <= 1024 && pruned1d_supported(sh.N2, sh.K2)) : sh.image_kernels();
-}
 
 // Mode counts between the built kernel sizes: the request runs on the next power of two K' >= K for which a kernel
 // exists and the forward side zeroes bins K .. K'-1 before the contraction (exactly the truncation to K).
@@ -87,6 +82,7 @@ int round_modes(int N, int K, Pred pred)
     return 0;
 }
 bool image_modes(int, int k) { return k == 16 || k == 32 || k == 64; }
+bool permode_1d(int N, int K) { return N <= 1024 && pruned1d_supported(N, K); }
 
 // Shape the kernels of `variant` run for the request `req` (its K1, K2 replaced by built sizes); false: no kernel.
 bool kernel_shape(const Shape &req, int variant, Shape *ks)
@@ -94,19 +90,21 @@ bool kernel_shape(const Shape &req, int variant, Shape *ks)
     *ks = req;
     if (variant == 1) return true;                          // the staged pipeline takes every K
     if (req.dims == 1) {
-        const int k = variant == 2 ? round_modes(req.N2, req.K2, pruned1d_supported)
+        const int k = variant == 6 ? round_modes(req.N2, req.K2, permode_1d)
+                    : variant == 2 ? round_modes(req.N2, req.K2, pruned1d_supported)
                     : (variant == 3 || variant == 4) ? round_modes(req.N2, req.K2, fused1d_partial_supported)
                     : round_modes(req.N2, req.K2, fused1d_supported);
         ks->K2 = k;
         return k != 0;
     }
-    if (variant != 0) return false;
+    if (variant != 0 && variant != 6) return false;
     const int k1 = round_modes(req.N1, req.K1, image_modes), k2 = round_modes(req.N2, req.K2, image_modes);
     if (k1 && k2 && fused2d_supported(req.N1, req.N2, k1, k2)) {
         ks->K1 = k1;
         ks->K2 = k2;
         return true;
     }
+    if (variant == 6) return false;                         // per-mode weights: transform kernels on whole images only
     const int k = round_modes(req.N2, req.K2, fused1d_supported);    // strip pipeline: the first axis takes any K1
     ks->K2 = k;
     return k != 0;
@@ -210,17 +208,18 @@ tfno_status run(const Shape &req, Variant variant, const void *x, const void *W,
 }
 
 // W: [C_in, C_out, K] (1-D) or [C_in, C_out, K1, K2] (2-D), an own matrix per retained mode.
-tfno_status run_permode(const Shape &sh, const void *x, const void *W, void *y, int B, int C_in, int C_out, void *stream)
+tfno_status run_permode(const Shape &req, const void *x, const void *W, void *y, int B, int C_in, int C_out, void *stream)
 {
     bool empty;
-    tfno_status st = validate(sh, x, W, y, B, C_in, C_out, &empty, true);
+    tfno_status st = validate(req, x, W, y, B, C_in, C_out, &empty, true);
     if (st != TFNO_OK || empty) return st;
-    if (!permode_supported(sh)) return TFNO_ERR_UNSUPPORTED;
+    Shape sh;                                               // the transform kernels' shape
+    if (!kernel_shape(req, 6, &sh)) return TFNO_ERR_UNSUPPORTED;
     const size_t pts = sh.pts(), M = sh.kpts();
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
-    const size_t wb = sizeof(c64) * (size_t)C_in * C_out * M;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out * req.kpts();
     void *wsp = nullptr;
-    st = check_workspace(workspace_for(sh, 6, B, C_in, C_out), x, xb, W, wb, y, yb, &wsp);
+    st = check_workspace(workspace_for(req, 6, B, C_in, C_out), x, xb, W, wb, y, yb, &wsp);
     if (st != TFNO_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const c64 *xc = (const c64 *)x, *Wc = (const c64 *)W;
@@ -231,15 +230,18 @@ tfno_status run_permode(const Shape &sh, const void *x, const void *W, void *y, 
         const int N = sh.N2, K = sh.K2;
         c64 *Yh = Xh + pruned1d_spectrum_elems(B, C_in, K);
         const long long tiles = ((long long)B * K + 127) / 128;
-        e = pruned1d_stages(PRUNED_FWD, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, K, s);
-        if (e == hipSuccess) e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, K, tiles, K >= 128 ? K / 128 : 1, scale, s);
+        e = pruned1d_stages(PRUNED_FWD, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, req.K2, s);
+        if (e == hipSuccess)
+            e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, K, tiles, K >= 128 ? K / 128 : 1, scale, K, 1, req.K2, s);
         if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, K, s);
     } else {
         c64 *Yh = Xh + (size_t)B * C_in * M;
-        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, s);
+        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, req.K1, req.K2, s);
         if (e == hipSuccess)
-            e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, (int)M, (long long)B * (long long)(M / 128), (int)(M / 128), scale, s);
-        if (e == hipSuccess) e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, s);
+            e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, (int)M, (long long)B * (long long)(M / 128), (int)(M / 128), scale,
+                                     sh.K2, req.K1, req.K2, s);
+        if (e == hipSuccess)
+            e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, s);
     }
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
@@ -384,14 +386,12 @@ size_t workspace_for(const Shape &req, int variant, int B, int C_in, int C_out)
         if (req.dims != 1) return 0;
         variant = (int)choose_variant(req.N2, req.K2, C_out);
     }
-    if (variant == 6) {     // per-mode weights: the truncated spectra of input and output
-        if (!permode_supported(req)) return 0;
-        return req.dims == 1 ? pruned1d_workspace_bytes(B, C_in, C_out, req.K2)
-                             : fused2d_workspace_bytes(B, C_in, C_out, req.K1, req.K2);
-    }
-    if (variant < 0 || variant > 4 || (variant >= 2 && req.dims != 1)) return 0;
+    if (variant < 0 || variant > 6 || variant == 5 || (variant >= 2 && variant <= 4 && req.dims != 1)) return 0;
     Shape sh;                                               // the kernels' shape (K rounded up to a built size)
     if (!kernel_shape(req, variant, &sh)) return 0;
+    if (variant == 6)       // per-mode weights: the truncated spectra of input and output
+        return sh.dims == 1 ? pruned1d_workspace_bytes(B, C_in, C_out, sh.K2)
+                            : fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2);
     if (variant == 2) return pruned1d_workspace_bytes(B, C_in, C_out, sh.K2);
     if (variant == 3 || variant == 4) return sizeof(c64) * pruned1d_spectrum_elems(B, variant == 3 ? C_out : C_in, sh.K2);
     if (variant == 1) return staged_workspace_bytes(B, C_in, C_out, req.N1, req.N2, req.K1, req.K2);

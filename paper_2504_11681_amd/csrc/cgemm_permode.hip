@@ -5,19 +5,20 @@
 namespace tfno {
 
 hipError_t cgemm_permode_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, int M, long long num_tiles,
-                                int TPI, float scale, hipStream_t s)
+                                int TPI, float scale, int K2p, int K1a, int K2a, hipStream_t s)
 {
     if (num_tiles <= 0) return hipSuccess;
     if (TPI < 1 || M < 1 || (long long)TPI * 128 > (long long)M + 127) return hipErrorInvalidValue;
+    if (K2p < 1 || M % K2p != 0 || K1a < 1 || K1a > M / K2p || K2a < 1 || K2a > K2p) return hipErrorInvalidValue;
     const long long per = (num_tiles + TPI - 1) / TPI;      // tiles that hold the same modes
     constexpr int OT = 8;
     const unsigned gy = (unsigned)((C_out + 2 * OT - 1) / (2 * OT));
     if (per >= 8) {
         const dim3 grid((unsigned)(TPI * ((per + 7) / 8)), gy);
-        hipLaunchKernelGGL((k_cgemm_permode<8, OT>), grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale);
+        hipLaunchKernelGGL((k_cgemm_permode<8, OT>), grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale, K2p, K1a, K2a);
     } else {
         const dim3 grid((unsigned)(TPI * ((per + 1) / 2)), gy);
-        hipLaunchKernelGGL((k_cgemm_permode<2, OT>), grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale);
+        hipLaunchKernelGGL((k_cgemm_permode<2, OT>), grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale, K2p, K1a, K2a);
     }
     return hipGetLastError();
 }

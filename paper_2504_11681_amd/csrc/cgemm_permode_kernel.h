@@ -10,6 +10,7 @@
 // reuses registers: a thread accumulates BT batch elements x OT outputs, so every W value loaded is used BT times
 // and every Xh value OT times.  Tiles t with the same t % TPI hold the same modes (TPI = tiles per batch element,
 // or 1 when several batch elements share a tile), which is what lets one W value serve BT tiles.
+// W is [C_in, C_out, K1a, K2a] for the modes actually kept; the spectra may be laid out for more (see below).
 #pragma once
 #include "common.h"
 
@@ -18,12 +19,17 @@ namespace tfno {
 template <int BT, int OT>
 __global__ void __launch_bounds__(256, 2)
 k_cgemm_permode(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh, int C_in, int C_out,
-                int M, long long num_tiles, int TPI, float scale)
+                int M, long long num_tiles, int TPI, float scale, int K2p, int K1a, int K2a)
 {
     const int tid = threadIdx.x, i = tid & 127, half = tid >> 7;
     const int r = (int)(blockIdx.x % (unsigned)TPI);
     const long long grp = blockIdx.x / (unsigned)TPI;
     const int m = (r * 128 + i) % M;                        // the mode this thread owns in every tile it visits
+    // The spectra are laid out for K1p x K2p modes (M = K1p K2p, the built kernel sizes), W for the K1a x K2a modes
+    // actually kept.  Surplus modes hold zeros in Xh; they read a clamped (valid) weight.
+    const int k1 = m / K2p, k2 = m % K2p;
+    const int Ma = K1a * K2a;
+    const int wm = (k1 < K1a ? k1 : K1a - 1) * K2a + (k2 < K2a ? k2 : K2a - 1);
     const int o0 = ((int)blockIdx.y * 2 + half) * OT;
 
     const c64 *xp[BT];
@@ -38,9 +44,9 @@ k_cgemm_permode(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__re
 #pragma unroll
     for (int oi = 0; oi < OT; ++oi) {
         const int o = o0 + oi < C_out ? o0 + oi : C_out - 1;
-        wp[oi] = W + (long long)o * M + m;
+        wp[oi] = W + (long long)o * Ma + wm;
     }
-    const long long wstep = (long long)C_out * M;
+    const long long wstep = (long long)C_out * Ma;
 
     c64 acc[BT][OT];
 #pragma unroll

@@ -28,9 +28,10 @@ hipError_t fused2d_images_n256(int dir, const c64 *in, c64 *out, long long image
 hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,
                               hipStream_t s);
 
-// Yh[t][o][i] = scale * sum_c Xh[t][c][i] * W[c][o][m(t, i)] with an own weight matrix per mode, W[C_in, C_out, M];
-// tile t, lane i holds mode m = ((t % TPI) * 128 + i) % M.
+// Yh[t][o][i] = scale * sum_c Xh[t][c][i] * W[c][o][k1][k2] with an own weight matrix per mode; tile t, lane i holds
+// mode m = ((t % TPI) * 128 + i) % M = k1 K2p + k2 of the M = K1p K2p modes the spectra are laid out for, W is
+// [C_in, C_out, K1a, K2a] for the modes kept (K1a <= K1p, K2a <= K2p; the surplus modes of Xh hold zeros).
 hipError_t cgemm_permode_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, int M, long long num_tiles,
-                                int TPI, float scale, hipStream_t s);
+                                int TPI, float scale, int K2p, int K1a, int K2a, hipStream_t s);
 
 }  // namespace tfno
