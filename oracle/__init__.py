@@ -40,7 +40,7 @@ def _load():
             fn = getattr(lib, name)
             fn.restype = c_int
             fn.argtypes = [c_void, c_void, c_void] + [c_int] * 6
-        for name in ("oracle_spectral_conv2d_rect", "oracle_spectral_conv2d_permode"):
+        for name in ("oracle_spectral_conv2d_rect", "oracle_spectral_conv2d_permode", "oracle_fno2d_real"):
             fn = getattr(lib, name)
             fn.restype = c_int
             fn.argtypes = [c_void, c_void, c_void] + [c_int] * 8
@@ -147,6 +147,23 @@ def spectral_conv1d_real(x: np.ndarray, W: np.ndarray, K: int, threads: int = 0)
     used = _load().oracle_spectral_conv1d_real(x.ctypes.data, W.ctypes.data, y.ctypes.data, B, C_in, C_out, N, K, threads)
     if used < 0:
         raise ValueError("oracle_spectral_conv1d_real: bad arguments")
+    return y, used
+
+
+def fno2d_real(x: np.ndarray, W: np.ndarray, threads: int = 0):
+    """The 2-D Fourier layer of FNO models on real fields: x[B,C_in,N1,N2] float32, W[C_in,C_out,2*M1,M2] complex64
+    (first-axis frequencies -M1..M1-1 at index k1 + M1, last-axis 0..M2-1), y[B,C_out,N1,N2] float64."""
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.float32:
+        raise TypeError("x must be float32")
+    W = _c64(W)
+    B, C_in, N1, N2 = x.shape
+    C_in2, C_out, J, M2 = W.shape
+    assert C_in2 == C_in and J % 2 == 0
+    y = np.empty((B, C_out, N1, N2), dtype=np.float64)
+    used = _load().oracle_fno2d_real(x.ctypes.data, W.ctypes.data, y.ctypes.data, B, C_in, C_out, N1, N2, J // 2, M2, threads)
+    if used < 0:
+        raise ValueError("oracle_fno2d_real: bad arguments")
     return y, used
 
 

@@ -370,6 +370,91 @@ int oracle_spectral_conv2d(const float *x, const float *W, double *y,
     return oracle_spectral_conv2d_rect(x, W, y, B, C_in, C_out, N, N, K, K, threads);
 }
 
+/* The 2-D Fourier layer as FNO models apply it to real fields (Sec. 1, Sec. 2.1: R2C transform, low modes,
+ * learned weights per mode, zero padding, C2R transform), in the layout of the public FNO implementations:
+ * x: [B, C_in, N1, N2] float32 REAL;  y: [B, C_out, N1, N2] float64 REAL;
+ * W: [C_in, C_out, 2 M1, M2] c64, an own matrix per retained mode; along the first axis the retained
+ * frequencies are k1 = -M1 .. M1-1 (both low-frequency blocks of the full-length axis, index j = k1 + M1 in W),
+ * along the last axis k2 = 0 .. M2-1 of the half spectrum.  2 M1 <= N1, M2 <= N2 / 2.
+ *
+ *   Xh[c, k1, k2] = sum_{n1, n2} x[c, n1, n2] exp(-2 pi i (k1 n1 / N1 + k2 n2 / N2))
+ *   Yh[o, k1, k2] = sum_c Xh[c, k1, k2] W[c, o, k1 + M1, k2]
+ *   y = C2R over the last axis of the inverse transform over the first axis of Yh (zero elsewhere), / (N1 N2)
+ *
+ * The C2R step is written as the full inverse of the Hermitian extension F[N1 - k1, N2 - k2] = conj F[k1, k2],
+ * with the k2 = 0 column taken as the Hermitian part the C2R transform sees (its imaginary input at n2-frequency
+ * zero is ignored by taking the real part of the column's inverse along the first axis). */
+static void fno2d_one(const float *x, const float *W, double *y, int C_in, int C_out, int N1, int N2, int M1, int M2)
+{
+    size_t NN = (size_t)N1 * N2, KK = (size_t)2 * M1 * M2;
+    int NL = N1 > N2 ? N1 : N2;
+    cplx *img = malloc(sizeof(cplx) * NN), *line = malloc(sizeof(cplx) * NL), *scr = malloc(sizeof(cplx) * NL);
+    cplx *Xh = malloc(sizeof(cplx) * C_in * KK), *Yh = malloc(sizeof(cplx) * C_out * KK);
+    for (int c = 0; c < C_in; ++c) {
+        for (size_t i = 0; i < NN; ++i) img[i] = (double)x[(size_t)c * NN + i];
+        fft2_inplace(img, N1, N2, -1, line, scr);
+        for (int j = 0; j < 2 * M1; ++j) {
+            int k1 = j - M1, row = (k1 + N1) % N1;
+            for (int k2 = 0; k2 < M2; ++k2) Xh[c * KK + (size_t)j * M2 + k2] = img[(size_t)row * N2 + k2];
+        }
+    }
+    for (int o = 0; o < C_out; ++o)
+        for (size_t m = 0; m < KK; ++m) {
+            cplx acc = 0.0;
+            for (int c = 0; c < C_in; ++c) acc += Xh[c * KK + m] * weight(W, c, o, C_out, m, KK, 1);
+            Yh[o * KK + m] = acc;
+        }
+    double scale = 1.0 / ((double)N1 * (double)N2);
+    for (int o = 0; o < C_out; ++o) {
+        /* half spectrum H[row, k2], k2 <= N2/2, zero outside the retained blocks */
+        for (size_t i = 0; i < NN; ++i) img[i] = 0.0;
+        for (int j = 0; j < 2 * M1; ++j) {
+            int row = (j - M1 + N1) % N1;
+            for (int k2 = 0; k2 < M2; ++k2) img[(size_t)row * N2 + k2] = Yh[o * KK + (size_t)j * M2 + k2];
+        }
+        /* inverse along the first axis (complex), column by column */
+        for (int k2 = 0; k2 < M2; ++k2) {
+            oracle_fft(img + k2, N2, line, N1, +1, scr);
+            for (int r = 0; r < N1; ++r) img[(size_t)r * N2 + k2] = line[r];
+        }
+        /* C2R along the last axis of every row: Hermitian extension, inverse, real part */
+        for (int r = 0; r < N1; ++r) {
+            cplx *rowp = img + (size_t)r * N2;
+            rowp[0] = creal(rowp[0]);
+            for (int k2 = 1; k2 < M2; ++k2) rowp[N2 - k2] = conj(rowp[k2]);
+            oracle_fft(rowp, 1, line, N2, +1, scr);
+            for (int n2 = 0; n2 < N2; ++n2) y[(size_t)o * NN + (size_t)r * N2 + n2] = creal(line[n2]) * scale;
+        }
+    }
+    free(img); free(line); free(scr); free(Xh); free(Yh);
+}
+
+int oracle_fno2d_real(const float *x, const float *W, double *y, int B, int C_in, int C_out,
+                      int N1, int N2, int M1, int M2, int threads)
+{
+    if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N1 <= 0 || N2 <= 0 || M1 <= 0 || M2 <= 0 ||
+        2 * M1 > N1 || 2 * M2 > N2)
+        return -1;
+    int used = 1;
+    size_t NN = (size_t)N1 * N2;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    #pragma omp parallel
+    {
+        #pragma omp single
+        used = omp_get_num_threads();
+        #pragma omp for schedule(dynamic, 1)
+        for (int b = 0; b < B; ++b)
+            fno2d_one(x + (size_t)b * C_in * NN, W, y + (size_t)b * C_out * NN, C_in, C_out, N1, N2, M1, M2);
+    }
+#else
+    (void)threads;
+    for (int b = 0; b < B; ++b)
+        fno2d_one(x + (size_t)b * C_in * NN, W, y + (size_t)b * C_out * NN, C_in, C_out, N1, N2, M1, M2);
+#endif
+    return used;
+}
+
 /* Thin complex128 entry points for the pin tests (buffers interleaved doubles). */
 void oracle_fft_c128(const double *in, double *out, int N, int sign)
 {

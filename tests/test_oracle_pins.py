@@ -381,6 +381,39 @@ def test_real_cosine_closed_form(oracle_mod):
     assert np.max(np.abs(y - 0.75)) < 1e-12
 
 
+# ------------------------------------------------------ FNO 2-D layer on real fields --
+
+@pytest.mark.parametrize("N1,N2,M1,M2", [(16, 16, 4, 4), (32, 16, 6, 8), (8, 64, 4, 12), (64, 32, 1, 1), (12, 20, 3, 5)])
+def test_fno2d_matches_numpy_rfft2_irfft2(oracle_mod, N1, N2, M1, M2):
+    """The reference formulation: rfft2, the two low-frequency corners with their own weights, irfft2."""
+    B, Ci, Co = 2, 3, 2
+    x = rng.standard_normal((B, Ci, N1, N2)).astype(np.float32)
+    W = crandn(Ci, Co, 2 * M1, M2)
+    y, _ = oracle_mod.fno2d_real(x, W)
+    xf = np.fft.rfft2(x.astype(np.float64))
+    out = np.zeros((B, Co, N1, N2 // 2 + 1), dtype=np.complex128)
+    Wd = W.astype(np.complex128)
+    out[:, :, :M1, :M2] = np.einsum("bixy,ioxy->boxy", xf[:, :, :M1, :M2], Wd[:, :, M1:, :])       # k1 = 0 .. M1-1
+    out[:, :, -M1:, :M2] = np.einsum("bixy,ioxy->boxy", xf[:, :, -M1:, :M2], Wd[:, :, :M1, :])     # k1 = -M1 .. -1
+    assert np.max(np.abs(np.fft.irfft2(out, s=(N1, N2)) - y)) < 1e-12
+
+
+def test_fno2d_plane_wave_picks_its_mode(oracle_mod):
+    """cos(2 pi (k1 n1/N1 + k2 n2/N2)) is scaled and phase-shifted by W[.., k1 + M1, k2] alone (k2 > 0): catches a wrong
+    sign of k1, swapped blocks and swapped axes."""
+    N1, N2, M1, M2 = 16, 32, 3, 5
+    W = crandn(1, 1, 2 * M1, M2)
+    n1, n2 = np.meshgrid(np.arange(N1), np.arange(N2), indexing="ij")
+    for (k1, k2) in [(2, 3), (-3, 1), (-1, 4), (0, 2)]:
+        ph = 2 * np.pi * (k1 * n1 / N1 + k2 * n2 / N2)
+        x = np.cos(ph)[None, None].astype(np.float32)
+        y, _ = oracle_mod.fno2d_real(x, W)
+        w = W[0, 0, k1 + M1, k2].astype(np.complex128)
+        assert np.max(np.abs(y[0, 0] - np.abs(w) * np.cos(ph + np.angle(w)))) < 5e-6
+    x = np.cos(2 * np.pi * (M1 * n1 / N1 + 2 * n2 / N2))[None, None].astype(np.float32)      # k1 = M1: outside
+    assert np.max(np.abs(oracle_mod.fno2d_real(x, W)[0])) < 5e-6
+
+
 # ------------------------------------------------------ facts the paper prints --
 
 def _needed_ops_radix2(N, kept):
