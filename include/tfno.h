@@ -160,6 +160,26 @@ tfno_status tfno_spectral_conv1d_real(const void *x, const void *W, void *y,
                                       int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
+ * The 2-D Fourier layer as FNO models apply it to real fields (Sec. 1 and Sec. 2.1 describe the pipeline; the
+ * paper's kernels and the entry points above are its C2C form with one low-frequency corner and a shared W):
+ *
+ *   y = irfft2( pad( sum_c rfft2(x[b,c])[k1, k2] * W[c, o, k1 + M1, k2] ) ),   -M1 <= k1 < M1,  0 <= k2 < M2
+ *
+ * x [B, C_in, N1, N2] and y [B, C_out, N1, N2] are device pointers to contiguous float32 tensors; W is
+ * [C_in, C_out, 2 M1, M2] c64, an own matrix per retained mode, the first-axis index holding the frequencies
+ * -M1 .. M1-1 in this order (the block of negative frequencies first; public FNO implementations keep the two
+ * blocks as two weight tensors: concatenate "weights2" then "weights1" along that axis).  2 M1 <= N1, 2 M2 <= N2.
+ * Three launches: the forward image kernel (reads float32 rows, R2C along the last axis, both low-frequency blocks
+ * of the first), the per-mode contraction, the inverse image kernel (C2R: stores the real part).  Shapes: N1, N2 in
+ * {64, 128, 256}, 2 M1 <= 64, M2 <= 64 (any such M1, M2: the kernels run the next built block size); others
+ * TFNO_ERR_UNSUPPORTED.  Needs tfno_fno2d_real_workspace_bytes(...) bytes of workspace (0 for unsupported or invalid
+ * arguments).  Pointer, aliasing, stream and error rules as above.
+ */
+tfno_status tfno_fno2d_real(const void *x, const void *W, void *y, int B, int C_in, int C_out,
+                            int N1, int N2, int M1, int M2, void *stream);
+size_t tfno_fno2d_real_workspace_bytes(int B, int C_in, int C_out, int N1, int N2, int M1, int M2);
+
+/*
  * 1-D spectral convolution as three launches with truncation, zero padding and butterfly pruning built into the
  * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and

@@ -28,6 +28,8 @@ EXPORTS = (
     "tfno_spectral_conv2d_permode",
     "tfno_spectral_conv1d_permode",
     "tfno_spectral_conv1d_real",
+    "tfno_fno2d_real",
+    "tfno_fno2d_real_workspace_bytes",
     "tfno_workspace_bytes",
     "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
@@ -65,6 +67,10 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
+        L.tfno_fno2d_real.restype = ci
+        L.tfno_fno2d_real.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
+        L.tfno_fno2d_real_workspace_bytes.restype = ctypes.c_size_t
+        L.tfno_fno2d_real_workspace_bytes.argtypes = [ci] * 7
         L.tfno_workspace_bytes.restype = ctypes.c_size_t
         L.tfno_workspace_bytes.argtypes = [ci] * 7
         L.tfno_workspace_bytes_2d.restype = ctypes.c_size_t
@@ -257,4 +263,28 @@ def spectral_conv1d_real(x, W, y, K: int, stream=None):
     st = lib().tfno_spectral_conv1d_real(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, K, stream)
     if st != OK:
         raise TfnoError(st, "tfno_spectral_conv1d_real")
+    return y
+
+
+def fno2d_real(x, W, y, stream=None):
+    """The 2-D Fourier layer of FNO models on real fields: x [B, C_in, N1, N2] and y [B, C_out, N1, N2] float32,
+    W [C_in, C_out, 2*M1, M2] complex64 (first-axis frequencies -M1..M1-1, last-axis 0..M2-1)."""
+    import torch
+    if x.dtype != torch.float32 or y.dtype != torch.float32 or W.dtype != torch.complex64:
+        raise TypeError("x, y must be float32 and W complex64")
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous device tensor")
+    if x.dim() != 4 or y.dim() != 4 or W.dim() != 4 or W.shape[2] % 2:
+        raise ValueError("x, y must be [B, C, N1, N2]; W must be [C_in, C_out, 2*M1, M2]")
+    B, C_in, N1, N2 = x.shape
+    C_out, M1, M2 = W.shape[1], W.shape[2] // 2, W.shape[3]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out, N1, N2):
+        raise ValueError("inconsistent tensor shapes")
+    ensure_workspace(lib().tfno_fno2d_real_workspace_bytes(B, C_in, C_out, N1, N2, M1, M2), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = lib().tfno_fno2d_real(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N1, N2, M1, M2, stream)
+    if st != OK:
+        raise TfnoError(st, "tfno_fno2d_real")
     return y

@@ -236,12 +236,12 @@ tfno_status run_permode(const Shape &req, const void *x, const void *W, void *y,
         if (e == hipSuccess) e = pruned1d_stages(PRUNED_INV, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, N, K, K, s);
     } else {
         c64 *Yh = Xh + (size_t)B * C_in * M;
-        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, req.K1, req.K2, s);
+        e = fused2d_images(-1, xc, Xh, (long long)B * C_in, C_in, sh.N1, sh.N2, sh.K1, sh.K2, req.K1, req.K2, false, 0, s);
         if (e == hipSuccess)
             e = cgemm_permode_launch(Xh, Wc, Yh, C_in, C_out, (int)M, (long long)B * (long long)(M / 128), (int)(M / 128), scale,
                                      sh.K2, req.K1, req.K2, s);
         if (e == hipSuccess)
-            e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, s);
+            e = fused2d_images(+1, Yh, yc, (long long)B * C_out, C_out, sh.N1, sh.N2, sh.K1, sh.K2, sh.K1, sh.K2, false, 0, s);
     }
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
@@ -268,6 +268,48 @@ tfno_status run_real1d(const void *x, const void *W, void *y, int B, int C_in, i
     a.y_outer_stride = (long long)C_out * N; a.y_inner_stride = 0; a.y_chan_stride = N;
     a.scale = 2.0f / (float)N;
     return fused1d_real_launch(N, Kk, a, B, (hipStream_t)stream) == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
+}
+
+// The 2-D Fourier layer of FNO models on real fields: x [B, C_in, N1, N2] and y [B, C_out, N1, N2] float32,
+// W [C_in, C_out, 2 M1, M2] c64 (first-axis frequencies -M1 .. M1-1 at index k1 + M1, last-axis 0 .. M2-1).
+tfno_status run_fno2d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1, int N2, int M1, int M2,
+                      void *stream, size_t *ws_bytes)
+{
+    if (ws_bytes) *ws_bytes = 0;
+    if (B < 0 || C_in < 1 || C_out < 1 || !axis_ok(N1, 1) || !axis_ok(N2, 1) || M1 < 1 || M2 < 1 || 2 * M1 > N1 ||
+        2 * M2 > N2)
+        return TFNO_ERR_SHAPE;
+    // the transform kernels' block of modes: the next built sizes
+    const int K1 = round_modes(N1, 2 * M1, image_modes), K2 = round_modes(N2, M2, image_modes);
+    const bool have = K1 && K2 && fused2d_supported(N1, N2, K1, K2);
+    if (ws_bytes) {                                         // size query only
+        if (have && B > 0) *ws_bytes = fused2d_workspace_bytes(B, C_in, C_out, K1, K2);
+        return have ? TFNO_OK : TFNO_ERR_UNSUPPORTED;
+    }
+    if (B == 0) return TFNO_OK;
+    if (!x || !W || !y) return TFNO_ERR_NULL;
+    const size_t pts = (size_t)N1 * N2;
+    if ((long double)B * C_in * pts >= 1099511627776.0L || (long double)B * C_out * pts >= 1099511627776.0L ||
+        (long double)B * (C_in > C_out ? C_in : C_out) >= 2147483647.0L)
+        return TFNO_ERR_SHAPE;
+    const size_t xb = sizeof(float) * (size_t)B * C_in * pts, yb = sizeof(float) * (size_t)B * C_out * pts;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out * 2 * M1 * M2;
+    if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!have) return TFNO_ERR_UNSUPPORTED;
+    void *wsp = nullptr;
+    tfno_status st = check_workspace(fused2d_workspace_bytes(B, C_in, C_out, K1, K2), x, xb, W, wb, y, yb, &wsp);
+    if (st != TFNO_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t M = (size_t)K1 * K2;
+    c64 *Xh = (c64 *)wsp, *Yh = Xh + (size_t)B * C_in * M;
+    const float scale = 2.0f / ((float)N1 * (float)N2);     // C2R along the last axis: twice the real part
+    hipError_t e = fused2d_images(-1, (const c64 *)x, Xh, (long long)B * C_in, C_in, N1, N2, K1, K2, 2 * M1, M2, true, M1, s);
+    if (e == hipSuccess)
+        e = cgemm_permode_launch(Xh, (const c64 *)W, Yh, C_in, C_out, (int)M, (long long)B * (long long)(M / 128),
+                                 (int)(M / 128), scale, K2, 2 * M1, M2, s);
+    if (e == hipSuccess)
+        e = fused2d_images(+1, Yh, (c64 *)y, (long long)B * C_out, C_out, N1, N2, K1, K2, K1, K2, true, M1, s);
+    return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
 
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
@@ -468,6 +510,19 @@ tfno_status tfno_spectral_conv1d_real(const void *x, const void *W, void *y, int
                                       void *stream)
 {
     return run_real1d(x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_fno2d_real(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1, int N2, int M1,
+                            int M2, void *stream)
+{
+    return run_fno2d(x, W, y, B, C_in, C_out, N1, N2, M1, M2, stream, nullptr);
+}
+
+size_t tfno_fno2d_real_workspace_bytes(int B, int C_in, int C_out, int N1, int N2, int M1, int M2)
+{
+    size_t bytes = 0;
+    run_fno2d(nullptr, nullptr, nullptr, B, C_in, C_out, N1, N2, M1, M2, nullptr, &bytes);
+    return bytes;
 }
 
 tfno_status tfno_spectral_conv1d_permode(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,

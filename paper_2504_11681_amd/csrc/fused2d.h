@@ -14,15 +14,21 @@ hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C
                           int K1, int K2, int k1_keep, int k2_keep, c64 *ws, hipStream_t s);
 // One of the two image kernels: dir < 0 forward x[images, N1, N2] -> Xh (C = C_in), dir > 0 inverse Yh -> y (C = C_out).
 // k1_keep, k2_keep (forward only): modes at or past them are written as zeros.
+// fno: the real-field variants (x, y float32 images; first-axis frequencies -h1 .. K1-h1-1 at positions 0 .. K1-1;
+// R2C / C2R along the last axis, the caller's contraction carries the scale 2 / (N1 N2)); h1 is ignored otherwise.
 hipError_t fused2d_images(int dir, const c64 *in, c64 *out, long long images, int C, int N1, int N2, int K1, int K2,
-                          int k1_keep, int k2_keep, hipStream_t s);
-// The two image kernels for one first-axis length (one translation unit each): forward x -> Xh, inverse Yh -> y.
-hipError_t fused2d_images_n64(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
-                              int k1_keep, int k2_keep, hipStream_t s);
-hipError_t fused2d_images_n128(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
-                               int k1_keep, int k2_keep, hipStream_t s);
-hipError_t fused2d_images_n256(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2,
-                               int k1_keep, int k2_keep, hipStream_t s);
+                          int k1_keep, int k2_keep, bool fno, int h1, hipStream_t s);
+// The two image kernels for one first-axis length (one translation unit each; fused2d_fno_*: the real-field variants).
+#define TFNO_DECLARE_IMAGES(name)                                                                                     \
+    hipError_t name(int dir, const c64 *in, c64 *out, long long images, int C, int N2, int K1, int K2, int k1_keep, \
+                    int k2_keep, int h1, hipStream_t s)
+TFNO_DECLARE_IMAGES(fused2d_images_n64);
+TFNO_DECLARE_IMAGES(fused2d_images_n128);
+TFNO_DECLARE_IMAGES(fused2d_images_n256);
+TFNO_DECLARE_IMAGES(fused2d_fno_images_n64);
+TFNO_DECLARE_IMAGES(fused2d_fno_images_n128);
+TFNO_DECLARE_IMAGES(fused2d_fno_images_n256);
+#undef TFNO_DECLARE_IMAGES
 
 // Yh = Xh . (scale W) over `tiles` tiles of 128 modes; both spectra mode-tile major ([tile][channel][128]).
 hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, int C_out, float scale, long long tiles,

@@ -40,11 +40,12 @@ hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, in
 }
 
 hipError_t fused2d_images(int dir, const c64 *in, c64 *out, long long images, int C, int N1, int N2, int K1, int K2,
-                          int k1_keep, int k2_keep, hipStream_t s)
+                          int k1_keep, int k2_keep, bool fno, int h1, hipStream_t s)
 {
-    if (!fused2d_supported(N1, N2, K1, K2)) return hipErrorInvalidValue;
-    auto run = N1 == 64 ? fused2d_images_n64 : N1 == 128 ? fused2d_images_n128 : fused2d_images_n256;
-    return run(dir, in, out, images, C, N2, K1, K2, k1_keep, k2_keep, s);
+    if (!fused2d_supported(N1, N2, K1, K2) || (fno && (h1 < 0 || h1 > K1))) return hipErrorInvalidValue;
+    auto run = fno ? (N1 == 64 ? fused2d_fno_images_n64 : N1 == 128 ? fused2d_fno_images_n128 : fused2d_fno_images_n256)
+                   : (N1 == 64 ? fused2d_images_n64 : N1 == 128 ? fused2d_images_n128 : fused2d_images_n256);
+    return run(dir, in, out, images, C, N2, K1, K2, k1_keep, k2_keep, fno ? h1 : 0, s);
 }
 
 hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C_in, int C_out, int N1, int N2,
@@ -52,11 +53,11 @@ hipError_t fused2d_launch(const c64 *x, const c64 *W, c64 *y, long long B, int C
 {
     const int M = K1 * K2;                                  // a multiple of 128
     c64 *Xh = ws, *Yh = ws + (size_t)B * C_in * M;
-    hipError_t e = fused2d_images(-1, x, Xh, B * C_in, C_in, N1, N2, K1, K2, k1_keep, k2_keep, s);
+    hipError_t e = fused2d_images(-1, x, Xh, B * C_in, C_in, N1, N2, K1, K2, k1_keep, k2_keep, false, 0, s);
     if (e != hipSuccess) return e;
     e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / ((float)N1 * (float)N2), B * (M / 128), s);
     if (e != hipSuccess) return e;
-    return fused2d_images(+1, Yh, y, B * C_out, C_out, N1, N2, K1, K2, K1, K2, s);
+    return fused2d_images(+1, Yh, y, B * C_out, C_out, N1, N2, K1, K2, K1, K2, false, 0, s);
 }
 
 }  // namespace tfno

@@ -1,0 +1,4 @@
+// 2-D image kernels of the real-field FNO layer for images with 256 rows.
+#define TFNO_N1 256
+#define TFNO_FNO 1
+#include "fused2d_images.inc"

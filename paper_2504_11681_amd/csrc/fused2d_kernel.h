@@ -116,9 +116,15 @@ __device__ __forceinline__ long long spec_index(long long b, int c, int C, int m
     return ((b * (M / 128) + m / 128) * C + c) * 128 + m % 128;
 }
 
-template <int N1, int N2, int K1, int K2>
+// FNO (both kernels): the layer as FNO models apply it to real fields.  x and y are float32 images; the first axis
+// keeps the frequencies k1 = -h1 .. K1-h1-1 (both low-frequency blocks; position j = k1 + h1 in the spectrum
+// buffers) -- a thread's accumulator slots then stand for other frequencies of the same residue mod RP, which only
+// changes the exponents of the pass twiddles --; the last axis is the R2C / C2R pair: the forward transform of a
+// real row is the complex one with zero imaginary part, and the C2R inverse equals twice the real part of the
+// zero-padded complex inverse once the k2 = 0 column is halved (done here, at the spectrum store).
+template <int N1, int N2, int K1, int K2, bool FNO = false>
 __global__ void __launch_bounds__(256, 3)
-k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, int K2_keep)
+k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, int K2_keep, int h1)
 {
     using C = Cfg2d<N1, N2, K1, K2, N2 == 256>;
     constexpr int LPR = C::LPR, RPS = C::RPS, S = C::S, SWEEPS = C::SWEEPS, KH = C::KH, CPL = C::CPL;
@@ -130,7 +136,8 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, 
     // (workgroup id = image: giving each XCD a contiguous range of images, which helps the 1-D kernels, measured
     // 5-9 % slower here)
     const unsigned image = blockIdx.x;
-    const c64 *__restrict__ img = x + (long long)image * N1 * N2;
+    using XT = std::conditional_t<FNO, float, c64>;
+    const XT *__restrict__ img = reinterpret_cast<const XT *>(x) + (long long)image * N1 * N2;
     // row-stage identity
     const bool row_on = tid < C::ACTIVE;
     const int g = tid / LPR, p = tid % LPR;
@@ -149,12 +156,13 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, 
     const int r_rot = (int)(blockIdx.x >> 3);
     auto load_rows = [&](c64 *v, int sweep) __attribute__((always_inline)) {
         const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
-        const c64 *src = img + (long long)(r + S * s) * N2 + p;
+        const XT *src = img + (long long)(r + S * s) * N2 + p;
         if (row_on) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 // (quarter-line pieces per row and instruction, LPR = 4, measured 13 % faster through the cache)
-                if constexpr (LPR >= 8) v[j] = load_nt(src + LPR * j);
+                if constexpr (FNO) v[j] = make_float2(src[LPR * j], 0.f);
+                else if constexpr (LPR >= 8) v[j] = load_nt(src + LPR * j);
                 else v[j] = src[LPR * j];
             }
         }
@@ -224,7 +232,8 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, 
             t = quad_dft4_fwd(t, q4);                       // F_r[ka + RPL kb]
 #pragma unroll
             for (int m = 0; m < MREP; ++m) {
-                const int k1 = ka + RPL * kb + RP * m;
+                // frequency of accumulator slot (ka, m); FNO: position jres + RP m of the block, frequency - h1
+                const int k1 = FNO ? (ka + RPL * kb + h1) % RP + RP * m - h1 : ka + RPL * kb + RP * m;
                 acc[m * RPL + ka] = cmac(acc[m * RPL + ka], t, L.twn[(r * k1) & (N1 - 1)]);
             }
         }
@@ -256,19 +265,24 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, 
         for (int m = 0; m < MREP; ++m)
 #pragma unroll
             for (int ka = 0; ka < RPL; ++ka) {
-                const int k1 = ka + RPL * kb + RP * m;
+                // position in the block of retained first-axis modes (FNO: frequency k1 - h1)
+                const int k1 = FNO ? (ka + RPL * kb + h1) % RP + RP * m : ka + RPL * kb + RP * m;
+                c64 val = acc[m * RPL + ka];
+                if constexpr (FNO) {
+                    if (k2 == 0) val = make_float2(0.5f * val.x, 0.5f * val.y);
+                }
                 // (modes at or past K1_keep x K2_keep are written as zeros: truncation finer than the kernel's)
                 if (k1 < K1)
                     Xh[spec_index(b, c, C_in, k1 * K2 + k2, K1 * K2)] =
-                        (k1 < K1_keep && k2 < K2_keep) ? acc[m * RPL + ka] : make_float2(0.f, 0.f);
+                        (k1 < K1_keep && k2 < K2_keep) ? val : make_float2(0.f, 0.f);
             }
     }
 }
 
 // ------------------------------------------------------------------------------------------------ inverse
-template <int N1, int N2, int K1, int K2>
+template <int N1, int N2, int K1, int K2, bool FNO = false>
 __global__ void __launch_bounds__(256, 3)
-k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
+k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out, int h1)
 {
     using C = Cfg2d<N1, N2, K1, K2, false>;
     constexpr int LPR = C::LPR, RPS = C::RPS, S = C::S, SWEEPS = C::SWEEPS, KH = C::KH, CPL = C::CPL;
@@ -278,7 +292,8 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
     const Lds2d L = lds_setup<N1, N2, K1, K2, C::RP == 16>(raw, tid);
 
     const unsigned image = blockIdx.x;
-    c64 *__restrict__ img = y + (long long)image * N1 * N2;
+    using XT = std::conditional_t<FNO, float, c64>;
+    XT *__restrict__ img = reinterpret_cast<XT *>(y) + (long long)image * N1 * N2;
     const bool row_on = tid < C::ACTIVE;
     const int g = tid / LPR, p = tid % LPR;
     c64 *scr = L.scr + g * GS;
@@ -294,7 +309,7 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
         for (int m = 0; m < MREP; ++m)
 #pragma unroll
             for (int ka = 0; ka < RPL; ++ka) {
-                const int k1 = ka + RPL * kb + RP * m;
+                const int k1 = FNO ? (ka + RPL * kb + h1) % RP + RP * m : ka + RPL * kb + RP * m;   // position in the block
                 const bool ok = col_on && k1 < K1;
                 c64 v = Yh[spec_index(b, o, C_out, ok ? k1 * K2 + k2 : 0, K1 * K2)];
                 Y[m * RPL + ka] = ok ? v : make_float2(0.f, 0.f);
@@ -313,7 +328,7 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
             c64 t = make_float2(0.f, 0.f);
 #pragma unroll
             for (int m = 0; m < MREP; ++m) {
-                const int k1 = ka + RPL * kb + RP * m;
+                const int k1 = FNO ? (ka + RPL * kb + h1) % RP + RP * m - h1 : ka + RPL * kb + RP * m;     // frequency
                 const c64 w = L.twn[(r * k1) & (N1 - 1)];
                 t = cmac(t, Y[m * RPL + ka], make_float2(w.x, -w.y));
             }
@@ -361,13 +376,14 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out)
     auto store_rows = [&](const c64 *out, int sweep) __attribute__((always_inline)) {
         if (!row_on) return;
         const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
-        c64 *dst = img + (long long)(r + S * s) * N2 + p;
+        XT *dst = img + (long long)(r + S * s) * N2 + p;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             // non-temporal only where the LPR lanes of a row write whole 128-byte lines: with narrower rows every
             // store instruction leaves half or quarter lines, which cost up to 40 % of the kernel time when they
             // bypass the cache that would have merged them
-            if constexpr (LPR >= 16) store_nt(dst + LPR * j, out[j]);
+            if constexpr (FNO) dst[LPR * j] = out[j].x;    // the C2R result: the real part (the scale 2 / (N1 N2) is in W)
+            else if constexpr (LPR >= 16) store_nt(dst + LPR * j, out[j]);
             else dst[LPR * j] = out[j];
         }
     };

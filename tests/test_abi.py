@@ -115,6 +115,26 @@ def test_real_layer_argument_checks(L):
     assert f(None, None, None, 0, 4, 4, 64, 16, None) == binding.OK
 
 
+def test_fno2d_argument_checks_and_workspace(L):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    f = L.tfno_fno2d_real
+    assert L.tfno_set_workspace(None, 0) == binding.OK
+    assert f(None, W, y, 2, 4, 4, 64, 64, 12, 12, None) == binding.ERR_NULL
+    assert f(x, W, y, 2, 4, 4, 64, 64, 33, 12, None) == binding.ERR_SHAPE           # 2 M1 <= N1
+    assert f(x, W, y, 2, 4, 4, 64, 64, 12, 33, None) == binding.ERR_SHAPE           # 2 M2 <= N2
+    assert f(x, W, y, 2, 4, 4, 48, 64, 12, 12, None) == binding.ERR_SHAPE
+    assert f(x, W, y, 2, 4, 4, 512, 64, 12, 12, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, y, 2, 4, 4, 256, 256, 40, 12, None) == binding.ERR_UNSUPPORTED   # 2 M1 > 64
+    assert f(x, W, x, 2, 4, 4, 64, 64, 12, 12, None) == binding.ERR_ALIAS
+    assert f(x, W, y, 2, 4, 4, 64, 64, 12, 12, None) == binding.ERR_WORKSPACE
+    assert f(None, None, None, 0, 4, 4, 64, 64, 12, 12, None) == binding.OK
+    wsb = L.tfno_fno2d_real_workspace_bytes
+    assert wsb(2, 3, 5, 64, 128, 12, 20) == 8 * 2 * 32 * 32 * (3 + 5)               # blocks of 24 x 20 run as 32 x 32
+    assert wsb(2, 3, 5, 64, 128, 8, 16) == 8 * 2 * 16 * 16 * (3 + 5)
+    assert wsb(2, 3, 5, 512, 128, 8, 16) == 0
+    assert wsb(2, 3, 5, 64, 128, 40, 16) == 0
+
+
 def test_fused_entry_points_report_unsupported_shapes(L):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, "tfno_spectral_conv1d_permode", x, W, y, 2, 4, 4, 512, 64) == binding.ERR_UNSUPPORTED

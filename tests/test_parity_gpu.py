@@ -496,6 +496,31 @@ def test_long_pencils_any_mode_count(gpu, oracle_mod):
             check(run_gpu(gpu, fn, x, W, K), want, fn)
 
 
+# the 2-D FNO layer on real fields (B, C_in, C_out, N1, N2, M1, M2): block sizes that are built sizes and others,
+# every row length, M1 at its maximum
+FNO_2D = [(2, 3, 5, 64, 64, 12, 12), (2, 4, 4, 64, 64, 8, 16), (1, 5, 9, 128, 128, 16, 16), (3, 2, 3, 256, 256, 32, 64),
+          (2, 3, 2, 64, 256, 5, 40), (2, 6, 3, 256, 64, 20, 7), (1, 17, 33, 128, 64, 1, 1), (9, 2, 2, 64, 128, 32, 32),
+          (2, 3, 3, 128, 256, 24, 20)]
+
+
+@pytest.mark.parametrize("shape", FNO_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_M%dx%d" % s)
+def test_fno2d_real_layer(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N1, N2, M1, M2 = shape
+    say(f"[case] fno2d_real {shape}")
+    x = np.ascontiguousarray(inputs.make_x(1300 + N1 + M2, B, Ci, (N1, N2)).real)
+    W = np.ascontiguousarray(inputs.make_W(1300 + N1 + M2, Ci, Co * 2 * M1 * M2).reshape(Ci, Co, 2 * M1, M2))
+    want, _ = oracle_mod.fno2d_real(x, W)
+    yd = torch.full((B, Co, N1, N2), float("nan"), dtype=torch.float32, device="cuda")
+    binding.fno2d_real(torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda(), yd)
+    torch.cuda.synchronize()
+    got = yd.cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm((got - want).ravel()) / np.linalg.norm(want.ravel())
+    mx = np.max(np.abs(got - want)) / np.max(np.abs(want))
+    say(f"   fno2d: rel_l2={rel:.3e} max_abs/max|y|={mx:.3e}")
+    assert rel <= REL_L2 and mx <= MAX_ABS
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
