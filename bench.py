@@ -242,6 +242,48 @@ def measure_real(torch, binding, w, steps, warmup, ramp):
     return dev, pair + 8 * w.C_in * w.C_out
 
 
+def measure_fno2d(torch, binding, B, C, N1, N2, M1, M2, steps, warmup, ramp):
+    """Device seconds per layer of the real-field 2-D FNO layer and of the same layer composed from PyTorch library calls
+    (rfft2, two einsum corners, irfft2); inputs of the usual recipe (real parts), weights per mode."""
+    from paper_2504_11681_amd import inputs
+    seed = 9
+    xd = torch.empty((B, C, N1, N2), dtype=torch.float32, device="cuda")
+    for b in range(B):
+        xd[b] = torch.from_numpy(inputs.make_x_element(seed, b, C, (N1, N2)).real.copy()).cuda()
+    Wd = torch.from_numpy(inputs.make_W(seed, C, C * 2 * M1 * M2)).cuda().reshape(C, C, 2 * M1, M2).contiguous()
+    pair = 8 * B * C * N1 * N2
+    nsets = max(2, min(64, -(-(1 << 30) // pair)))
+    sets = [(xd, torch.zeros_like(xd))] + [(xd.clone(), torch.zeros_like(xd)) for _ in range(nsets - 1)]
+    stream = torch.cuda.current_stream().cuda_stream
+    turn = [0]
+
+    def call():
+        xi, yi = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        binding.fno2d_real(xi, Wd, yi, stream)
+
+    _, dev = time_calls(torch, call, steps, warmup, ramp)
+
+    def layer():
+        xi, _ = sets[turn[0] % len(sets)]
+        turn[0] += 1
+        xf = torch.fft.rfft2(xi)
+        out = torch.zeros((B, C, N1, N2 // 2 + 1), dtype=torch.complex64, device="cuda")
+        out[:, :, :M1, :M2] = torch.einsum("bixy,ioxy->boxy", xf[:, :, :M1, :M2], Wd[:, :, M1:, :])
+        out[:, :, -M1:, :M2] = torch.einsum("bixy,ioxy->boxy", xf[:, :, -M1:, :M2], Wd[:, :, :M1, :])
+        return torch.fft.irfft2(out, s=(N1, N2))
+
+    ref = layer()
+    call()
+    torch.cuda.synchronize()
+    got = sets[(turn[0] - 1) % len(sets)][1]
+    err = (torch.linalg.norm(got - ref) / torch.linalg.norm(ref)).item()
+    _, dev_t = time_calls(torch, layer, max(10, steps // 10), 3, ramp)
+    del xd, Wd, sets, ref
+    torch.cuda.empty_cache()
+    return dev, dev_t, err, pair + 8 * C * C * 2 * M1 * M2
+
+
 def pytorch_baseline(w, torch, binding, steps, ramp):
     """The layer as PyTorch composes it from library calls (the structure the paper measures against, Sec. 1 and 5):
     full FFT, slice, complex matmul over channels, zero pad, full inverse FFT -- rocFFT and the BLAS library under
@@ -474,6 +516,16 @@ def main():
                            "effective_hbm_GBps": nb / devp / 1e9, "hbm_frac": nb / devp / 1e9 / HBM_PEAK_GBPS,
                            "contraction_TFLOPs": flops_of(wp) / devp / 1e12})
             out["per_mode_weights"] = pm
+            # the 2-D FNO layer on real fields, next to the same layer composed from PyTorch library calls
+            fno = []
+            for (Bf, Cf, N1, N2, M1, M2) in [(32, 64, 256, 256, 16, 32), (256, 64, 64, 64, 12, 12)]:
+                devf, devt, errf, nbf = measure_fno2d(torch, binding, Bf, Cf, N1, N2, M1, M2, max(50, args.steps // 8),
+                                                     max(10, args.warmup // 8), args.ramp / 3)
+                fno.append({"workload": f"fno2d_real_B{Bf}_C{Cf}_N{N1}x{N2}_M{M1}x{M2}", "us_per_layer": devf * 1e6,
+                            "layers_per_s": 1.0 / devf, "effective_hbm_GBps": nbf / devf / 1e9,
+                            "hbm_frac": nbf / devf / 1e9 / HBM_PEAK_GBPS, "pytorch_us_per_layer": devt * 1e6,
+                            "speedup_vs_pytorch": devt / devf, "rel_l2_vs_pytorch": errf})
+            out["fno2d_real"] = fno
             # real-valued layer (R2C / C2R semantics): half the bytes of the complex layer
             if w.name.startswith("cfg3"):
                 devr, nbr = measure_real(torch, binding, w, max(50, args.steps // 4), max(10, args.warmup // 4), args.ramp / 3)
