@@ -36,7 +36,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         c_int, c_void = ctypes.c_int, ctypes.c_void_p
         for name in ("oracle_spectral_conv1d", "oracle_spectral_conv2d", "oracle_spectral_conv1d_permode",
-                     "oracle_spectral_conv1d_real"):
+                     "oracle_spectral_conv1d_real", "oracle_fno1d_real"):
             fn = getattr(lib, name)
             fn.restype = c_int
             fn.argtypes = [c_void, c_void, c_void] + [c_int] * 6
@@ -147,6 +147,23 @@ def spectral_conv1d_real(x: np.ndarray, W: np.ndarray, K: int, threads: int = 0)
     used = _load().oracle_spectral_conv1d_real(x.ctypes.data, W.ctypes.data, y.ctypes.data, B, C_in, C_out, N, K, threads)
     if used < 0:
         raise ValueError("oracle_spectral_conv1d_real: bad arguments")
+    return y, used
+
+
+def fno1d_real(x: np.ndarray, W: np.ndarray, threads: int = 0):
+    """The 1-D Fourier layer of FNO models on real fields: x[B,C_in,N] float32, W[C_in,C_out,M] complex64 (one matrix
+    per mode 0..M-1 of the half spectrum), y[B,C_out,N] float64."""
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.float32:
+        raise TypeError("x must be float32")
+    W = _c64(W)
+    B, C_in, N = x.shape
+    C_in2, C_out, M = W.shape
+    assert C_in2 == C_in
+    y = np.empty((B, C_out, N), dtype=np.float64)
+    used = _load().oracle_fno1d_real(x.ctypes.data, W.ctypes.data, y.ctypes.data, B, C_in, C_out, N, M, threads)
+    if used < 0:
+        raise ValueError("oracle_fno1d_real: bad arguments")
     return y, used
 
 

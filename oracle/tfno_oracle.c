@@ -197,7 +197,7 @@ int oracle_spectral_conv1d_permode(const float *x, const float *W, double *y,
  * where C2R is the inverse transform of the Hermitian extension: F[0] = Re Yh[0], F[k] = Yh[k] and
  * F[N-k] = conj(Yh[k]) for 0 < k < K, zero elsewhere; y = (1/N) * inverse DFT of F, whose imaginary part
  * vanishes and is dropped. */
-static void conv1d_real_one(const float *x, const float *W, double *y, int C_in, int C_out, int N, int K)
+static void conv1d_real_one(const float *x, const float *W, double *y, int C_in, int C_out, int N, int K, int per_mode)
 {
     cplx *sig = malloc(sizeof(cplx) * N), *spec = malloc(sizeof(cplx) * N), *scr = malloc(sizeof(cplx) * N);
     cplx *Xh = malloc(sizeof(cplx) * (size_t)C_in * K), *Yh = malloc(sizeof(cplx) * (size_t)C_out * K);
@@ -209,7 +209,7 @@ static void conv1d_real_one(const float *x, const float *W, double *y, int C_in,
     for (int o = 0; o < C_out; ++o)
         for (int k = 0; k < K; ++k) {
             cplx acc = 0.0;
-            for (int c = 0; c < C_in; ++c) acc += Xh[(size_t)c * K + k] * weight(W, c, o, C_out, (size_t)k, (size_t)K, 0);
+            for (int c = 0; c < C_in; ++c) acc += Xh[(size_t)c * K + k] * weight(W, c, o, C_out, (size_t)k, (size_t)K, per_mode);
             Yh[(size_t)o * K + k] = acc;
         }
     for (int o = 0; o < C_out; ++o) {
@@ -225,8 +225,8 @@ static void conv1d_real_one(const float *x, const float *W, double *y, int C_in,
     free(sig); free(spec); free(scr); free(Xh); free(Yh);
 }
 
-int oracle_spectral_conv1d_real(const float *x, const float *W, double *y,
-                                int B, int C_in, int C_out, int N, int K, int threads)
+static int conv1d_real_batch(const float *x, const float *W, double *y,
+                             int B, int C_in, int C_out, int N, int K, int threads, int per_mode)
 {
     if (!x || !W || !y || B < 0 || C_in <= 0 || C_out <= 0 || N <= 0 || K <= 0 || 2 * K > N) return -1;
     int used = 1;
@@ -238,14 +238,28 @@ int oracle_spectral_conv1d_real(const float *x, const float *W, double *y,
         used = omp_get_num_threads();
         #pragma omp for schedule(dynamic, 1)
         for (int b = 0; b < B; ++b)
-            conv1d_real_one(x + (size_t)b * C_in * N, W, y + (size_t)b * C_out * N, C_in, C_out, N, K);
+            conv1d_real_one(x + (size_t)b * C_in * N, W, y + (size_t)b * C_out * N, C_in, C_out, N, K, per_mode);
     }
 #else
     (void)threads;
     for (int b = 0; b < B; ++b)
-        conv1d_real_one(x + (size_t)b * C_in * N, W, y + (size_t)b * C_out * N, C_in, C_out, N, K);
+        conv1d_real_one(x + (size_t)b * C_in * N, W, y + (size_t)b * C_out * N, C_in, C_out, N, K, per_mode);
 #endif
     return used;
+}
+
+int oracle_spectral_conv1d_real(const float *x, const float *W, double *y,
+                                int B, int C_in, int C_out, int N, int K, int threads)
+{
+    return conv1d_real_batch(x, W, y, B, C_in, C_out, N, K, threads, 0);
+}
+
+/* The 1-D Fourier layer of FNO models on real fields: as above with an own weight matrix per retained mode,
+ * W [C_in, C_out, M] (M = K modes). */
+int oracle_fno1d_real(const float *x, const float *W, double *y,
+                      int B, int C_in, int C_out, int N, int M, int threads)
+{
+    return conv1d_real_batch(x, W, y, B, C_in, C_out, N, M, threads, 1);
 }
 
 /* Untruncated forward spectra of one [C, N] block (no scaling): Xh[c,k], k < N. */

@@ -381,6 +381,22 @@ def test_real_cosine_closed_form(oracle_mod):
     assert np.max(np.abs(y - 0.75)) < 1e-12
 
 
+@pytest.mark.parametrize("N,M", [(64, 16), (32, 16), (12, 5), (128, 1)])
+def test_fno1d_matches_numpy_rfft_einsum_irfft(oracle_mod, N, M):
+    B, Ci, Co = 2, 3, 4
+    x = rng.standard_normal((B, Ci, N)).astype(np.float32)
+    W = crandn(Ci, Co, M)
+    y, _ = oracle_mod.fno1d_real(x, W)
+    half = np.zeros((B, Co, N // 2 + 1), dtype=np.complex128)
+    half[..., :M] = np.einsum("bix,iox->box", np.fft.rfft(x.astype(np.float64))[..., :M], W.astype(np.complex128))
+    assert np.max(np.abs(np.fft.irfft(half, n=N) - y)) < 1e-12
+    # equal matrices: the shared-weight real layer
+    Ws = crandn(Ci, Co)
+    a, _ = oracle_mod.fno1d_real(x, np.ascontiguousarray(np.repeat(Ws[:, :, None], M, axis=2)))
+    b, _ = oracle_mod.spectral_conv1d_real(x, Ws, M)
+    assert np.array_equal(a, b)
+
+
 # ------------------------------------------------------ FNO 2-D layer on real fields --
 
 @pytest.mark.parametrize("N1,N2,M1,M2", [(16, 16, 4, 4), (32, 16, 6, 8), (8, 64, 4, 12), (64, 32, 1, 1), (12, 20, 3, 5)])
