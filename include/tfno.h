@@ -180,6 +180,17 @@ tfno_status tfno_fno2d_real(const void *x, const void *W, void *y, int B, int C_
 size_t tfno_fno2d_real_workspace_bytes(int B, int C_in, int C_out, int N1, int N2, int M1, int M2);
 
 /*
+ * The 1-D counterpart:  y = irfft( pad( sum_c rfft(x[b,c])[k] * W[c, o, k] ) ),  0 <= k < M,  2 M <= N.
+ * x [B, C_in, N], y [B, C_out, N] float32, W [C_in, C_out, M] c64.  Three launches (pruned forward transform of the
+ * real pencils, per-mode contraction, pruned inverse storing the real part).  Shapes: N in {64, 128, 256} with
+ * M <= N/2, or N = 1024 with M <= 128; others TFNO_ERR_UNSUPPORTED.  Workspace:
+ * tfno_fno1d_real_workspace_bytes(...) bytes.
+ */
+tfno_status tfno_fno1d_real(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int M,
+                            void *stream);
+size_t tfno_fno1d_real_workspace_bytes(int B, int C_in, int C_out, int N, int M);
+
+/*
  * 1-D spectral convolution as three launches with truncation, zero padding and butterfly pruning built into the
  * transforms but no fusion across the contraction (the variant "A" of Table 2, Sec. 5: pruned FFT, CGEMM, pruned
  * iFFT): only the K retained bins of every pencil cross global memory between the launches.  Same contract and

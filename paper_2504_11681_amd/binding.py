@@ -30,6 +30,8 @@ EXPORTS = (
     "tfno_spectral_conv1d_real",
     "tfno_fno2d_real",
     "tfno_fno2d_real_workspace_bytes",
+    "tfno_fno1d_real",
+    "tfno_fno1d_real_workspace_bytes",
     "tfno_workspace_bytes",
     "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
@@ -71,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.tfno_fno2d_real.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
         L.tfno_fno2d_real_workspace_bytes.restype = ctypes.c_size_t
         L.tfno_fno2d_real_workspace_bytes.argtypes = [ci] * 7
+        L.tfno_fno1d_real.restype = ci
+        L.tfno_fno1d_real.argtypes = [vp, vp, vp] + [ci] * 5 + [vp]
+        L.tfno_fno1d_real_workspace_bytes.restype = ctypes.c_size_t
+        L.tfno_fno1d_real_workspace_bytes.argtypes = [ci] * 5
         L.tfno_workspace_bytes.restype = ctypes.c_size_t
         L.tfno_workspace_bytes.argtypes = [ci] * 7
         L.tfno_workspace_bytes_2d.restype = ctypes.c_size_t
@@ -287,4 +293,28 @@ def fno2d_real(x, W, y, stream=None):
     st = lib().tfno_fno2d_real(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N1, N2, M1, M2, stream)
     if st != OK:
         raise TfnoError(st, "tfno_fno2d_real")
+    return y
+
+
+def fno1d_real(x, W, y, stream=None):
+    """The 1-D Fourier layer of FNO models on real fields: x [B, C_in, N], y [B, C_out, N] float32,
+    W [C_in, C_out, M] complex64 (one matrix per mode 0..M-1)."""
+    import torch
+    if x.dtype != torch.float32 or y.dtype != torch.float32 or W.dtype != torch.complex64:
+        raise TypeError("x, y must be float32 and W complex64")
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous device tensor")
+    if x.dim() != 3 or y.dim() != 3 or W.dim() != 3:
+        raise ValueError("x, y must be [B, C, N]; W must be [C_in, C_out, M]")
+    B, C_in, N = x.shape
+    C_out, M = W.shape[1], W.shape[2]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out, N):
+        raise ValueError("inconsistent tensor shapes")
+    ensure_workspace(lib().tfno_fno1d_real_workspace_bytes(B, C_in, C_out, N, M), x.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = lib().tfno_fno1d_real(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, M, stream)
+    if st != OK:
+        raise TfnoError(st, "tfno_fno1d_real")
     return y

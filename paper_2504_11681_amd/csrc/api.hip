@@ -312,6 +312,41 @@ tfno_status run_fno2d(const void *x, const void *W, void *y, int B, int C_in, in
     return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
 }
 
+// The 1-D Fourier layer of FNO models on real fields: x [B, C_in, N], y [B, C_out, N] float32, W [C_in, C_out, M] c64.
+tfno_status run_fno1d(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int M, void *stream,
+                      size_t *ws_bytes)
+{
+    if (ws_bytes) *ws_bytes = 0;
+    if (B < 0 || C_in < 1 || C_out < 1 || !axis_ok(N, M) || 2 * M > N) return TFNO_ERR_SHAPE;
+    const int K = round_modes(N, M, permode_1d);            // the transform kernels' K
+    if (ws_bytes) {                                         // size query only
+        if (K && B > 0) *ws_bytes = pruned1d_workspace_bytes(B, C_in, C_out, K);
+        return K ? TFNO_OK : TFNO_ERR_UNSUPPORTED;
+    }
+    if (B == 0) return TFNO_OK;
+    if (!x || !W || !y) return TFNO_ERR_NULL;
+    if ((long double)B * C_in * N >= 1099511627776.0L || (long double)B * C_out * N >= 1099511627776.0L ||
+        (long double)B * (C_in > C_out ? C_in : C_out) >= 2147483647.0L)
+        return TFNO_ERR_SHAPE;
+    const size_t xb = sizeof(float) * (size_t)B * C_in * N, yb = sizeof(float) * (size_t)B * C_out * N;
+    const size_t wb = sizeof(c64) * (size_t)C_in * C_out * M;
+    if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!K) return TFNO_ERR_UNSUPPORTED;
+    void *wsp = nullptr;
+    tfno_status st = check_workspace(pruned1d_workspace_bytes(B, C_in, C_out, K), x, xb, W, wb, y, yb, &wsp);
+    if (st != TFNO_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    c64 *Xh = (c64 *)wsp, *Yh = Xh + pruned1d_spectrum_elems(B, C_in, K);
+    const long long tiles = ((long long)B * K + 127) / 128;
+    hipError_t e = pruned1d_real_stages(PRUNED_FWD, (const float *)x, (float *)y, Xh, Yh, B, C_in, C_out, N, K, M, s);
+    if (e == hipSuccess)
+        e = cgemm_permode_launch(Xh, (const c64 *)W, Yh, C_in, C_out, K, tiles, K >= 128 ? K / 128 : 1, 2.0f / (float)N, K,
+                                 1, M, s);
+    if (e == hipSuccess)
+        e = pruned1d_real_stages(PRUNED_INV, (const float *)x, (float *)y, Xh, Yh, B, C_in, C_out, N, K, K, s);
+    return e == hipSuccess ? TFNO_OK : TFNO_ERR_HIP;
+}
+
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
 // sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels
 // (C_out <= 128); above that every 128-output slab repeats the forward transform of its batch row, and the
@@ -510,6 +545,18 @@ tfno_status tfno_spectral_conv1d_real(const void *x, const void *W, void *y, int
                                       void *stream)
 {
     return run_real1d(x, W, y, B, C_in, C_out, N, K, stream);
+}
+
+tfno_status tfno_fno1d_real(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int M, void *stream)
+{
+    return run_fno1d(x, W, y, B, C_in, C_out, N, M, stream, nullptr);
+}
+
+size_t tfno_fno1d_real_workspace_bytes(int B, int C_in, int C_out, int N, int M)
+{
+    size_t bytes = 0;
+    run_fno1d(nullptr, nullptr, nullptr, B, C_in, C_out, N, M, nullptr, &bytes);
+    return bytes;
 }
 
 tfno_status tfno_fno2d_real(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1, int N2, int M1,

@@ -20,4 +20,9 @@ size_t pruned1d_spectrum_elems(long long B, int C, int K);
 hipError_t pruned1d_stages(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
                            int C_out, int N, int K, int K_keep, hipStream_t s);
 
+// Real pencils (x, y float32; N <= 1024): PRUNED_FWD writes the R2C bins with bin 0 halved, PRUNED_INV stores the real
+// part of the zero-padded inverse; the contraction between them (not run here) carries the scale 2 / N.
+hipError_t pruned1d_real_stages(int stages, const float *x, float *y, c64 *Xh, c64 *Yh, long long B, int C_in, int C_out,
+                                int N, int K, int K_keep, hipStream_t s);
+
 }  // namespace tfno

@@ -32,7 +32,7 @@ size_t pruned1d_workspace_bytes(long long B, int C_in, int C_out, int K)
 
 size_t pruned1d_spectrum_elems(long long B, int C, int K) { return (size_t)mode_tiles(B, K) * 128 * (size_t)C; }
 
-template <int N, int K>
+template <int N, int K, bool REAL = false>
 static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B, int C_in,
                             int C_out, int K_keep, hipStream_t s)
 {
@@ -44,13 +44,13 @@ static hipError_t launch_nk(int stages, const c64 *x, const c64 *W, c64 *y, c64 
     const unsigned gin = (unsigned)(sin < 1024 ? sin : 1024), gout = (unsigned)(sout < 1024 ? sout : 1024);
     hipError_t e = hipSuccess;
     if (stages & PRUNED_FWD) {
-        hipLaunchKernelGGL((k_fwd1d<N, K>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin, K_keep);
+        hipLaunchKernelGGL((k_fwd1d<N, K, REAL>), dim3(gin), dim3(256), 0, s, x, Xh, C_in, pin, K_keep);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (stages & PRUNED_GEMM)
         if ((e = cgemm_modes_launch(Xh, W, Yh, C_in, C_out, 1.0f / (float)N, tiles, s)) != hipSuccess) return e;
     if (stages & PRUNED_INV) {
-        hipLaunchKernelGGL((k_inv1d<N, K>), dim3(gout), dim3(256), 0, s, (const c64 *)Yh, y, C_out, pout);
+        hipLaunchKernelGGL((k_inv1d<N, K, REAL>), dim3(gout), dim3(256), 0, s, (const c64 *)Yh, y, C_out, pout);
         e = hipGetLastError();
     }
     return e;
@@ -93,17 +93,17 @@ static hipError_t launch_long_n(int K2, int stages, const c64 *x, const c64 *W, 
     }
 }
 
-template <int N>
+template <int N, bool REAL = false>
 static hipError_t launch_n(int K, int stages, const c64 *x, const c64 *W, c64 *y, c64 *Xh, c64 *Yh, long long B,
                            int C_in, int C_out, int K_keep, hipStream_t s)
 {
     constexpr int LPR = N / 16;
     switch (K) {
-    case 16: return launch_nk<N, 16>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
-    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
-    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
-    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
-    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 16: return launch_nk<N, 16, REAL>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 32: if constexpr (LPR >= 2) return launch_nk<N, 32, REAL>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 64: if constexpr (LPR >= 4) return launch_nk<N, 64, REAL>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 128: if constexpr (LPR >= 8) return launch_nk<N, 128, REAL>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
+    case 256: if constexpr (LPR >= 16) return launch_nk<N, 256, REAL>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s); break;
     default: break;
     }
     return hipErrorInvalidValue;
@@ -122,6 +122,24 @@ hipError_t pruned1d_stages(int stages, const c64 *x, const c64 *W, c64 *y, c64 *
         return launch_nk<1024, 128>(stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
     case 2048: return launch_long_n<8>(K / 8, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
     case 4096: return launch_long_n<16>(K / 16, stages, x, W, y, Xh, Yh, B, C_in, C_out, K_keep, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t pruned1d_real_stages(int stages, const float *x, float *y, c64 *Xh, c64 *Yh, long long B, int C_in, int C_out,
+                                int N, int K, int K_keep, hipStream_t s)
+{
+    if (!pruned1d_supported(N, K) || N > 1024 || K_keep < 1 || K_keep > K || (stages & PRUNED_GEMM))
+        return hipErrorInvalidValue;
+    const c64 *xc = reinterpret_cast<const c64 *>(x);
+    c64 *yc = reinterpret_cast<c64 *>(y);
+    switch (N) {
+    case 64: return launch_n<64, true>(K, stages, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 128: return launch_n<128, true>(K, stages, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 256: return launch_n<256, true>(K, stages, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, K_keep, s);
+    case 1024:
+        if (K == 64) return launch_nk<1024, 64, true>(stages, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, K_keep, s);
+        return launch_nk<1024, 128, true>(stages, xc, nullptr, yc, Xh, Yh, B, C_in, C_out, K_keep, s);
     default: return hipErrorInvalidValue;
     }
 }

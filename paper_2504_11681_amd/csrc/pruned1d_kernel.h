@@ -84,7 +84,11 @@ __device__ __forceinline__ int p1_slot(int c, int p)
 
 // ------------------------------------------------------------------------------------------------ forward
 // x: [npencils, N] contiguous (pencil q = b * C + c).  Xh: mode-tile major, joint mode m = b K + k.
-template <int N, int K>
+// REAL (both kernels): pencils of float32 values.  The forward transform of a real pencil is the complex one with a
+// zero imaginary part (its first K bins are the R2C bins); bin 0 is stored halved so that the inverse kernel, which
+// stores the real part of the zero-padded complex inverse, yields the C2R transform when the contraction in between
+// carries the scale 2 / N.
+template <int N, int K, bool REAL = false>
 __global__ void __launch_bounds__(256)
 k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npencils, int K_keep)
 {
@@ -102,9 +106,15 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
     auto load_pencil = [&](long long sweep) __attribute__((always_inline)) {
         long long q = sweep * PPS + g;
         if (q >= npencils) q = npencils - 1;                // a valid address; the result is not stored
-        const c64 *src = x + q * N + p;
+        if constexpr (REAL) {
+            const float *src = reinterpret_cast<const float *>(x) + q * N + p;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = src[LPR * j];
+            for (int j = 0; j < 16; ++j) v[j] = make_float2(src[LPR * j], 0.f);
+        } else {
+            const c64 *src = x + q * N + p;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = src[LPR * j];
+        }
     };
     auto stage = [&](long long sweep, auto refill, long long next_sweep) __attribute__((always_inline)) {
         constexpr bool REFILL = decltype(refill)::value;
@@ -142,8 +152,13 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
                 }, xo);
                 if (ok) {
 #pragma unroll
-                    for (int kh = 0; kh < KH; ++kh)        // bins K_keep .. K-1: truncation finer than the kernel's K
-                        Xh[spec1d_index(b * K + kl + 16 * kh, ch, C)] = kl + 16 * kh < K_keep ? xo[kh] : make_float2(0.f, 0.f);
+                    for (int kh = 0; kh < KH; ++kh) {      // bins K_keep .. K-1: truncation finer than the kernel's K
+                        c64 val = kl + 16 * kh < K_keep ? xo[kh] : make_float2(0.f, 0.f);
+                        if constexpr (REAL) {
+                            if (kl + 16 * kh == 0) val = make_float2(0.5f * val.x, 0.5f * val.y);
+                        }
+                        Xh[spec1d_index(b * K + kl + 16 * kh, ch, C)] = val;
+                    }
                 }
             }
         } else {
@@ -175,8 +190,14 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
             if (ok) {
 #pragma unroll
                 for (int i = 0; i < OPL; ++i)
-                    Xh[spec1d_index(b * K + kl_w + 16 * (OPL * qa + i), ch, C)] =
-                        kl_w + 16 * (OPL * qa + i) < K_keep ? O[i] : make_float2(0.f, 0.f);
+                {
+                    const int k = kl_w + 16 * (OPL * qa + i);
+                    c64 val = k < K_keep ? O[i] : make_float2(0.f, 0.f);
+                    if constexpr (REAL) {
+                        if (k == 0) val = make_float2(0.5f * val.x, 0.5f * val.y);
+                    }
+                    Xh[spec1d_index(b * K + k, ch, C)] = val;
+                }
             }
         }
     };
@@ -191,7 +212,7 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
 
 // ------------------------------------------------------------------------------------------------ inverse
 // Yh: mode-tile major (joint mode m = b K + k, C channels).  y: [npencils, N] contiguous (pencil q = b * C + o).
-template <int N, int K>
+template <int N, int K, bool REAL = false>
 __global__ void __launch_bounds__(256)
 k_inv1d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C, long long npencils)
 {
@@ -264,9 +285,15 @@ k_inv1d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C, long long npenci
         RegFFT<16, +1, 1>::run(z, res);
         const long long q = sweep * PPS + g;
         if (q < npencils) {
-            c64 *dst = y + q * N + p;
+            if constexpr (REAL) {
+                float *dst = reinterpret_cast<float *>(y) + q * N + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) store_nt(dst + LPR * j, res[j]);
+                for (int j = 0; j < 16; ++j) dst[LPR * j] = res[j].x;
+            } else {
+                c64 *dst = y + q * N + p;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) store_nt(dst + LPR * j, res[j]);
+            }
         }
     };
 

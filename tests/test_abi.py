@@ -135,6 +135,21 @@ def test_fno2d_argument_checks_and_workspace(L):
     assert wsb(2, 3, 5, 64, 128, 40, 16) == 0
 
 
+def test_fno1d_argument_checks_and_workspace(L):
+    x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
+    f = L.tfno_fno1d_real
+    assert L.tfno_set_workspace(None, 0) == binding.OK
+    assert f(None, W, y, 2, 4, 4, 64, 12, None) == binding.ERR_NULL
+    assert f(x, W, y, 2, 4, 4, 64, 33, None) == binding.ERR_SHAPE            # 2 M <= N
+    assert f(x, W, y, 2, 4, 4, 512, 16, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, y, 2, 4, 4, 1024, 200, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, x, 2, 4, 4, 64, 12, None) == binding.ERR_ALIAS
+    assert f(x, W, y, 2, 4, 4, 64, 12, None) == binding.ERR_WORKSPACE
+    assert f(None, None, None, 0, 4, 4, 64, 12, None) == binding.OK
+    assert L.tfno_fno1d_real_workspace_bytes(4, 16, 16, 64, 12) == binding.workspace_bytes(1, 2, 4, 16, 16, 64, 16)
+    assert L.tfno_fno1d_real_workspace_bytes(4, 16, 16, 512, 12) == 0
+
+
 def test_fused_entry_points_report_unsupported_shapes(L):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, "tfno_spectral_conv1d_permode", x, W, y, 2, 4, 4, 512, 64) == binding.ERR_UNSUPPORTED

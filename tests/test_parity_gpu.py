@@ -521,6 +521,29 @@ def test_fno2d_real_layer(gpu, oracle_mod, shape):
     assert rel <= REL_L2 and mx <= MAX_ABS
 
 
+# the 1-D FNO layer on real fields (B, C_in, C_out, N, M)
+FNO_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 12), (9, 33, 40, 128, 20), (17, 6, 18, 256, 128), (2, 20, 30, 1024, 64),
+          (11, 13, 17, 1024, 100), (2, 3, 3, 128, 1), (8, 3, 2, 256, 33)]
+
+
+@pytest.mark.parametrize("shape", FNO_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_M%d" % s)
+def test_fno1d_real_layer(gpu, oracle_mod, shape):
+    torch, binding = gpu
+    B, Ci, Co, N, M = shape
+    say(f"[case] fno1d_real {shape}")
+    x = np.ascontiguousarray(inputs.make_x(1400 + N + M, B, Ci, (N,)).real)
+    W = np.ascontiguousarray(inputs.make_W(1400 + N + M, Ci, Co * M).reshape(Ci, Co, M))
+    want, _ = oracle_mod.fno1d_real(x, W)
+    yd = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+    binding.fno1d_real(torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda(), yd)
+    torch.cuda.synchronize()
+    got = yd.cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm((got - want).ravel()) / np.linalg.norm(want.ravel())
+    mx = np.max(np.abs(got - want)) / np.max(np.abs(want))
+    say(f"   fno1d: rel_l2={rel:.3e} max_abs/max|y|={mx:.3e}")
+    assert rel <= REL_L2 and mx <= MAX_ABS
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
