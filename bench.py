@@ -526,6 +526,30 @@ def main():
                             "hbm_frac": nbf / devf / 1e9 / HBM_PEAK_GBPS, "pytorch_us_per_layer": devt * 1e6,
                             "speedup_vs_pytorch": devt / devf, "rel_l2_vs_pytorch": errf})
             out["fno2d_real"] = fno
+            # the 1-D FNO layer on real fields (pruned transforms around the per-mode contraction), cfg3's shape
+            if w.name.startswith("cfg3"):
+                xr = torch.randn((w.B, w.C_in, w.N), device="cuda", dtype=torch.float32)
+                Wm = torch.view_as_complex(torch.randn((w.C_in, w.C_out, w.K, 2), device="cuda", dtype=torch.float32)) / (w.C_in ** 0.5)
+                yr = torch.zeros((w.B, w.C_out, w.N), device="cuda", dtype=torch.float32)
+                strm = torch.cuda.current_stream().cuda_stream
+                _, dev1 = time_calls(torch, lambda: binding.fno1d_real(xr, Wm, yr, strm), max(50, args.steps // 8),
+                                     max(10, args.warmup // 8), args.ramp / 3)
+
+                def torch_layer():
+                    half = torch.zeros((w.B, w.C_out, w.N // 2 + 1), dtype=torch.complex64, device="cuda")
+                    half[..., :w.K] = torch.einsum("bix,iox->box", torch.fft.rfft(xr)[..., :w.K], Wm)
+                    return torch.fft.irfft(half, n=w.N)
+
+                ref1 = torch_layer()
+                err1 = (torch.linalg.norm(yr - ref1) / torch.linalg.norm(ref1)).item()
+                _, devt1 = time_calls(torch, torch_layer, 20, 3, args.ramp / 3)
+                nb1 = 4 * w.B * w.N * (w.C_in + w.C_out) + 8 * w.C_in * w.C_out * w.K
+                out["fno1d_real"] = [{"workload": f"fno1d_real_B{w.B}_C{w.C_in}_N{w.N}_M{w.K}", "us_per_layer": dev1 * 1e6,
+                                      "layers_per_s": 1.0 / dev1, "effective_hbm_GBps": nb1 / dev1 / 1e9,
+                                      "hbm_frac": nb1 / dev1 / 1e9 / HBM_PEAK_GBPS, "pytorch_us_per_layer": devt1 * 1e6,
+                                      "speedup_vs_pytorch": devt1 / dev1, "rel_l2_vs_pytorch": err1}]
+                del xr, Wm, yr, ref1
+                torch.cuda.empty_cache()
             # real-valued layer (R2C / C2R semantics): half the bytes of the complex layer
             if w.name.startswith("cfg3"):
                 devr, nbr = measure_real(torch, binding, w, max(50, args.steps // 4), max(10, args.warmup // 4), args.ramp / 3)
