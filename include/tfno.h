@@ -30,7 +30,8 @@
  *  - Argument errors are detected on the host before anything is launched, so a
  *    failed call has no effect on y.  B == 0 is a valid empty call (TFNO_OK,
  *    nothing launched, pointers may be NULL).
- *  - N must be a power of two, 2 <= N <= 4096; 1 <= K <= N; C_in, C_out >= 1.
+ *  - N must be a power of two, 2 <= N <= 4096; 1 <= K <= N; C_in, C_out >= 1.  The staged entry points (and
+ *    tfno_spectral_conv1d_auto, which falls back to them) also take any other 2 <= N <= 4096.
  *  - Mode counts: the kernels are built for the power-of-two K that each entry point lists.  Every other K, down
  *    to 1, runs on the next built size K' >= K: the forward transform zeroes bins K .. K'-1 before the contraction,
  *    which is exactly the truncation to K (Sec. 3.3), so e.g. K = 12, 20 or 48 are served by the fused kernels; a

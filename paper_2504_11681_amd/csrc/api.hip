@@ -35,18 +35,20 @@ struct Shape {
 Shape shape1d(int N, int K) { return Shape{1, 1, N, 1, K}; }
 Shape shape2d(int N1, int N2, int K1, int K2) { return Shape{2, N1, N2, K1, K2}; }
 
-bool axis_ok(int N, int K) { return N >= 2 && N <= 4096 && is_pow2(N) && K >= 1 && K <= N; }
-bool sizes_ok(const Shape &sh, int B, int C_in, int C_out)
+// any_n: the staged pipeline also takes lengths that are not powers of two
+bool axis_ok(int N, int K, bool any_n = false) { return N >= 2 && N <= 4096 && (any_n || is_pow2(N)) && K >= 1 && K <= N; }
+bool sizes_ok(const Shape &sh, int B, int C_in, int C_out, bool any_n = false)
 {
-    return B >= 0 && C_in >= 1 && C_out >= 1 && axis_ok(sh.N2, sh.K2) && (sh.dims == 1 || axis_ok(sh.N1, sh.K1));
+    return B >= 0 && C_in >= 1 && C_out >= 1 && axis_ok(sh.N2, sh.K2, any_n) &&
+           (sh.dims == 1 || axis_ok(sh.N1, sh.K1, any_n));
 }
 
 // Everything that can be decided on the host.  *empty is set for a valid call with nothing to do.
 tfno_status validate(const Shape &sh, const void *x, const void *W, const void *y, int B, int C_in, int C_out,
-                     bool *empty, bool per_mode = false)
+                     bool *empty, bool per_mode = false, bool any_n = false)
 {
     *empty = false;
-    if (!sizes_ok(sh, B, C_in, C_out)) return TFNO_ERR_SHAPE;
+    if (!sizes_ok(sh, B, C_in, C_out, any_n)) return TFNO_ERR_SHAPE;
     if (B == 0) { *empty = true; return TFNO_OK; }
     if (!x || !W || !y) return TFNO_ERR_NULL;
     const size_t pts = sh.pts();
@@ -129,7 +131,7 @@ tfno_status run(const Shape &req, Variant variant, const void *x, const void *W,
 {
     const bool staged = variant == STAGED;
     bool empty;
-    tfno_status st = validate(req, x, W, y, B, C_in, C_out, &empty);
+    tfno_status st = validate(req, x, W, y, B, C_in, C_out, &empty, false, staged);
     if (st != TFNO_OK || empty) return st;
     Shape sh;                                               // the kernels' shape: req with K rounded up to a built size
     if (!kernel_shape(req, (int)variant, &sh)) return TFNO_ERR_UNSUPPORTED;
@@ -458,11 +460,11 @@ namespace {
 
 size_t workspace_for(const Shape &req, int variant, int B, int C_in, int C_out)
 {
-    if (B < 1 || !sizes_ok(req, B, C_in, C_out)) return 0;
     if (variant == 5) {
         if (req.dims != 1) return 0;
         variant = (int)choose_variant(req.N2, req.K2, C_out);
     }
+    if (B < 1 || !sizes_ok(req, B, C_in, C_out, variant == 1)) return 0;
     if (variant < 0 || variant > 6 || variant == 5 || (variant >= 2 && variant <= 4 && req.dims != 1)) return 0;
     Shape sh;                                               // the kernels' shape (K rounded up to a built size)
     if (!kernel_shape(req, variant, &sh)) return 0;

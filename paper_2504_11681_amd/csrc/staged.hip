@@ -1,7 +1,8 @@
 // Unfused baseline: the five-stage structure the paper attributes to the PyTorch Fourier
 // layer (Sec. 1 and Sec. 2.1: FFT, frequency filter copy, CGEMM, zero-pad copy, iFFT as separate
-// kernels with every intermediate in global memory).  Simple, general kernels (any power-of-two
-// N up to 4096, any K, any channel count); they are the reference point for the fused/staged ratio.
+// kernels with every intermediate in global memory).  Simple, general kernels (any N up to 4096 --
+// a radix-2 transform for powers of two, a direct sum otherwise --, any K, any channel count); they
+// are the reference point for the fused/staged ratio.
 #include "common.h"
 #include "staged.h"
 
@@ -96,6 +97,44 @@ k_staged_fft(const c64 *__restrict__ in, c64 *__restrict__ out, int N, int log2N
     }
 }
 
+// The same transform for lengths that are not powers of two, as the direct sum
+//   out[k] = scale * sum_{n < n_in} in[n] exp(DIR 2 pi i k n / N),   k < n_out
+// (n_in * n_out complex multiply-adds per pencil; addressing, zero padding, truncation and aliasing rules as above).
+template <int DIR>
+__global__ void __launch_bounds__(256)
+k_staged_dft(const c64 *__restrict__ in, c64 *__restrict__ out, int N, int PC, long long num_pencils,
+             long long inner_count, long long in_outer_stride, long long out_outer_stride, long long elem_stride,
+             int n_in, int n_out, float scale)
+{
+    extern __shared__ float2 lds[];
+    c64 *buf = lds;                   // [PC][N]
+    c64 *tw = lds + (size_t)PC * N;   // [N] : exp(DIR * 2 pi i m / N)
+    const int tid = threadIdx.x, nth = blockDim.x;
+    const long long q0 = (long long)blockIdx.x * PC;
+    for (int m = tid; m < N; m += nth) tw[m] = cis2pi((float)(DIR * m), (float)N);
+    // consecutive threads take consecutive addresses: along the pencil when it is contiguous, across pencils otherwise
+    const bool along = elem_stride == 1;
+    for (int i = tid; i < PC * n_in; i += nth) {
+        const int n = along ? i % n_in : i / PC, j = along ? i / n_in : i % PC;
+        const long long q = q0 + j;
+        if (q < num_pencils) buf[j * N + n] = in[(q / inner_count) * in_outer_stride + (q % inner_count) + n * elem_stride];
+    }
+    __syncthreads();
+    for (int i = tid; i < PC * n_out; i += nth) {
+        const int k = along ? i % n_out : i / PC, j = along ? i / n_out : i % PC;
+        const long long q = q0 + j;
+        if (q >= num_pencils) continue;
+        c64 acc = make_float2(0.f, 0.f);
+        int idx = 0;                  // (k n) mod N
+        for (int n = 0; n < n_in; ++n) {
+            acc = cmac(acc, buf[j * N + n], tw[idx]);
+            idx += k;
+            if (idx >= N) idx -= N;
+        }
+        out[(q / inner_count) * out_outer_stride + (q % inner_count) + k * elem_stride] = make_float2(acc.x * scale, acc.y * scale);
+    }
+}
+
 // Frequency filter: keep rows [0,Kr) x cols [0,Kc) of every [R, Cc] image.   out: [imgs, Kr, Kc]
 __global__ void __launch_bounds__(256)
 k_staged_truncate(const c64 *__restrict__ in, c64 *__restrict__ out, long long imgs, int R, int Cc, int Kr, int Kc)
@@ -166,6 +205,27 @@ hipError_t launch_axis_fft(int dir, const c64 *in, c64 *out, int N, long long nu
     if (num_pencils == 0) return hipSuccess;
     int PC = 4096 / N; if (PC > 16) PC = 16; if (PC < 1) PC = 1;
     if (inner_count > 1) { while (PC > 1 && inner_count % PC) PC >>= 1; }
+    if ((N & (N - 1)) != 0) {                               // not a power of two: direct sum
+        static bool dft_attr_done = false;
+        if (!dft_attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_staged_dft<-1>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_staged_dft<+1>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            if (e != hipSuccess) return e;
+            dft_attr_done = true;
+        }
+        const size_t dlds = ((size_t)PC * N + N) * sizeof(c64);
+        const long long dblocks = (num_pencils + PC - 1) / PC;
+        if (dir < 0)
+            hipLaunchKernelGGL(k_staged_dft<-1>, dim3((unsigned)dblocks), dim3(256), dlds, s, in, out, N, PC, num_pencils,
+                               inner_count, in_outer_stride, out_outer_stride, elem_stride, n_in, n_out, scale);
+        else
+            hipLaunchKernelGGL(k_staged_dft<+1>, dim3((unsigned)dblocks), dim3(256), dlds, s, in, out, N, PC, num_pencils,
+                               inner_count, in_outer_stride, out_outer_stride, elem_stride, n_in, n_out, scale);
+        return hipGetLastError();
+    }
     size_t lds = ((size_t)2 * PC * N + N / 2) * sizeof(c64);
     long long blocks = (num_pencils + PC - 1) / PC;
     int threads = 256;

@@ -182,7 +182,10 @@ def test_1d_pruned_unsupported_shapes(gpu):
 
 
 STAGED_ONLY_1D = [(2, 3, 4, 2, 1), (2, 3, 4, 4, 3), (3, 6, 5, 32, 5), (2, 4, 4, 2048, 100), (1, 2, 3, 4096, 4096),
-                  (2, 5, 3, 256, 48)]
+                  (2, 5, 3, 256, 48),
+                  # lengths that are not powers of two (direct-sum transform)
+                  (2, 3, 4, 3, 2), (3, 5, 4, 48, 12), (2, 4, 6, 421, 24), (1, 3, 2, 1000, 1000), (2, 2, 2, 85, 85),
+                  (1, 2, 2, 4095, 7)]
 
 
 @pytest.mark.parametrize("shape", STAGED_ONLY_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
@@ -210,6 +213,20 @@ def test_2d_small(gpu, oracle_mod, fn, shape):
     W = inputs.make_W(200 + N + K, Ci, Co)
     want, _ = oracle_mod.spectral_conv2d(x, W, K)
     check(run_gpu(gpu, fn, x, W, K), want, fn)
+
+
+def test_staged_lengths_that_are_not_powers_of_two(gpu, oracle_mod):
+    """2-D staged twin on 85 x 48 and 421 x 12 grids, and the 1-D per-shape dispatch falling back to the staged path."""
+    for (B, Ci, Co, N1, N2, K1, K2) in [(2, 3, 2, 85, 48, 12, 12), (1, 2, 3, 12, 421, 5, 20), (1, 2, 2, 64, 100, 16, 30)]:
+        say(f"[case] staged rect {(B, Ci, Co, N1, N2, K1, K2)}")
+        x = inputs.make_x(1500 + N1 + N2, B, Ci, (N1, N2))
+        W = inputs.make_W(1500 + N1 + N2, Ci, Co)
+        want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+        check(run_gpu_rect(gpu, "spectral_conv2d_rect_staged", x, W, K1, K2), want, "staged rect, any N")
+    x = inputs.make_x(1501, 2, 3, (300,))
+    W = inputs.make_W(1501, 3, 4)
+    want, _ = oracle_mod.spectral_conv1d(x, W, 40)
+    check(run_gpu(gpu, "spectral_conv1d_auto", x, W, 40), want, "auto, N = 300")
 
 
 def test_2d_staged_general_shape(gpu, oracle_mod):
