@@ -65,9 +65,10 @@ typedef enum {
  *   y[b,o,:] = iFFT_N( pad_N( sum_c trunc_K( FFT_N(x[b,c,:]) ) * W[c,o] ) )
  *
  * One kernel launch; the spectra never leave the chip.  Needs no workspace.
- * Supported by the fused kernel: N in {64,128,256,512,1024}, K a multiple of 16
- * that divides N (K = N allowed).  Other valid shapes: TFNO_ERR_UNSUPPORTED
- * (use the staged entry point).
+ * Built sizes of the fused kernel: K a power of two, 8..64 for N = 64, 16..128 for N = 128, 16..256 for N = 256,
+ * 32..256 for N = 512 and N = 1024 (K = N allowed where listed); every smaller K runs on the next built size (see
+ * "Mode counts" above).  Other valid shapes: TFNO_ERR_UNSUPPORTED (use the staged entry point or
+ * tfno_spectral_conv1d_auto).
  */
 tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y,
                                  int B, int C_in, int C_out, int N, int K, void *stream);
@@ -78,7 +79,7 @@ tfno_status tfno_spectral_conv1d(const void *x, const void *W, void *y,
  *
  *   y[b,o] = iFFT2( pad_NxN( sum_c trunc_KxK( FFT2(x[b,c]) ) * W[c,o] ) )
  *
- * N in {64,128,256}, K in {16,32,64}, K <= N: three launches -- a per-image truncated forward transform, the
+ * N in {64,128,256}, K <= 64 (built sizes 16, 32, 64): three launches -- a per-image truncated forward transform, the
  * CGEMM over the K*K retained modes, a per-image zero-padded inverse -- whose only intermediates are the
  * truncated spectra (tfno_workspace_bytes(2, 0, ...) = 8 B K^2 (C_in + C_out) bytes of workspace).
  * Other shapes that the 1-D fused kernel supports run the paper's 2-D pipeline instead: truncated forward
@@ -135,8 +136,9 @@ tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void 
  * (2-D), modes innermost; x, y, stream, aliasing and error rules as for the other entry points.  Three launches:
  * pruned forward transform with built-in truncation, per-mode contraction on the truncated spectra, pruned inverse
  * with built-in zero padding (the transform kernels of tfno_spectral_conv1d_pruned and tfno_spectral_conv2d_rect).
- * Shapes: 1-D those of tfno_spectral_conv1d_pruned with N <= 1024; 2-D N1, N2 in {64,128,256}, K1, K2 in
- * {16,32,64}; others TFNO_ERR_UNSUPPORTED.  Workspace: tfno_workspace_bytes(1, 6, ...) and
+ * Shapes: 1-D those of tfno_spectral_conv1d_pruned with N <= 1024; 2-D N1, N2 in {64,128,256}, K1, K2 <= 64
+ * (W holds exactly the K, or K1 x K2, matrices of the modes kept, whatever built size the transforms run);
+ * others TFNO_ERR_UNSUPPORTED.  Workspace: tfno_workspace_bytes(1, 6, ...) and
  * tfno_workspace_bytes_2d(6, ...) bytes.
  */
 tfno_status tfno_spectral_conv1d_permode(const void *x, const void *W, void *y,
@@ -154,8 +156,8 @@ tfno_status tfno_spectral_conv2d_permode(const void *x, const void *W, void *y, 
  * K <= N/2.  One launch of the fully fused kernel: the pencils are read as 4-byte reals, bin 0 enters the
  * contraction with weight 1/2 and the epilogue stores 2/N times the real part of the zero-padded inverse -- the
  * C2R transform of the Hermitian extension -- so the layer moves half the bytes of the complex one.  Shapes: N in
- * {64,128,256,512,1024}, K a power of two with K <= N/2 and K >= 8 (N = 64), 16 (N = 128, 256), 32 (N = 512,
- * 1024); others TFNO_ERR_UNSUPPORTED.  Needs no workspace.  Pointer, aliasing, stream and error rules as above.
+ * {64,128,256,512,1024}, K <= N/2 (built sizes: powers of two from 8 (N = 64), 16 (N = 128, 256), 32 (N = 512,
+ * 1024); K <= 256); others TFNO_ERR_UNSUPPORTED.  Needs no workspace.  Pointer, aliasing, stream and error rules as above.
  */
 tfno_status tfno_spectral_conv1d_real(const void *x, const void *W, void *y,
                                       int B, int C_in, int C_out, int N, int K, void *stream);
