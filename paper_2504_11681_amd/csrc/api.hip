@@ -386,7 +386,7 @@ bool fused1d_real_supported(int N, int K)
     switch (N) {
     case 64: return K >= 8;
     case 128: case 256: return K >= 16;
-    case 512: case 1024: return K >= 32;
+    case 512: case 1024: return K >= 32 && K <= 256;
     default: return false;
     }
 }

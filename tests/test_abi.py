@@ -114,6 +114,8 @@ def test_real_layer_argument_checks(L):
     assert f(x, W, y, 2, 4, 4, 48, 16, None) == binding.ERR_SHAPE
     assert f(x, W, y, 2, 4, 4, 2048, 128, None) == binding.ERR_UNSUPPORTED
     assert f(x, W, y, 2, 4, 4, 32, 8, None) == binding.ERR_UNSUPPORTED
+    assert f(x, W, y, 2, 4, 4, 1024, 300, None) == binding.ERR_UNSUPPORTED         # built sizes end at 256
+    assert f(x, W, y, 2, 4, 4, 1024, 512, None) == binding.ERR_UNSUPPORTED
     # float tensors: y right behind x (4 B per element) does not overlap, y inside x does
     assert f(x, W, x + 4 * 2 * 4 * 64 - 4, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
     assert f(x, W, W, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
