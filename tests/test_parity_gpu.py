@@ -561,6 +561,114 @@ def test_fno1d_real_layer(gpu, oracle_mod, shape):
     assert rel <= REL_L2 and mx <= MAX_ABS
 
 
+def test_every_1d_shape_either_runs_or_is_reported_unsupported(gpu, oracle_mod):
+    """Sweeps N and K over their whole range for every 1-D entry point: a call must end in TFNO_OK or
+    TFNO_ERR_UNSUPPORTED (never a launch error from a shape the dispatch accepted but no kernel was built for), and
+    what runs must match the oracle."""
+    torch, binding = gpu
+    B, Ci, Co = 2, 3, 2
+    ran = 0
+    for e in range(1, 13):
+        N = 1 << e
+        x = inputs.make_x(1600 + e, B, Ci, (N,))
+        xd = torch.from_numpy(x).cuda()
+        xr = np.ascontiguousarray(x.real)
+        xrd = torch.from_numpy(xr).cuda()
+        W = inputs.make_W(1600 + e, Ci, Co)
+        Wd = torch.from_numpy(W).cuda()
+        ks = sorted({k for k in (1, 2, 3, 5, 8, 12, 16, 24, 32, 48, 64, 100, 128, 200, 256, 300, 512, 1000, 1024, 2048, 4096,
+                                 N // 2, N) if 1 <= k <= N})
+        for K in ks:
+            want = None
+            for fn in ("spectral_conv1d", "spectral_conv1d_pruned", "spectral_conv1d_fft_gemm", "spectral_conv1d_gemm_ifft",
+                       "spectral_conv1d_auto"):
+                yd = torch.full((B, Co, N), float("nan"), dtype=torch.complex64, device="cuda")
+                try:
+                    getattr(binding, fn)(xd, Wd, yd, K)
+                except binding.TfnoError as err:
+                    assert err.status == binding.ERR_UNSUPPORTED, (fn, N, K, err.status)
+                    assert fn != "spectral_conv1d_auto", (N, K)
+                    continue
+                torch.cuda.synchronize()
+                if want is None:
+                    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+                got = yd.cpu().numpy().astype(np.complex128)
+                assert np.linalg.norm((got - want).ravel()) <= REL_L2 * np.linalg.norm(want.ravel()), (fn, N, K)
+                ran += 1
+            if 2 * K <= N:
+                Wm = np.ascontiguousarray(np.repeat(W[:, :, None], K, axis=2))
+                Wmd = torch.from_numpy(Wm).cuda()
+                wantr = None
+                for fn, args in (("spectral_conv1d_real", (xrd, Wd)), ("fno1d_real", (xrd, Wmd))):
+                    yd = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+                    try:
+                        if fn == "fno1d_real":
+                            binding.fno1d_real(*args, yd)
+                        else:
+                            binding.spectral_conv1d_real(*args, yd, K)
+                    except binding.TfnoError as err:
+                        assert err.status == binding.ERR_UNSUPPORTED, (fn, N, K, err.status)
+                        continue
+                    torch.cuda.synchronize()
+                    if wantr is None:
+                        wantr, _ = oracle_mod.spectral_conv1d_real(xr, W, K)     # equal matrices: the same operator
+                    got = yd.cpu().numpy().astype(np.float64)
+                    assert np.linalg.norm((got - wantr).ravel()) <= REL_L2 * np.linalg.norm(wantr.ravel()), (fn, N, K)
+                    ran += 1
+    say(f"   {ran} (entry point, N, K) combinations ran and matched the oracle")
+    assert ran > 400
+
+
+def test_every_2d_shape_either_runs_or_is_reported_unsupported(gpu, oracle_mod):
+    """The same sweep for the 2-D entry points over N1, N2 in {32 .. 512} and mode counts from 1 to N/2."""
+    torch, binding = gpu
+    B, Ci, Co = 1, 2, 2
+    ran = 0
+    for N1 in (32, 64, 128, 256, 512):
+        for N2 in (32, 64, 128, 256, 512):
+            x = inputs.make_x(1700 + N1 + 3 * N2, B, Ci, (N1, N2))
+            xd = torch.from_numpy(x).cuda()
+            xr = np.ascontiguousarray(x.real)
+            xrd = torch.from_numpy(xr).cuda()
+            W = inputs.make_W(1700 + N1, Ci, Co)
+            Wd = torch.from_numpy(W).cuda()
+            for (K1, K2) in sorted({(1, 1), (5, 12), (16, 16), (24, 40), (64, 64), (N1 // 2, N2 // 2), (12, N2 // 2)}):
+                if K1 > N1 or K2 > N2:
+                    continue
+                want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+                Wm = np.broadcast_to(W[:, :, None, None], (Ci, Co, K1, K2)).copy()
+                for fn, args in (("spectral_conv2d_rect", (xd, Wd)), ("spectral_conv2d_permode", (xd, torch.from_numpy(Wm).cuda()))):
+                    yd = torch.full((B, Co, N1, N2), float("nan"), dtype=torch.complex64, device="cuda")
+                    try:
+                        if fn == "spectral_conv2d_rect":
+                            binding.spectral_conv2d_rect(*args, yd, K1, K2)
+                        else:
+                            binding.spectral_conv2d_permode(*args, yd)
+                    except binding.TfnoError as err:
+                        assert err.status == binding.ERR_UNSUPPORTED, (fn, N1, N2, K1, K2, err.status)
+                        continue
+                    torch.cuda.synchronize()
+                    got = yd.cpu().numpy().astype(np.complex128)
+                    assert np.linalg.norm((got - want).ravel()) <= REL_L2 * np.linalg.norm(want.ravel()), (fn, N1, N2, K1, K2)
+                    ran += 1
+                M1 = K1 // 2
+                if M1 >= 1 and 2 * K2 <= N2:
+                    Wf = np.ascontiguousarray(inputs.make_W(1700 + K1 + K2, Ci, Co * 2 * M1 * K2).reshape(Ci, Co, 2 * M1, K2))
+                    yd = torch.full((B, Co, N1, N2), float("nan"), dtype=torch.float32, device="cuda")
+                    try:
+                        binding.fno2d_real(xrd, torch.from_numpy(Wf).cuda(), yd)
+                    except binding.TfnoError as err:
+                        assert err.status == binding.ERR_UNSUPPORTED, ("fno2d_real", N1, N2, M1, K2, err.status)
+                        continue
+                    torch.cuda.synchronize()
+                    wantf, _ = oracle_mod.fno2d_real(xr, Wf)
+                    got = yd.cpu().numpy().astype(np.float64)
+                    assert np.linalg.norm((got - wantf).ravel()) <= REL_L2 * np.linalg.norm(wantf.ravel()), ("fno2d", N1, N2, M1, K2)
+                    ran += 1
+    say(f"   {ran} (entry point, N1, N2, K1, K2) combinations ran and matched the oracle")
+    assert ran > 150
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
