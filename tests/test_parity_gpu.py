@@ -669,6 +669,44 @@ def test_every_2d_shape_either_runs_or_is_reported_unsupported(gpu, oracle_mod):
     assert ran > 150
 
 
+def test_channel_count_sweep(gpu, oracle_mod):
+    """Ragged and boundary channel counts (around every tile size of the kernels) on the main entry points."""
+    torch, binding = gpu
+    vals = [1, 2, 3, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 127, 128, 129, 160, 255, 256, 257]
+    rs = np.random.default_rng(77)
+    pairs = [(int(rs.choice(vals)), int(rs.choice(vals))) for _ in range(20)] + [(1, 257), (257, 1), (129, 129)]
+    for idx, (Ci, Co) in enumerate(pairs):
+        N, K, B = (256, 64, 2) if idx % 3 else (1024, 128, 1)
+        x = inputs.make_x(1800 + idx, B, Ci, (N,))
+        W = inputs.make_W(1800 + idx, Ci, Co)
+        want, _ = oracle_mod.spectral_conv1d(x, W, K)
+        fns = ["spectral_conv1d", "spectral_conv1d_pruned", "spectral_conv1d_auto"]
+        if N == 256:
+            fns += ["spectral_conv1d_fft_gemm", "spectral_conv1d_gemm_ifft"]
+        for fn in fns:
+            got = run_gpu(gpu, fn, x, W, K).astype(np.complex128)
+            assert np.linalg.norm((got - want).ravel()) <= REL_L2 * np.linalg.norm(want.ravel()), (fn, Ci, Co, N)
+        xr = np.ascontiguousarray(x.real)
+        wantr, _ = oracle_mod.spectral_conv1d_real(xr, W, K)
+        yd = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+        binding.spectral_conv1d_real(torch.from_numpy(xr).cuda(), torch.from_numpy(W).cuda(), yd, K)
+        torch.cuda.synchronize()
+        got = yd.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm((got - wantr).ravel()) <= REL_L2 * np.linalg.norm(wantr.ravel()), ("real", Ci, Co, N)
+        # 2-D image kernels, mode CGEMM and per-mode contraction with the same channel counts
+        x2 = inputs.make_x(1900 + idx, 1, Ci, (64, 64))
+        want2, _ = oracle_mod.spectral_conv2d(x2, W, 16)
+        got = run_gpu(gpu, "spectral_conv2d", x2, W, 16).astype(np.complex128)
+        assert np.linalg.norm((got - want2).ravel()) <= REL_L2 * np.linalg.norm(want2.ravel()), ("2d", Ci, Co)
+        Wm = np.broadcast_to(W[:, :, None, None], (Ci, Co, 16, 16)).copy()
+        yd = torch.full((1, Co, 64, 64), float("nan"), dtype=torch.complex64, device="cuda")
+        binding.spectral_conv2d_permode(torch.from_numpy(x2).cuda(), torch.from_numpy(Wm).cuda(), yd)
+        torch.cuda.synchronize()
+        got = yd.cpu().numpy().astype(np.complex128)
+        assert np.linalg.norm((got - want2).ravel()) <= REL_L2 * np.linalg.norm(want2.ravel()), ("2d permode", Ci, Co)
+    say(f"   {len(pairs)} channel-count pairs on 8-9 entry points each")
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
