@@ -707,6 +707,46 @@ def test_channel_count_sweep(gpu, oracle_mod):
     say(f"   {len(pairs)} channel-count pairs on 8-9 entry points each")
 
 
+def test_batch_size_sweep(gpu, oracle_mod):
+    """Odd and boundary batch sizes on the kernels that group pencils, tiles or images (pruned sweeps, two long
+    pencils per sweep, mode tiles shared by batch elements, the batch groups of the per-mode contraction)."""
+    torch, binding = gpu
+    Ci, Co = 3, 5
+    for B in (1, 2, 3, 5, 7, 8, 9, 15, 16, 17, 31, 33, 65):
+        for (fn, N, K) in (("spectral_conv1d_pruned", 64, 16), ("spectral_conv1d_pruned", 256, 32),
+                           ("spectral_conv1d_pruned", 2048, 128), ("spectral_conv1d_gemm_ifft", 128, 32),
+                           ("spectral_conv1d", 64, 8)):
+            x = inputs.make_x(2000 + B + N, B, Ci, (N,))
+            W = inputs.make_W(2000 + B + N, Ci, Co)
+            want, _ = oracle_mod.spectral_conv1d(x, W, K)
+            got = run_gpu(gpu, fn, x, W, K).astype(np.complex128)
+            assert np.linalg.norm((got - want).ravel()) <= REL_L2 * np.linalg.norm(want.ravel()), (fn, B, N, K)
+        for (N, K) in ((64, 16), (256, 12)):
+            x = inputs.make_x(2100 + B + N, B, Ci, (N,))
+            Wm = np.ascontiguousarray(inputs.make_W(2100 + B + N, Ci, Co * K).reshape(Ci, Co, K))
+            want, _ = oracle_mod.spectral_conv1d_permode(x, Wm)
+            yd = torch.full((B, Co, N), float("nan"), dtype=torch.complex64, device="cuda")
+            binding.spectral_conv1d_permode(torch.from_numpy(x).cuda(), torch.from_numpy(Wm).cuda(), yd)
+            torch.cuda.synchronize()
+            got = yd.cpu().numpy().astype(np.complex128)
+            assert np.linalg.norm((got - want).ravel()) <= REL_L2 * np.linalg.norm(want.ravel()), ("permode", B, N, K)
+            xr = np.ascontiguousarray(x.real)
+            wantr, _ = oracle_mod.fno1d_real(xr, Wm)
+            yr = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+            binding.fno1d_real(torch.from_numpy(xr).cuda(), torch.from_numpy(Wm).cuda(), yr)
+            torch.cuda.synchronize()
+            got = yr.cpu().numpy().astype(np.float64)
+            assert np.linalg.norm((got - wantr).ravel()) <= REL_L2 * np.linalg.norm(wantr.ravel()), ("fno1d", B, N, K)
+        x2 = np.ascontiguousarray(inputs.make_x(2200 + B, B, Ci, (64, 64)).real)
+        Wf = np.ascontiguousarray(inputs.make_W(2200 + B, Ci, Co * 24 * 12).reshape(Ci, Co, 24, 12))
+        wantf, _ = oracle_mod.fno2d_real(x2, Wf)
+        yf = torch.full((B, Co, 64, 64), float("nan"), dtype=torch.float32, device="cuda")
+        binding.fno2d_real(torch.from_numpy(x2).cuda(), torch.from_numpy(Wf).cuda(), yf)
+        torch.cuda.synchronize()
+        got = yf.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm((got - wantf).ravel()) <= REL_L2 * np.linalg.norm(wantf.ravel()), ("fno2d", B)
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
