@@ -7,23 +7,31 @@ hipError_t fused1d_launch_n256(int K, const Fused1dArgs &a, long long rows, hipS
 {
     switch (K) {
     case 16:
-        if (a.C_out > 64) return launch_fused1d<256, 16, 4>(a, rows, s);
-        if (a.C_out > 32) return launch_fused1d<256, 16, 2>(a, rows, s);
-        return launch_fused1d<256, 16, 1>(a, rows, s);
+        switch (pick_output_tiles(a.C_out, rows, 4)) {
+        case 4: return launch_fused1d<256, 16, 4>(a, rows, s);
+        case 2: return launch_fused1d<256, 16, 2>(a, rows, s);
+        default: return launch_fused1d<256, 16, 1>(a, rows, s);
+        }
     case 32:
-        if (a.C_out > 64) return launch_fused1d<256, 32, 4>(a, rows, s);
-        if (a.C_out > 32) return launch_fused1d<256, 32, 2>(a, rows, s);
-        return launch_fused1d<256, 32, 1>(a, rows, s);
+        switch (pick_output_tiles(a.C_out, rows, 4)) {
+        case 4: return launch_fused1d<256, 32, 4>(a, rows, s);
+        case 2: return launch_fused1d<256, 32, 2>(a, rows, s);
+        default: return launch_fused1d<256, 32, 1>(a, rows, s);
+        }
     case 64:
-        if (a.C_out > 64) return launch_fused1d<256, 64, 4>(a, rows, s);
-        if (a.C_out > 32) return launch_fused1d<256, 64, 2>(a, rows, s);
-        return launch_fused1d<256, 64, 1>(a, rows, s);
+        switch (pick_output_tiles(a.C_out, rows, 4)) {
+        case 4: return launch_fused1d<256, 64, 4>(a, rows, s);
+        case 2: return launch_fused1d<256, 64, 2>(a, rows, s);
+        default: return launch_fused1d<256, 64, 1>(a, rows, s);
+        }
     case 128:
-        if (a.C_out > 64) return launch_fused1d<256, 128, 4>(a, rows, s);
-        if (a.C_out > 32) return launch_fused1d<256, 128, 2>(a, rows, s);
-        return launch_fused1d<256, 128, 1>(a, rows, s);
+        switch (pick_output_tiles(a.C_out, rows, 4)) {
+        case 4: return launch_fused1d<256, 128, 4>(a, rows, s);
+        case 2: return launch_fused1d<256, 128, 2>(a, rows, s);
+        default: return launch_fused1d<256, 128, 1>(a, rows, s);
+        }
     case 256:
-        if (a.C_out > 32) return launch_fused1d<256, 256, 2>(a, rows, s);
+        if (pick_output_tiles(a.C_out, rows, 2) == 2) return launch_fused1d<256, 256, 2>(a, rows, s);
         return launch_fused1d<256, 256, 1>(a, rows, s);
     default: return hipErrorInvalidValue;
     }

@@ -747,6 +747,28 @@ def test_batch_size_sweep(gpu, oracle_mod):
         assert np.linalg.norm((got - wantf).ravel()) <= REL_L2 * np.linalg.norm(wantf.ravel()), ("fno2d", B)
 
 
+def test_wide_output_slabs_with_ragged_channels(gpu, oracle_mod):
+    """Batches large enough that the fused kernel keeps its widest output slabs (small batches are given narrower
+    ones to fill the chip), with channel counts that leave the last slab, the last 32-output tile and the last
+    channel block partly empty."""
+    for (B, Ci, Co, N, K) in [(140, 5, 70, 64, 16), (150, 9, 130, 128, 32), (140, 33, 40, 256, 64), (130, 20, 96, 512, 64),
+                              (135, 7, 100, 256, 128), (132, 17, 33, 1024, 32), (140, 3, 129, 64, 64)]:
+        say(f"[case] wide slabs {(B, Ci, Co, N, K)}")
+        x = inputs.make_x(2300 + N + K, B, Ci, (N,))
+        W = inputs.make_W(2300 + N + K, Ci, Co)
+        want, _ = oracle_mod.spectral_conv1d(x, W, K)
+        check(run_gpu(gpu, "spectral_conv1d", x, W, K), want, "fused, wide slabs")
+        if 2 * K <= N:
+            torch, binding = gpu
+            xr = np.ascontiguousarray(x.real)
+            wantr, _ = oracle_mod.spectral_conv1d_real(xr, W, K)
+            yd = torch.full((B, Co, N), float("nan"), dtype=torch.float32, device="cuda")
+            binding.spectral_conv1d_real(torch.from_numpy(xr).cuda(), torch.from_numpy(W).cuda(), yd, K)
+            torch.cuda.synchronize()
+            got = yd.cpu().numpy().astype(np.float64)
+            assert np.linalg.norm((got - wantr).ravel()) <= REL_L2 * np.linalg.norm(wantr.ravel())
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
