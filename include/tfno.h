@@ -38,6 +38,14 @@
  *    call is TFNO_ERR_UNSUPPORTED only when no built size >= K exists for its N.  Workspace sizes follow K'.
  *  - Thread safety: entry points may be called concurrently from several host
  *    threads; tfno_set_workspace must not race with calls that use the workspace.
+ *  - The workspace is ONE buffer per process (not per stream, not per device): every entry point that needs
+ *    intermediates uses the buffer registered last, on whatever stream it is given.  Calls that use it must
+ *    therefore be ordered against each other by the caller, and a buffer may be replaced or freed only after
+ *    every stream has passed the calls that used it (a captured HIP graph keeps the address it was captured with).
+ *  - Two environment variables, read once per process, select alternative kernels for A/B measurements and tests:
+ *    TFNO_CONTRACTION=f32 (FP32-MFMA contractions instead of the exact-split BF16 ones) and, for N = 1024,
+ *    TFNO_KERNEL=ws | generic (the wave-specialised or the four-wave kernel instead of the default).  Results stay
+ *    within the same tolerance; production callers leave both unset.
  */
 #ifndef TFNO_H
 #define TFNO_H

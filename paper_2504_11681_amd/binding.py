@@ -125,11 +125,19 @@ def set_workspace(tensor) -> None:
 
 
 def ensure_workspace(nbytes: int, device) -> None:
-    """Makes sure a registered workspace of at least nbytes exists (allocates with torch if not)."""
+    """Makes sure a registered workspace of at least nbytes exists (allocates with torch if not).
+
+    The workspace is one buffer per process, shared by every stream.  Before a larger one replaces it the device is
+    synchronised, so no kernel enqueued earlier on any stream still reads or writes the old buffer when torch frees
+    it.  A HIP graph captured with the old buffer keeps the old address: growing the workspace invalidates such
+    graphs (capture after the largest shape has been run once, or register a buffer of the final size up front with
+    ``set_workspace``)."""
     import torch
     if nbytes == 0:
         return
     if _workspace is None or _workspace.numel() * _workspace.element_size() < nbytes or _workspace.device != device:
+        if _workspace is not None:
+            torch.cuda.synchronize(_workspace.device)
         set_workspace(torch.empty(nbytes, dtype=torch.uint8, device=device))
 
 

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <initializer_list>
+#include <mutex>
 
 namespace tfno {
 
@@ -58,6 +60,23 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned id, unsigned n)
     const unsigned q = n >> 3, r = n & 7, x = id & 7;
     return x * q + (x < r ? x : r) + (id >> 3);
 }
+
+// Raises the dynamic-LDS limit of a launch site's kernels exactly once per process, whichever host thread gets
+// there first (std::call_once); later calls return the result of that one attempt.
+struct LdsLimitOnce {
+    std::once_flag flag;
+    hipError_t result = hipSuccess;
+    hipError_t set(std::initializer_list<const void *> kernels, int bytes)
+    {
+        std::call_once(flag, [&] {
+            for (const void *k : kernels) {
+                result = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+                if (result != hipSuccess) return;
+            }
+        });
+        return result;
+    }
+};
 
 // exp(2 pi i * num / den) with one accurate sincospi evaluation
 __device__ __forceinline__ c64 cis2pi(float num, float den)

@@ -35,11 +35,6 @@
 #include "fused1d.h"
 #include "bf16x3.h"
 
-#ifndef TFNO_STAMP
-#define TFNO_STAMP(i)   // four phase-timestamp hooks (start, after prologue, after k-loop, end) that a timing
-                        // harness may define before including this header; empty in the library
-#endif
-
 namespace tfno {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -145,8 +140,6 @@ k_fused1d(Fused1dArgs a)
         if constexpr (REAL && N == 1024) return __builtin_nontemporal_load(q);
         else return *q;
     };
-
-    TFNO_STAMP(0);
     // stage-A identity of this lane; twiddles w_N^(t p) = exp(-2 pi i t p / N) live in LDS as [t][p]
     // (stage-B lanes read consecutive p: conflict-free), computed once per workgroup with accurate sincospi
     const int jw = lane / T, t = lane % T;
@@ -363,7 +356,6 @@ k_fused1d(Fused1dArgs a)
             if (n_it > 2) load_pencil(2 * PPI);
         }
         __syncthreads();
-        TFNO_STAMP(1);
         {
             int it = 0;
             for (; it + 3 < n_it; ++it) step(yes, yes, yes, it);
@@ -426,8 +418,6 @@ k_fused1d(Fused1dArgs a)
         if (it + 1 < n_it) { sstep(yes, no, it); ++it; }
         sstep(no, no, it);
     }
-
-    TFNO_STAMP(2);
     // ------------------------------------------------------------------ epilogue
     if constexpr (MODE == 1) {
         // FFT + CGEMM: register r of lane l of tile i holds Yh[o][k] for o = 8(r/4) + 4(l/32) + r%4 of the wave's
@@ -541,23 +531,17 @@ k_fused1d(Fused1dArgs a)
             __syncthreads();
         }
     }
-    TFNO_STAMP(3);
 }
 
 template <int N, int K, int OT, bool BF, int MODE = 0, bool REAL = false>
 hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
     using C = FusedCfg<N, K, OT, BF>;
-    static bool attr_done = false;   // benign race: every thread sets the same value
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsLimitOnce lds_limit;
+    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL>),
+                                        reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL>)},
+                                       (int)C::LDS_DYN);
+    if (e != hipSuccess) return e;
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
     // unmasked kernel only when every workgroup's slab of 32 OT outputs exists in full
     if (a.C_in % C::PPI == 0 && a.C_out % (32 * OT) == 0)

@@ -78,8 +78,6 @@ k_fused1d_sym(Fused1dArgs a)
     const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
-
-    TFNO_STAMP(0);
     const int n_it = (a.C_in + PPI - 1) / PPI;
     c64 *patch = patch_all + wave * C::PATCH;
     const int p = lane;                                 // row-stage identity
@@ -261,7 +259,6 @@ k_fused1d_sym(Fused1dArgs a)
     }
     split_w();
     __syncthreads();                                        // XS[0] holds block 0
-    TFNO_STAMP(1);
     if constexpr (DEEP) {
         // iteration `it` transforms block it + 1 (buffer (it + 1) & 1) and refills that buffer with block it + 3
         int it = 0;
@@ -281,7 +278,6 @@ k_fused1d_sym(Fused1dArgs a)
     }
 
     // ------------------------------------------------------------------ epilogue
-    TFNO_STAMP(2);
     __syncthreads();                                        // every wave is done reading XS, which YH aliases
     for (int r = 0; r < 16; ++r) {
         // spectra of this round's 8 output pencils (slot 2 slab + l/32), in mode order
@@ -332,24 +328,18 @@ k_fused1d_sym(Fused1dArgs a)
             for (int j = 0; j < 16; ++j) store_nt(dst + 64 * j, res[j]);
         }
     }
-    TFNO_STAMP(3);
 }
 
 template <int K>
 hipError_t launch_fused1d_sym(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
     using C = SymCfg<K>;
-    static bool attr_done = false;   // benign race: every thread sets the same value
-    if (!attr_done) {
-        const void *kernels[3] = {reinterpret_cast<const void *>(&k_fused1d_sym<K, true, true>),
-                                  reinterpret_cast<const void *>(&k_fused1d_sym<K, true, false>),
-                                  reinterpret_cast<const void *>(&k_fused1d_sym<K, false, false>)};
-        for (const void *k : kernels) {
-            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-            if (e != hipSuccess) return e;
-        }
-        attr_done = true;
-    }
+    static LdsLimitOnce lds_limit;
+    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d_sym<K, true, true>),
+                                        reinterpret_cast<const void *>(&k_fused1d_sym<K, true, false>),
+                                        reinterpret_cast<const void *>(&k_fused1d_sym<K, false, false>)},
+                                       (int)C::LDS_DYN);
+    if (e != hipSuccess) return e;
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 127) / 128));
     const bool even = a.C_in % C::PPI == 0 && a.C_out % 128 == 0;
     const int n_it = (a.C_in + C::PPI - 1) / C::PPI;

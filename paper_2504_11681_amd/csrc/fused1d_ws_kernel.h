@@ -78,8 +78,6 @@ k_fused1d_ws(Fused1dArgs a)
     const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
-
-    TFNO_STAMP(0);
     const int n_it = (a.C_in + PPI - 1) / PPI;
     const int h = lane >> 5, p = lane & 31;     // half-wave = pencil slot; p = t in the row stage, column in the column stage
     // Z tile element (row pp, position t) of this half-wave's pencil lives at  pp*32 + (t ^ pp):
@@ -182,7 +180,6 @@ k_fused1d_ws(Fused1dArgs a)
         __syncthreads();                                    // P1: the M waves have built the twiddle table
         col_stage(0);
         __syncthreads();                                    // P2: XS[0] holds block 0
-        TFNO_STAMP(1);
         int it = 0;
         for (; it + 2 < n_it; ++it) {                       // blocks 1 .. n_it - 2, each refilling v with its successor
             row_stage(refill, (it + 2) * PPI);
@@ -194,7 +191,6 @@ k_fused1d_ws(Fused1dArgs a)
             col_stage((it + 1) & 1);
             __syncthreads();
         }
-        TFNO_STAMP(2);
         // epilogue: stage A' of the pencil the M wave (wave + 4) left in Z[r & 1], coalesced store
         for (int r = 0; r < 16; ++r) {
             __syncthreads();                                // E_r: Z[r & 1] holds round r
@@ -210,7 +206,6 @@ k_fused1d_ws(Fused1dArgs a)
                 for (int jj = 0; jj < P; ++jj) store_nt(dst + T * jj, res[jj]);
             }
         }
-        TFNO_STAMP(3);
         return;
     }
 
@@ -322,16 +317,10 @@ template <int K>
 hipError_t launch_fused1d_ws(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
     using C = WsCfg<K>;
-    static bool attr_done = false;   // benign race: every thread sets the same value
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_ws<K, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fused1d_ws<K, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_DYN);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsLimitOnce lds_limit;
+    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d_ws<K, true>),
+                                        reinterpret_cast<const void *>(&k_fused1d_ws<K, false>)}, (int)C::LDS_DYN);
+    if (e != hipSuccess) return e;
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 127) / 128));
     if (a.C_in % C::PPI == 0 && a.C_out % 128 == 0)
         hipLaunchKernelGGL((k_fused1d_ws<K, true>), grid, dim3(512), C::LDS_DYN, s, a);

@@ -192,30 +192,17 @@ hipError_t launch_axis_fft(int dir, const c64 *in, c64 *out, int N, long long nu
                            long long inner_count, long long in_outer_stride, long long out_outer_stride,
                            long long elem_stride, int n_in, int n_out, float scale, hipStream_t s)
 {
-    static bool attr_done = false;   // benign race: every thread sets the same value
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_staged_fft<-1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_staged_fft<+1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsLimitOnce fft_limit, dft_limit;
+    hipError_t e = fft_limit.set({reinterpret_cast<const void *>(&k_staged_fft<-1>),
+                                  reinterpret_cast<const void *>(&k_staged_fft<+1>)}, 96 * 1024);
+    if (e != hipSuccess) return e;
     if (num_pencils == 0) return hipSuccess;
     int PC = 4096 / N; if (PC > 16) PC = 16; if (PC < 1) PC = 1;
     if (inner_count > 1) { while (PC > 1 && inner_count % PC) PC >>= 1; }
     if ((N & (N - 1)) != 0) {                               // not a power of two: direct sum
-        static bool dft_attr_done = false;
-        if (!dft_attr_done) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_staged_dft<-1>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_staged_dft<+1>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            if (e != hipSuccess) return e;
-            dft_attr_done = true;
-        }
+        e = dft_limit.set({reinterpret_cast<const void *>(&k_staged_dft<-1>),
+                           reinterpret_cast<const void *>(&k_staged_dft<+1>)}, 96 * 1024);
+        if (e != hipSuccess) return e;
         const size_t dlds = ((size_t)PC * N + N) * sizeof(c64);
         const long long dblocks = (num_pencils + PC - 1) / PC;
         if (dir < 0)

@@ -799,6 +799,32 @@ def test_empty_batch_and_error_paths(gpu):
     torch.cuda.synchronize()
 
 
+def test_workspace_growth_does_not_disturb_earlier_work_on_another_stream(gpu, oracle_mod):
+    """A call that uses the workspace is enqueued on a side stream behind a long queue of other launches; a call
+    with a larger workspace need follows on the default stream at once.  The binding synchronises the device before
+    it replaces the registered buffer, so the first call still finds its intermediates: its result must match the
+    oracle."""
+    torch, binding = gpu
+    binding.set_workspace(None)                               # start from no workspace at all
+    xa = inputs.make_x(2500, 6, 24, (256,)); Wa = inputs.make_W(2500, 24, 40)
+    xb = inputs.make_x(2501, 24, 48, (256,)); Wb = inputs.make_W(2501, 48, 64)
+    xad, Wad = torch.from_numpy(xa).cuda(), torch.from_numpy(Wa).cuda()
+    xbd, Wbd = torch.from_numpy(xb).cuda(), torch.from_numpy(Wb).cuda()
+    ya = torch.full((6, 40, 256), float("nan"), dtype=torch.complex64, device="cuda")
+    yb = torch.full((24, 64, 256), float("nan"), dtype=torch.complex64, device="cuda")
+    filler = torch.empty(1 << 26, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(20):
+            filler.fill_(1.0)                                 # keeps the side stream busy ahead of the call
+        binding.spectral_conv1d_pruned(xad, Wad, ya, 64, stream=side.cuda_stream)
+    binding.spectral_conv1d_pruned(xbd, Wbd, yb, 64)          # needs a larger workspace
+    torch.cuda.synchronize()
+    check(ya.cpu().numpy(), oracle_mod.spectral_conv1d(xa, Wa, 64)[0], "first call (side stream)")
+    check(yb.cpu().numpy(), oracle_mod.spectral_conv1d(xb, Wb, 64)[0], "second call (larger workspace)")
+
+
 # ----------------------------------------------------- full benchmark sizes, sampled batch elements
 
 def full_size_case(gpu, oracle_mod, w, fn_name, sample_b):
