@@ -99,6 +99,23 @@ tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y,
                                  int B, int C_in, int C_out, int N, int K, void *stream);
 
 /*
+ * tfno_spectral_conv2d for callers that cannot allocate device memory or register a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and kernels as
+ * tfno_spectral_conv2d, but the intermediates (the truncated spectra, or the strips of the strip pipeline) live in
+ * a scratch array of TFNO_NOALLOC_SCRATCH_BYTES that is part of the library image: every GPU the library runs on
+ * holds its own copy until the process ends, and the call allocates and frees nothing and ignores
+ * tfno_set_workspace.  A shape whose tfno_workspace_bytes(2, 0, ...) exceeds TFNO_NOALLOC_SCRATCH_BYTES returns
+ * TFNO_ERR_WORKSPACE before anything is launched.  The first call on a device looks up the array's address there
+ * (hipGetSymbolAddress); a failure of that lookup is TFNO_ERR_HIP.  All calls on one GPU share that GPU's array:
+ * calls that may overlap in time on one GPU (different streams, or host threads without ordering) race on it and
+ * must be serialised by the caller.  Nothing in the array needs clearing between calls: every element a launch
+ * reads was written earlier in the same call.
+ */
+#define TFNO_NOALLOC_SCRATCH_BYTES (32u << 20)
+tfno_status tfno_spectral_conv2d_noalloc(const void *x, const void *W, void *y,
+                                         int B, int C_in, int C_out, int N, int K, void *stream);
+
+/*
  * Unfused baseline with the structure the paper attributes to the PyTorch Fourier
  * layer (Sec. 1, Sec. 2.1): full FFT, truncate copy, CGEMM, zero-pad copy, full
  * inverse FFT, every intermediate in global memory (five launches in 1-D; the 2-D

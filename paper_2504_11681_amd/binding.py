@@ -32,6 +32,7 @@ EXPORTS = (
     "tfno_fno2d_real_workspace_bytes",
     "tfno_fno1d_real",
     "tfno_fno1d_real_workspace_bytes",
+    "tfno_spectral_conv2d_noalloc",
     "tfno_workspace_bytes",
     "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
@@ -61,7 +62,8 @@ def lib() -> ctypes.CDLL:
                                "(there is no fallback path)")
         L = ctypes.CDLL(LIB_PATH)
         vp, ci = ctypes.c_void_p, ctypes.c_int
-        for name in CONV_EXPORTS + ("tfno_spectral_conv1d_permode", "tfno_spectral_conv1d_real"):
+        for name in CONV_EXPORTS + ("tfno_spectral_conv1d_permode", "tfno_spectral_conv1d_real",
+                                    "tfno_spectral_conv2d_noalloc"):
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
@@ -167,6 +169,29 @@ def spectral_conv1d(x, W, y, K: int, stream=None):
 
 def spectral_conv2d(x, W, y, K: int, stream=None):
     return _call("tfno_spectral_conv2d", 2, False, x, W, y, K, stream)
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20     # TFNO_NOALLOC_SCRATCH_BYTES of the header
+
+
+def spectral_conv2d_noalloc(x, W, y, K: int, stream=None):
+    """tfno_spectral_conv2d with the library's own scratch array: allocates nothing and registers no workspace."""
+    import torch
+    for t, what in ((x, "x"), (W, "W"), (y, "y")):
+        if t.dtype != torch.complex64 or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"{what} must be a contiguous complex64 device tensor")
+    if x.dim() != 4 or y.dim() != 4 or W.dim() != 2 or x.shape[2] != x.shape[3]:
+        raise ValueError("x, y must be [B, C, N, N]; W must be [C_in, C_out]")
+    B, C_in, N = x.shape[0], x.shape[1], x.shape[2]
+    C_out = W.shape[1]
+    if W.shape[0] != C_in or tuple(y.shape) != (B, C_out, N, N):
+        raise ValueError("inconsistent tensor shapes")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = lib().tfno_spectral_conv2d_noalloc(x.data_ptr(), W.data_ptr(), y.data_ptr(), B, C_in, C_out, N, K, stream)
+    if st != OK:
+        raise TfnoError(st, "tfno_spectral_conv2d_noalloc")
+    return y
 
 
 def spectral_conv1d_staged(x, W, y, K: int, stream=None):

@@ -8,14 +8,39 @@
 
 #include <atomic>
 #include <cstdlib>
+#include <mutex>
 
 using namespace tfno;
+
+// Library-owned scratch of tfno_spectral_conv2d_noalloc: every GPU the library runs on holds its own copy of this
+// array until the process ends.  In host code the name is a stand-in, not a device address: host code only ever
+// uses the per-device address that scratch_address() looks up once per device.
+static __device__ __align__(256) unsigned char scratch[TFNO_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
 struct Workspace { void *ptr; size_t bytes; };
 std::atomic<void *> g_ws_ptr{nullptr};
 std::atomic<size_t> g_ws_bytes{0};
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call there; no allocation).
+tfno_status scratch_address(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return TFNO_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TFNO_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TFNO_OK;
+}
 
 bool is_pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
 
@@ -126,8 +151,9 @@ tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W
 
 enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2, FFT_GEMM = 3, GEMM_IFFT = 4 };
 
+// own_scratch: the intermediates go to the library's static scratch array instead of the registered workspace
 tfno_status run(const Shape &req, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out,
-                void *stream)
+                void *stream, bool own_scratch = false)
 {
     const bool staged = variant == STAGED;
     bool empty;
@@ -142,7 +168,12 @@ tfno_status run(const Shape &req, Variant variant, const void *x, const void *W,
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     void *ws = nullptr;
-    st = check_workspace(workspace_for(req, (int)variant, B, C_in, C_out), x, xb, W, wb, y, yb, &ws);
+    if (own_scratch) {
+        if (workspace_for(req, (int)variant, B, C_in, C_out) > (size_t)TFNO_NOALLOC_SCRATCH_BYTES) return TFNO_ERR_WORKSPACE;
+        st = scratch_address(&ws);
+    } else {
+        st = check_workspace(workspace_for(req, (int)variant, B, C_in, C_out), x, xb, W, wb, y, yb, &ws);
+    }
     if (st != TFNO_OK) return st;
 
     hipStream_t s = (hipStream_t)stream;
@@ -495,6 +526,12 @@ tfno_status tfno_spectral_conv2d(const void *x, const void *W, void *y, int B, i
     return run(shape2d(N, N, K, K), FUSED, x, W, y, B, C_in, C_out, stream);
 }
 
+tfno_status tfno_spectral_conv2d_noalloc(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N, int K,
+                                         void *stream)
+{
+    return run(shape2d(N, N, K, K), FUSED, x, W, y, B, C_in, C_out, stream, true);
+}
+
 tfno_status tfno_spectral_conv1d_pruned(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N,
                                         int K, void *stream)
 {
@@ -616,7 +653,7 @@ const char *tfno_status_string(tfno_status s)
     case TFNO_ERR_SHAPE: return "a size argument is out of range";
     case TFNO_ERR_UNSUPPORTED: return "no fused kernel for this shape (use the staged entry point)";
     case TFNO_ERR_ALIAS: return "y or the workspace overlaps another buffer";
-    case TFNO_ERR_WORKSPACE: return "workspace missing or too small (see tfno_workspace_bytes)";
+    case TFNO_ERR_WORKSPACE: return "workspace missing or too small (see tfno_workspace_bytes), or the shape needs more than the built-in scratch";
     case TFNO_ERR_HIP: return "the HIP runtime reported an error at launch";
     default: return "unknown status";
     }

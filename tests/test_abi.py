@@ -45,7 +45,7 @@ def call(L, name, x, W, y, B, Ci, Co, N, K):
     return getattr(L, name)(x, W, y, B, Ci, Co, N, K, None)
 
 
-@pytest.mark.parametrize("name", binding.CONV_EXPORTS + ("tfno_spectral_conv1d_permode",))
+@pytest.mark.parametrize("name", binding.CONV_EXPORTS + ("tfno_spectral_conv1d_permode", "tfno_spectral_conv2d_noalloc"))
 def test_argument_errors_are_caught_on_the_host(L, name):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     assert call(L, name, None, W, y, 2, 4, 4, 64, 16) == binding.ERR_NULL
@@ -230,3 +230,14 @@ def test_workspace_contract(L):
     assert L.tfno_set_workspace(x, need) == binding.OK
     assert call(L, "tfno_spectral_conv1d_staged", x, W, y, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
     assert L.tfno_set_workspace(None, 0) == binding.OK
+
+
+def test_noalloc_entry_point_refuses_shapes_beyond_its_scratch_on_the_host(L):
+    """The shape check of tfno_spectral_conv2d_noalloc runs before any HIP call: a shape whose intermediates exceed
+    the built-in scratch array is TFNO_ERR_WORKSPACE."""
+    x, W, y = FAKE, FAKE + (1 << 40), FAKE + (2 << 40)
+    assert binding.workspace_bytes(2, 0, 32, 64, 64, 256, 64) > binding.NOALLOC_SCRATCH_BYTES
+    assert L.tfno_spectral_conv2d_noalloc(x, W, y, 32, 64, 64, 256, 64, None) == binding.ERR_WORKSPACE
+    text = open(os.path.join(ROOT, "include", "tfno.h")).read()
+    m = re.search(r"#define TFNO_NOALLOC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == binding.NOALLOC_SCRATCH_BYTES
