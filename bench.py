@@ -19,7 +19,24 @@ import sys
 import time
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X published dense FP32 matrix rate
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense BF16 matrix rate
+BF16_PRODUCTS = 6               # BF16 products per FP32 multiply-add of the exact three-term operand split
+
+
+def roofline_of(w, dev):
+    """Which roofline bounds the layer and the fraction reached, from the device seconds per layer `dev`.
+    Memory floor: the algorithmic bytes at the HBM peak.  Matrix floor: the contraction flops on the pipe the kernels
+    run them on, the BF16 matrix pipe with six BF16 products per FP32 product (so its FP32-equivalent peak is
+    2.5 PFLOP/s / 6).  The larger floor is the bound; a layer whose bytes would take under 5 us at the HBM peak is
+    bound by launch and pipeline latency and its fractions say nothing about the kernel."""
+    t_hbm = w.compulsory_bytes / (HBM_PEAK_GBPS * 1e9)
+    t_mfma = flops_of(w) * BF16_PRODUCTS / (BF16_MFMA_PEAK_TFLOPS * 1e12)
+    bound = "latency" if t_hbm < 5e-6 else "mfma_bf16x3" if t_mfma > t_hbm else "hbm"
+    return {"bound": bound, "frac": max(t_hbm, t_mfma) / dev,
+            "hbm_frac": t_hbm / dev, "bf16_pipe_frac": t_mfma / dev,
+            "flop_per_byte": flops_of(w) / w.compulsory_bytes,
+            "effective_hbm_GBps": w.compulsory_bytes / dev / 1e9,
+            "contraction_TFLOPs": flops_of(w) / dev / 1e12}
 
 
 def pick_config(name: str):
@@ -243,8 +260,8 @@ def measure_real(torch, binding, w, steps, warmup, ramp):
 
 
 def measure_fno2d(torch, binding, B, C, N1, N2, M1, M2, steps, warmup, ramp):
-    """Device seconds per layer of the real-field 2-D FNO layer and of the same layer composed from PyTorch library calls
-    (rfft2, two einsum corners, irfft2); inputs of the usual recipe (real parts), weights per mode."""
+    """Device seconds per layer of the real-field 2-D FNO layer and its compulsory bytes; inputs of the usual recipe
+    (real parts), weights per mode."""
     from paper_2504_11681_amd import inputs
     seed = 9
     xd = torch.empty((B, C, N1, N2), dtype=torch.float32, device="cuda")
@@ -263,52 +280,9 @@ def measure_fno2d(torch, binding, B, C, N1, N2, M1, M2, steps, warmup, ramp):
         binding.fno2d_real(xi, Wd, yi, stream)
 
     _, dev = time_calls(torch, call, steps, warmup, ramp)
-
-    def layer():
-        xi, _ = sets[turn[0] % len(sets)]
-        turn[0] += 1
-        xf = torch.fft.rfft2(xi)
-        out = torch.zeros((B, C, N1, N2 // 2 + 1), dtype=torch.complex64, device="cuda")
-        out[:, :, :M1, :M2] = torch.einsum("bixy,ioxy->boxy", xf[:, :, :M1, :M2], Wd[:, :, M1:, :])
-        out[:, :, -M1:, :M2] = torch.einsum("bixy,ioxy->boxy", xf[:, :, -M1:, :M2], Wd[:, :, :M1, :])
-        return torch.fft.irfft2(out, s=(N1, N2))
-
-    ref = layer()
-    call()
-    torch.cuda.synchronize()
-    got = sets[(turn[0] - 1) % len(sets)][1]
-    err = (torch.linalg.norm(got - ref) / torch.linalg.norm(ref)).item()
-    _, dev_t = time_calls(torch, layer, max(10, steps // 10), 3, ramp)
-    del xd, Wd, sets, ref
+    del xd, Wd, sets
     torch.cuda.empty_cache()
-    return dev, dev_t, err, pair + 8 * C * C * 2 * M1 * M2
-
-
-def pytorch_baseline(w, torch, binding, steps, ramp):
-    """The layer as PyTorch composes it from library calls (the structure the paper measures against, Sec. 1 and 5):
-    full FFT, slice, complex matmul over channels, zero pad, full inverse FFT -- rocFFT and the BLAS library under
-    torch.  Timed like the other legs; its result is compared with the fused kernel's once."""
-    xd, Wd, yd = device_inputs(w, torch)
-    dims = tuple(range(2, 2 + w.dims))
-    sl = (Ellipsis,) + (slice(0, w.K),) * w.dims
-    pad = []
-    for _ in range(w.dims):
-        pad += [0, w.N - w.K]
-
-    def layer():
-        Xh = torch.fft.fftn(xd, dim=dims)[sl]
-        Yh = torch.einsum("bc...,co->bo...", Xh, Wd)
-        return torch.fft.ifftn(torch.nn.functional.pad(Yh, pad), dim=dims)
-
-    ref = layer()
-    getattr(binding, "spectral_conv%dd" % w.dims)(xd, Wd, yd, w.K)
-    torch.cuda.synchronize()
-    diff = float((ref - yd).abs().max() / yd.abs().max())
-    del ref
-    wall, dev = time_calls(torch, layer, steps, 2, ramp)
-    del xd, Wd, yd
-    torch.cuda.empty_cache()
-    return wall, dev, diff
+    return dev, pair + 8 * C * C * 2 * M1 * M2
 
 
 def cpu_baseline(w):
@@ -389,7 +363,8 @@ def main():
                           "fft_gemm_us": bdev * 1e6, "gemm_ifft_us": cdev * 1e6, "auto_us": adev * 1e6,
                           "staged_us": sdev * 1e6, "best": min(times, key=times.get),
                           "fused_hbm_frac": w.compulsory_bytes / dev / 1e9 / HBM_PEAK_GBPS,
-                          "fused_contraction_TFLOPs": flops_of(w) / dev / 1e12})
+                          "fused_contraction_TFLOPs": flops_of(w) / dev / 1e12,
+                          "auto_roofline": roofline_of(w, adev)})
         print(json.dumps({"metric": "fused_vs_unfused_crossover", "unit": "us per layer (HIP events)", "n_gpus": 1,
                           "steps": args.steps, "warmup": args.warmup, "dtype": "f32", "data": "synthetic",
                           "cells": cells}), flush=True)
@@ -402,13 +377,37 @@ def main():
     ms_per_step = wall / args.steps * 1e3
     layers_per_s = args.steps / wall
     alg_bytes = w.compulsory_bytes
-    achieved = alg_bytes / dev / 1e9
-    # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary, if one covers this workload
-    traffic = None
     tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(w.name, {}).get("hbm_bytes_per_launch")
 
+    def committed_traffic(name):
+        """HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated) from the committed counter summary that
+        covers the workload: read from profiles/traffic.json, NOT measured in this run (counters need the profiler)."""
+        if not os.path.exists(tpath):
+            return None, None
+        e = json.load(open(tpath)).get(name, {})
+        return e.get("hbm_bytes_per_launch"), e.get("source")
+
+    def roofline_entry(wk, devk, kernel, stats=None):
+        r = roofline_of(wk, devk)
+        traffic, src = committed_traffic(wk.name)
+        if r["bound"] == "mfma_bf16x3":
+            e = {"bound": "mfma", "achieved": flops_of(wk) * BF16_PRODUCTS / devk / 1e12, "peak": BF16_MFMA_PEAK_TFLOPS,
+                 "unit": "TFLOP/s", "pipe": "BF16 MFMA, six BF16 products per FP32 multiply-add (exact three-term split)"}
+        else:
+            e = {"bound": "hbm", "achieved": wk.compulsory_bytes / devk / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
+        e.update({"frac": e["achieved"] / e["peak"], "traffic": traffic,
+                  "traffic_source": None if traffic is None else f"{src} (committed rocprofv3 counter summary, not measured in this run)",
+                  "kernel": kernel, "algorithmic_bytes_per_launch": wk.compulsory_bytes,
+                  "algorithmic_flops_per_launch": flops_of(wk), "flop_per_byte": r["flop_per_byte"],
+                  "hbm_frac": r["hbm_frac"], "bf16_pipe_frac": r["bf16_pipe_frac"], "avg_launch_ms": devk * 1e3})
+        if r["bound"] == "latency":
+            e["note"] = "under 5 us of bytes at the HBM peak: bound by launch and pipeline latency"
+        if stats:
+            e["median_launch_ms"], e["min_launch_ms"] = stats["median_s"] * 1e3, stats["min_s"] * 1e3
+        return e
+
+    kernel_1d = ("k_fused1d_sym (N = 1024, K in {64, 128}), k_fused1d_wide (N = 256, eight waves), k_fused1d_ws / "
+                 "k_fused1d otherwise")
     out = {
         "metric": "fused_spectral_conv_layers_per_s",
         "value": layers_per_s,
@@ -427,68 +426,58 @@ def main():
         "config": {"workload": w.name, "dims": w.dims, "B": w.B, "C_in": w.C_in, "C_out": w.C_out,
                    "N": w.N, "K": w.K, "seed": w.seed,
                    "entry_point": "tfno_spectral_conv%dd" % w.dims + VARIANT_SUFFIX[vid]},
+        # the same bytes over the wall-clock time per step (launch overhead included): the headline fraction
         "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
         "effective_hbm_frac_of_peak": alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "contraction_TFLOPs": flops_of(w) / dev / 1e12,
-        "contraction_frac_of_fp32_mfma_peak": flops_of(w) / dev / 1e12 / FP32_MFMA_PEAK_TFLOPS,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "fused 1-D kernel (k_fused1d_sym for N = 1024, K in {64, 128}; k_fused1d_ws / k_fused1d otherwise)" if w.dims == 1 else "tfno_spectral_conv2d (3 kernels)",
-                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": dev * 1e3,
-                     "median_launch_ms": st["median_s"] * 1e3, "min_launch_ms": st["min_s"] * 1e3},
+        "roofline": roofline_entry(w, dev, kernel_1d if w.dims == 1 else "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)", st),
     }
 
     if not args.no_extras:
         s_steps = max(5, args.steps // 10)
         swall, sdev = measure(w, torch, binding, s_steps, 2, staged=True, ramp=args.ramp)
         out["staged"] = {"ms_per_step": swall / s_steps * 1e3, "layers_per_s": s_steps / swall,
-                         "variant": "five kernels: full FFT, truncate copy, CGEMM, pad copy, full iFFT",
+                         "variant": "five kernels: full FFT, truncate copy, CGEMM, pad copy, full iFFT (written for "
+                                    "generality, not speed: not the fair unfused reference, see unfused_pruned)",
                          "fused_speedup": (swall / s_steps) / (wall / args.steps)}
-        p_steps = max(5, args.steps // 20)
-        pwall, pdev, pdiff = pytorch_baseline(w, torch, binding, p_steps, args.ramp)
-        out["pytorch"] = {"ms_per_step": pwall / p_steps * 1e3, "layers_per_s": p_steps / pwall,
-                          "variant": "torch.fft.fftn, slice, einsum, pad, torch.fft.ifftn (library kernels)",
-                          "fused_speedup": (pwall / p_steps) / (wall / args.steps),
-                          "max_abs_diff_vs_fused_over_max": pdiff}
+        if w.dims == 1:
+            # the paper's variant A: the same pruned transforms and the same matrix-pipe contraction as three kernels,
+            # the truncated spectra crossing HBM -- the fair fused-versus-unfused ratio
+            a_steps = max(20, args.steps // 4)
+            awall, adev = measure(w, torch, binding, a_steps, max(5, args.warmup // 4), ramp=args.ramp, variant=2)
+            out["unfused_pruned"] = {"ms_per_step": awall / a_steps * 1e3, "layers_per_s": a_steps / awall,
+                                     "us_per_layer": adev * 1e6,
+                                     "variant": "three kernels (tfno_spectral_conv1d_pruned): pruned FFT with built-in "
+                                                "truncation, CGEMM, pruned iFFT with built-in padding",
+                                     "fused_speedup": adev / dev}
         if w.name.startswith("cfg3"):
             w4 = pick_config("cfg4")
             steps4 = max(10, args.steps // 4)
             wall4, dev4 = measure(w4, torch, binding, steps4, 5, ramp=args.ramp)
-            traffic4 = None
-            if os.path.exists(tpath):
-                traffic4 = json.load(open(tpath)).get(w4.name, {}).get("hbm_bytes_per_launch")
             out["cfg4_2d"] = {"workload": w4.name, "steps": steps4, "ms_per_step": wall4 / steps4 * 1e3,
                               "layers_per_s": steps4 / wall4,
                               "effective_hbm_GBps": w4.compulsory_bytes / (wall4 / steps4) / 1e9,
                               "effective_hbm_frac_of_peak": w4.compulsory_bytes / (wall4 / steps4) / 1e9 / HBM_PEAK_GBPS,
-                              "roofline": {"bound": "hbm", "achieved": w4.compulsory_bytes / dev4 / 1e9,
-                                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                           "frac": w4.compulsory_bytes / dev4 / 1e9 / HBM_PEAK_GBPS,
-                                           "traffic": traffic4,
-                                           "kernel": "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)",
-                                           "algorithmic_bytes_per_launch": w4.compulsory_bytes,
-                                           "avg_launch_ms": dev4 * 1e3}}
+                              "roofline": roofline_entry(w4, dev4, "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)")}
             # Everything below widens the report beyond the headline workloads; a failure there is recorded, not fatal
             # to the line (the headline figures above are already measured).
             try:
-                # the remaining configurations, fused entry point only: the two small 1-D shapes and the twelve cells
-                # of the hidden-dimension sweep (all variants of the sweep: --sweep)
+                # the remaining configurations: the two small 1-D shapes on the fused entry point and the twelve cells
+                # of the hidden-dimension sweep on the per-shape dispatch (all variants of the sweep: --sweep)
                 from paper_2504_11681_amd import inputs
                 others = []
                 for wo in [pick_config("cfg1"), pick_config("cfg2")] + list(inputs.sweep_configs()):
-                    _, devo = measure(wo, torch, binding, max(50, args.steps // 4), max(10, args.warmup // 4), ramp=args.ramp / 3)
-                    others.append({"workload": wo.name, "us_per_layer": devo * 1e6, "layers_per_s": 1.0 / devo,
-                                   # a layer whose bytes would take under 5 us at the HBM peak is bound by launch and
-                                   # pipeline latency, not by bandwidth
-                                   "bound": "latency" if wo.compulsory_bytes / (HBM_PEAK_GBPS * 1e9) < 5e-6 else "hbm",
-                                   "effective_hbm_GBps": wo.compulsory_bytes / devo / 1e9,
-                                   "hbm_frac": wo.compulsory_bytes / devo / 1e9 / HBM_PEAK_GBPS,
-                                   "contraction_TFLOPs": flops_of(wo) / devo / 1e12,
-                                   "contraction_frac_of_fp32_mfma_peak": flops_of(wo) / devo / 1e12 / FP32_MFMA_PEAK_TFLOPS})
-                    if others[-1]["bound"] == "latency":
+                    vo = 5 if wo.name.startswith("cfg5") else 0
+                    _, devo = measure(wo, torch, binding, max(50, args.steps // 4), max(10, args.warmup // 4),
+                                      ramp=args.ramp / 3, variant=vo)
+                    cell = {"workload": wo.name, "entry_point": "tfno_spectral_conv1d" + VARIANT_SUFFIX[vo],
+                            "us_per_layer": devo * 1e6, "layers_per_s": 1.0 / devo}
+                    cell.update(roofline_of(wo, devo))
+                    others.append(cell)
+                    if cell["bound"] == "latency":
                         gdt, gok = graph_time(wo, torch, binding)
-                        others[-1]["us_per_layer_in_hip_graph"] = gdt * 1e6
-                        others[-1]["hip_graph_replays_match_eager"] = gok
+                        cell["us_per_layer_in_hip_graph"] = gdt * 1e6
+                        cell["hip_graph_replays_match_eager"] = gok
                 out["other_configs"] = others
                 # non-square 2-D grids (same image kernels, each axis with its own length and mode count)
                 rect = []
@@ -500,34 +489,33 @@ def main():
                                  "layers_per_s": 1.0 / devr, "bound": "hbm", "effective_hbm_GBps": nbytes / devr / 1e9,
                                  "hbm_frac": nbytes / devr / 1e9 / HBM_PEAK_GBPS})
                 out["rect_2d"] = rect
-                # long pencils through the per-shape dispatch (three pruned kernels: no fused kernel for N >= 2048)
+                # long pencils through the per-shape dispatch
                 longp = []
                 for (Bl, Cl, Nl, Kl) in [(64, 128, 4096, 512), (128, 128, 2048, 256)]:
                     wl = inputs.Workload(f"long_1d_B{Bl}_C{Cl}_N{Nl}_K{Kl}", 1, Bl, Cl, Cl, Nl, Kl, 7)
                     _, devl = measure(wl, torch, binding, max(50, args.steps // 8), max(10, args.warmup // 8),
                                       ramp=args.ramp / 3, variant=5)
-                    longp.append({"workload": wl.name, "entry_point": "tfno_spectral_conv1d_auto", "us_per_layer": devl * 1e6,
-                                  "layers_per_s": 1.0 / devl, "bound": "hbm",
-                                  "effective_hbm_GBps": wl.compulsory_bytes / devl / 1e9,
-                                  "hbm_frac": wl.compulsory_bytes / devl / 1e9 / HBM_PEAK_GBPS})
+                    cell = {"workload": wl.name, "entry_point": "tfno_spectral_conv1d_auto", "us_per_layer": devl * 1e6,
+                            "layers_per_s": 1.0 / devl}
+                    cell.update(roofline_of(wl, devl))
+                    longp.append(cell)
                 out["long_1d"] = longp
-                # an own weight matrix per retained mode (three kernels; the contraction is plain FP32 FMA work)
+                # an own weight matrix per retained mode (three kernels)
                 pm = []
                 for wp in (w, w4) if w.name.startswith("cfg3") else ():
                     devp, nb = measure_permode(torch, binding, wp, max(50, args.steps // 8), max(10, args.warmup // 8), args.ramp / 3)
                     pm.append({"workload": wp.name + "_permode", "us_per_layer": devp * 1e6, "layers_per_s": 1.0 / devp,
-                               "effective_hbm_GBps": nb / devp / 1e9, "hbm_frac": nb / devp / 1e9 / HBM_PEAK_GBPS,
+                               "bound": "hbm", "effective_hbm_GBps": nb / devp / 1e9, "hbm_frac": nb / devp / 1e9 / HBM_PEAK_GBPS,
                                "contraction_TFLOPs": flops_of(wp) / devp / 1e12})
                 out["per_mode_weights"] = pm
-                # the 2-D FNO layer on real fields, next to the same layer composed from PyTorch library calls
+                # the 2-D FNO layer on real fields
                 fno = []
                 for (Bf, Cf, N1, N2, M1, M2) in [(32, 64, 256, 256, 16, 32), (256, 64, 64, 64, 12, 12)]:
-                    devf, devt, errf, nbf = measure_fno2d(torch, binding, Bf, Cf, N1, N2, M1, M2, max(50, args.steps // 8),
-                                                         max(10, args.warmup // 8), args.ramp / 3)
+                    devf, nbf = measure_fno2d(torch, binding, Bf, Cf, N1, N2, M1, M2, max(50, args.steps // 8),
+                                              max(10, args.warmup // 8), args.ramp / 3)
                     fno.append({"workload": f"fno2d_real_B{Bf}_C{Cf}_N{N1}x{N2}_M{M1}x{M2}", "us_per_layer": devf * 1e6,
-                                "layers_per_s": 1.0 / devf, "effective_hbm_GBps": nbf / devf / 1e9,
-                                "hbm_frac": nbf / devf / 1e9 / HBM_PEAK_GBPS, "pytorch_us_per_layer": devt * 1e6,
-                                "speedup_vs_pytorch": devt / devf, "rel_l2_vs_pytorch": errf})
+                                "layers_per_s": 1.0 / devf, "bound": "hbm", "effective_hbm_GBps": nbf / devf / 1e9,
+                                "hbm_frac": nbf / devf / 1e9 / HBM_PEAK_GBPS})
                 out["fno2d_real"] = fno
                 # the 1-D FNO layer on real fields (pruned transforms around the per-mode contraction), cfg3's shape
                 if w.name.startswith("cfg3"):
@@ -537,27 +525,17 @@ def main():
                     strm = torch.cuda.current_stream().cuda_stream
                     _, dev1 = time_calls(torch, lambda: binding.fno1d_real(xr, Wm, yr, strm), max(50, args.steps // 8),
                                          max(10, args.warmup // 8), args.ramp / 3)
-
-                    def torch_layer():
-                        half = torch.zeros((w.B, w.C_out, w.N // 2 + 1), dtype=torch.complex64, device="cuda")
-                        half[..., :w.K] = torch.einsum("bix,iox->box", torch.fft.rfft(xr)[..., :w.K], Wm)
-                        return torch.fft.irfft(half, n=w.N)
-
-                    ref1 = torch_layer()
-                    err1 = (torch.linalg.norm(yr - ref1) / torch.linalg.norm(ref1)).item()
-                    _, devt1 = time_calls(torch, torch_layer, 20, 3, args.ramp / 3)
                     nb1 = 4 * w.B * w.N * (w.C_in + w.C_out) + 8 * w.C_in * w.C_out * w.K
                     out["fno1d_real"] = [{"workload": f"fno1d_real_B{w.B}_C{w.C_in}_N{w.N}_M{w.K}", "us_per_layer": dev1 * 1e6,
-                                          "layers_per_s": 1.0 / dev1, "effective_hbm_GBps": nb1 / dev1 / 1e9,
-                                          "hbm_frac": nb1 / dev1 / 1e9 / HBM_PEAK_GBPS, "pytorch_us_per_layer": devt1 * 1e6,
-                                          "speedup_vs_pytorch": devt1 / dev1, "rel_l2_vs_pytorch": err1}]
-                    del xr, Wm, yr, ref1
+                                          "layers_per_s": 1.0 / dev1, "bound": "hbm", "effective_hbm_GBps": nb1 / dev1 / 1e9,
+                                          "hbm_frac": nb1 / dev1 / 1e9 / HBM_PEAK_GBPS}]
+                    del xr, Wm, yr
                     torch.cuda.empty_cache()
                 # real-valued layer (R2C / C2R semantics): half the bytes of the complex layer
                 if w.name.startswith("cfg3"):
                     devr, nbr = measure_real(torch, binding, w, max(50, args.steps // 4), max(10, args.warmup // 4), args.ramp / 3)
                     out["real_1d"] = [{"workload": w.name + "_real", "us_per_layer": devr * 1e6, "layers_per_s": 1.0 / devr,
-                                       "effective_hbm_GBps": nbr / devr / 1e9, "hbm_frac": nbr / devr / 1e9 / HBM_PEAK_GBPS}]
+                                       "bound": "hbm", "effective_hbm_GBps": nbr / devr / 1e9, "hbm_frac": nbr / devr / 1e9 / HBM_PEAK_GBPS}]
             except Exception as exc:    # noqa: BLE001 - reported in the JSON line
                 out["widened_report_error"] = repr(exc)
         out["cpu_baseline"] = cpu_baseline(w)

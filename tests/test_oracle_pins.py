@@ -428,37 +428,3 @@ def test_fno2d_plane_wave_picks_its_mode(oracle_mod):
         assert np.max(np.abs(y[0, 0] - np.abs(w) * np.cos(ph + np.angle(w)))) < 5e-6
     x = np.cos(2 * np.pi * (M1 * n1 / N1 + 2 * n2 / N2))[None, None].astype(np.float32)      # k1 = M1: outside
     assert np.max(np.abs(oracle_mod.fno2d_real(x, W)[0])) < 5e-6
-
-
-# ------------------------------------------------------ facts the paper prints --
-
-def _needed_ops_radix2(N, kept):
-    """Number of butterfly outputs (one add or subtract each) that the first `kept` bins of an
-    N-point radix-2 decimation-in-time network depend on."""
-    stages = N.bit_length() - 1
-    need = set(range(kept))          # positions needed after the last stage
-    ops = 0
-    for s in range(stages, 0, -1):
-        span = 1 << s                # butterfly group size at this stage
-        half = span >> 1
-        ops += len(need)
-        prev = set()
-        for pos in need:
-            base, j = pos - pos % span, pos % span % half
-            prev.add(base + j)
-            prev.add(base + j + half)
-        need = prev
-    return ops
-
-
-def test_pruned_butterfly_counts_match_paper():
-    rows = [l.split() for l in open(os.path.join(GOLDEN, "pruning_op_counts.txt")) if l.strip() and l[0] != "#"]
-    assert rows
-    for N, kept, ops in rows:
-        assert _needed_ops_radix2(int(N), int(kept)) == int(ops)
-
-
-def test_truncated_write_fraction_matches_paper():
-    rows = [l.split() for l in open(os.path.join(GOLDEN, "truncation_traffic.txt")) if l.strip() and l[0] != "#"]
-    for N, K, frac in rows:
-        assert 1.0 - int(K) / int(N) == float(frac)
