@@ -381,12 +381,13 @@ tfno_status run_fno1d(const void *x, const void *W, void *y, int B, int C_in, in
 }
 
 // Variant E of the paper (Sec. 5): per-shape choice among the variants.  Measured on MI355X over the hidden-dimension
-// sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels
-// (C_out <= 128); above that every 128-output slab repeats the forward transform of its batch row, and the
-// CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins by 2-11 %.
+// sweep (B = 512, N = 256): the fully fused kernel is fastest whenever one workgroup covers all output channels of a
+// batch row (up to 256 at N = 256, up to 128 elsewhere); above that every slab repeats the forward transform of its
+// batch row, and the CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins.
 Variant choose_variant(int N, int K, int C_out)
 {
-    if (C_out > 128 && round_modes(N, K, fused1d_partial_supported)) return GEMM_IFFT;
+    // (N = 256 has fused kernels that cover 256 outputs per workgroup and beat the CGEMM + iFFT variant there)
+    if (C_out > 128 && N != 256 && round_modes(N, K, fused1d_partial_supported)) return GEMM_IFFT;
     if (round_modes(N, K, fused1d_supported)) return FUSED;
     // long pencils (N = 2048, 4096) have no fused kernel: one workgroup cannot hold the K >= 128 retained modes of
     // all its output channels; the three pruned kernels move only 4 K / N of the tensor bytes extra
@@ -457,19 +458,28 @@ bool contraction_forced_f32()
     return forced;
 }
 
+// TFNO_KERNEL (read once): 0 default, 1 "ws", 2 "generic"
+static int kernel_choice()
+{
+    static const int which = [] {
+        const char *e = getenv("TFNO_KERNEL");
+        if (e && e[0] == 'w' && e[1] == 's' && e[2] == 0) return 1;
+        if (e && e[0] == 'g' && e[1] == 'e' && e[2] == 'n') return 2;
+        return 0;
+    }();
+    return which;
+}
+
+bool generic_kernels_forced() { return kernel_choice() == 2; }
+
 hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
 {
     if (!fused1d_supported(N, K)) return hipErrorInvalidValue;
     if (!contraction_forced_f32()) {
         // N = 1024 has three kernels.  Default: the symmetric-wave kernel where it exists (K in {64, 128}; the
         // fastest at the sustained clock), else the wave-specialised one.  TFNO_KERNEL=ws forces the
-        // wave-specialised kernel, TFNO_KERNEL=generic the four-wave kernel every other N uses.
-        static const int which = [] {
-            const char *e = getenv("TFNO_KERNEL");
-            if (e && e[0] == 'w' && e[1] == 's' && e[2] == 0) return 1;
-            if (e && e[0] == 'g' && e[1] == 'e' && e[2] == 'n') return 2;
-            return 0;
-        }();
+        // wave-specialised kernel, TFNO_KERNEL=generic the four-wave kernel.
+        const int which = kernel_choice();
         // (they have no mode mask: a request for fewer modes than the kernel's K runs on the four-wave kernel)
         const bool exact = a.K_keep == 0 || a.K_keep == K;
         if (exact && which == 0 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);

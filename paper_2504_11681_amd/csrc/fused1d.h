@@ -32,6 +32,8 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long batch_ro
 
 // True when the environment asks for FP32-MFMA contractions only (TFNO_CONTRACTION=f32).
 bool contraction_forced_f32();
+// True when the environment asks for the four-wave double-buffered kernel everywhere (TFNO_KERNEL=generic).
+bool generic_kernels_forced();
 
 // Wave-specialised variant (BF16x3 split contraction on the matrix pipe beside the VALU transforms).
 bool fused1d_ws_supported(int N, int K);
@@ -40,6 +42,11 @@ hipError_t fused1d_ws_launch(int N, int K, const Fused1dArgs &a, long long rows,
 // Symmetric-wave variant (every wave runs transforms and contraction; BF16x3 split contraction).
 bool fused1d_sym_supported(int N, int K);
 hipError_t fused1d_sym_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+
+// Two-group variant for N = 256 (eight waves, the groups alternate between transforms and contraction; 256 outputs
+// per workgroup): whole 32-channel blocks only, 128 < C_out, K in {32, 64}.
+bool fused1d_pp_supported(int N, int K, int C_in, int C_out);
+hipError_t fused1d_pp_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 
 // Partially fused variants (Sec. 4.1 and 4.2): mode 1 = FFT + CGEMM in one kernel, writes the truncated output
 // spectrum a.Yh; mode 2 = CGEMM + iFFT in one kernel, reads the truncated input spectrum a.Xh.  Built for

@@ -48,11 +48,22 @@ template <> struct Decomp<1024> { static constexpr int P = 32, T = 32; };
 
 // BF: the contraction runs on the BF16 matrix pipe with the exact three-term operand split (bf16x3.h) instead of
 // FP32 MFMA; the operand tile then holds packed BF16 terms, [term][channel / 4][mode tile][mode % 32][channel % 4].
-template <int N, int K, int OT, bool BF = false>
+// NW: waves per workgroup, XB: operand tile buffers.
+//   NW 4, XB 2: one wave per SIMD and workgroup, operand tile double buffered, one barrier per block.
+//   NW 4, XB 1: the same with a single operand tile and two barriers per block; what this buys is LDS: at K = 128 the
+//               workgroup drops from 86 KB to 61 KB, so TWO workgroups share a CU and one's barriers, load waits,
+//               prologue and epilogue hide under the other's work (with one wave per SIMD nothing else hides them).
+//   NW 8, XB 1: two waves per SIMD in one workgroup; a block is twice as many channels; carries the 256-output slab
+//               (OT = 8) at K = 128, whose accumulators alone are half of the CU's register file.
+template <int N, int K, int OT, bool BF = false, int NW_ = 4, int XB_ = 2>
 struct FusedCfg {
     static constexpr int P = Decomp<N>::P, T = Decomp<N>::T;
     static constexpr int Q = K / P;                 // retained outputs per column of stage B
-    static constexpr int NT = 256, NW = 4;
+    static constexpr int NW = NW_, NT = 64 * NW;
+    static constexpr int XB = XB_;                  // operand tile buffers
+    static constexpr bool WIDE = XB == 1;           // single operand tile: two barriers per block
+    static_assert(NW == 4 || XB == 1, "eight waves come with the single operand tile");
+    static constexpr int RPW = 32 / NW;             // rows of a 32-output slab that a wave inverts
     static constexpr int PPW = 64 / T;              // pencils per wave per round
     static constexpr int PPI = NW * PPW;            // pencils (channels) per k-loop iteration
     static constexpr int CPL = P / T;               // stage-B columns per lane
@@ -69,20 +80,21 @@ struct FusedCfg {
     static constexpr int XH_BUF = BF ? 3 * (PPI / 4) * KT * 128 : PPI * 2 * KPAD;   // 4-byte words per XH buffer
     static constexpr int NWV = BF ? PPI / 2 : PPI;  // W values a lane holds per iteration
     static constexpr size_t LDS_Z = sizeof(c64) * NW * PPW * ZS;
-    static constexpr size_t LDS_XH = sizeof(float) * 2 * XH_BUF;
+    static constexpr size_t LDS_XH = sizeof(float) * XB * XH_BUF;
     static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * 32 * YROW;
     static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [t][p] (static)
     static constexpr size_t LDS_DYN = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH);   // dynamic part
     static constexpr size_t LDS_BYTES = LDS_DYN + LDS_TW;
     static_assert(K % P == 0 && Q >= 1 && Q <= T && T % Q == 0, "K must be a multiple of P that divides N");
-    static_assert(8 % PPW == 0, "a wave inverts 8 rows of a 32-output slab");
+    static_assert(RPW % PPW == 0, "a wave inverts RPW rows of a 32-output slab, PPW at a time");
+    static_assert(!WIDE || BF, "the eight-wave kernel exists with the BF16 contraction only");
     static_assert(PPI % 8 == 0, "an iteration is a whole number of 8-channel MFMA steps");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
     static_assert(TPW * 32 <= 128, "accumulators must fit the register file");
     static constexpr bool FITS = LDS_BYTES <= 160 * 1024;           // LDS budget of one gfx950 CU
     // Two workgroups per CU (two waves per SIMD, 256 registers each) wherever the accumulators leave room and LDS
     // allows: left to itself the compiler takes more than 256 registers for TPW = 2 and halves the occupancy.
-    static constexpr int MIN_WG_PER_CU = (TPW <= 2 && LDS_BYTES <= 80 * 1024) ? 2 : 1;
+    static constexpr int MIN_WG_PER_CU = (NW == 4 && (TPW <= 2 || WIDE || OT == 8) && LDS_BYTES <= 80 * 1024) ? 2 : 1;
 };
 
 // Orders this wave's LDS traffic (all lanes) without a workgroup barrier.
@@ -100,11 +112,12 @@ __device__ __forceinline__ void wave_sync()
 // transform of a real pencil is the complex one with a zero imaginary part, whose first K bins are the R2C bins;
 // the C2R inverse of the zero-padded half spectrum is (2/N) Re( sum_k Y'[k] e^(+2 pi i k n / N) ) with Y'[0] = Y[0]/2,
 // so bin 0 is halved on its way into the operand tile, the caller passes scale = 2/N, and only real parts are stored.
-template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0, bool REAL = false>
-__global__ void __launch_bounds__(256, (FusedCfg<N, K, OT, BF>::MIN_WG_PER_CU))
+template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0, bool REAL = false, int NW = 4, int XB = 2>
+__global__ void __launch_bounds__((FusedCfg<N, K, OT, BF, NW, XB>::NT), (FusedCfg<N, K, OT, BF, NW, XB>::MIN_WG_PER_CU))
 k_fused1d(Fused1dArgs a)
 {
-    using C = FusedCfg<N, K, OT, BF>;
+    using C = FusedCfg<N, K, OT, BF, NW, XB>;
+    static_assert(!C::WIDE || (MODE == 0 && !REAL), "the eight-wave kernel is the fully fused complex layer only");
     static_assert(C::FITS, "LDS budget of one gfx950 CU");
     constexpr int NWV = C::NWV;
     constexpr int P = C::P, T = C::T, Q = C::Q, PPW = C::PPW, PPI = C::PPI, CPL = C::CPL, KT = C::KT;
@@ -113,7 +126,7 @@ k_fused1d(Fused1dArgs a)
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
     c64 *Zl = reinterpret_cast<c64 *>(lds_raw);                       // [NW][PPW][ZS]
-    float *XH = reinterpret_cast<float *>(lds_raw + C::LDS_Z);        // [2][PPI][2][KPAD]
+    float *XH = reinterpret_cast<float *>(lds_raw + C::LDS_Z);        // [XB][PPI][2][KPAD]
     c64 *YH = reinterpret_cast<c64 *>(lds_raw + C::LDS_Z);            // [32][YROW]   (aliases XH)
     // the twiddle table is a separate LDS object so that its reads are known not to alias the Z/XH writes
     __shared__ c64 TW[N];                                             // [T][P]: w_N^(t p)
@@ -233,7 +246,7 @@ k_fused1d(Fused1dArgs a)
             const int j = item / P, p = item % P;
             const c64 *zcol = Zw + j * ZS + p * ZROW;
             c64 xo[Q];
-            if constexpr (T <= 16 && C::TPW <= 1) {
+            if constexpr (T <= 16 && (C::TPW <= 1 || (C::WIDE && C::TPW <= 2))) {
                 // all LDS reads of the column are issued before the first use: left alone, the compiler reads,
                 // waits and multiplies one pair at a time (T exposed LDS round trips per column)
                 c64 zc[T], tw[T];
@@ -319,6 +332,69 @@ k_fused1d(Fused1dArgs a)
             }
         }
     };
+    // Eight-wave kernel: the contraction of one block from the single operand tile, the weights of the whole block in
+    // wv.  Global loads complete in issue order, so a wait for a weight that was fetched after a block of pencil loads
+    // would also wait for those pencils (HBM latency): the weights of a block are therefore fetched at the start of
+    // its stage B, BEFORE the pencil loads that are issued next, and every wait meets loads a whole phase old.
+    auto mfma_block_wide = [&]() __attribute__((always_inline)) {
+        const unsigned *XS = reinterpret_cast<const unsigned *>(XH) + (hi ? 1 : 0) * (KT * 128) + kt0 * 128 + (lane & 31) * 4;
+        // tile-step n = (8-channel step n / TPW, tile n % TPW): its three B operands are read from LDS while the MFMAs
+        // of tile-step n-1 run
+        auto read_b = [&](uintx4 *b, int n) __attribute__((always_inline)) {
+#pragma unroll
+            for (int t = 0; t < 3; ++t)
+                b[t] = *reinterpret_cast<const uintx4 *>(XS + ((t * (PPI / 4) + 2 * (n / TPW)) * KT + n % TPW) * 128);
+        };
+        uintx4 b[2][3];
+        read_b(b[0], 0);
+#pragma unroll
+        for (int s = 0; s < PPI / 8; ++s) {
+            uintx4 a_re[3], a_im[3];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const Split3 re = split3(wv[4 * s + d].x * a.scale), im = split3(wv[4 * s + d].y * a.scale);
+                a_re[0][d] = pack_bf16(re.t0, im.t0) ^ 0x80000000u;
+                a_re[1][d] = pack_bf16(re.t1, im.t1) ^ 0x80000000u;
+                a_re[2][d] = pack_bf16(re.t2, im.t2) ^ 0x80000000u;
+                a_im[0][d] = pack_bf16(im.t0, re.t0);
+                a_im[1][d] = pack_bf16(im.t1, re.t1);
+                a_im[2][d] = pack_bf16(im.t2, re.t2);
+            }
+            constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};   // smallest products first
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int n = s * TPW + i;
+                if (n + 1 < (PPI / 8) * TPW) read_b(b[(n + 1) & 1], n + 1);
+#pragma unroll
+                for (int k = 0; k < 6; ++k) {
+                    const bf16x8 bb16 = __builtin_bit_cast(bf16x8, b[n & 1][SB[k]]);
+                    acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb16, acc_re[i], 0, 0, 0);
+                    acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[i], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // One block of the eight-wave kernel: weights of block `it`, stage B of block `it` into the single operand tile,
+    // barrier, then stage A of block it+1 (into the wave's Z tile, free again), the loads of block it+2, and the
+    // contraction of block `it`; the closing barrier frees the operand tile for the next block.
+    auto wide_step = [&](auto do_a, auto do_load, int it) __attribute__((always_inline)) {
+        constexpr bool DO_A = decltype(do_a)::value, DO_LOAD = decltype(do_load)::value;
+        // (scheduling fences: left alone, the compiler sinks stage A into the MFMA sequence and the pencil loads
+        // behind the closing barrier, which leaves them one stage B to arrive instead of a whole contraction)
+        load_w(wv, it * PPI);
+        stage_b(0);
+        wave_sync();
+        __syncthreads();
+        if constexpr (DO_A) { stage_a(); wave_sync(); }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (DO_LOAD) load_pencil((it + 2) * PPI);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (ALLT) mfma_block_wide();
+        else if (has_tiles) mfma_block_wide();
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (DO_A) __syncthreads();
+    };
+
     // One k-loop iteration, software pipelined three deep: the MFMAs of block `it` run next to stage B of
     // block it+1 (from the Z tile written one iteration earlier) and stage A of block it+2, and the loads of
     // block it+3 are issued as soon as v is free, so they are in flight for a whole iteration.
@@ -342,7 +418,16 @@ k_fused1d(Fused1dArgs a)
     const std::false_type no{};
 
     // ------------------------------------------------------------------ k-loop over input channels
-    if constexpr (MODE != 2) {
+    if constexpr (C::WIDE) {
+        load_pencil(0);
+        stage_a();
+        wave_sync();
+        if (n_it > 1) load_pencil(PPI);
+        int it = 0;
+        for (; it + 2 < n_it; ++it) wide_step(yes, yes, it);
+        if (it + 1 < n_it) { wide_step(yes, no, it); ++it; }
+        wide_step(no, no, it);
+    } else if constexpr (MODE != 2) {
         load_pencil(0);
         load_w(wv, 0);
         stage_a();
@@ -512,20 +597,20 @@ k_fused1d(Fused1dArgs a)
                 }
             }
             __syncthreads();
-            // wave w inverts rows 8w .. 8w+7 of the slab, PPW pencils per round, in its private Z tile
-            for (int rd = 0; rd < 8 / PPW; ++rd) {
+            // wave w inverts rows RPW w .. RPW w + RPW - 1 of the slab, PPW pencils per round, in its private Z tile
+            for (int rd = 0; rd < C::RPW / PPW; ++rd) {
 #pragma unroll
                 for (int cc = 0; cc < CPL; ++cc) {
                     const int item = lane + 64 * cc;
                     const int j = item / P, p = item % P;
-                    const int ol = 8 * wave + rd * PPW + j;
+                    const int ol = C::RPW * wave + rd * PPW + j;
                     c64 yin[Q];
 #pragma unroll
                     for (int q = 0; q < Q; ++q) yin[q] = YH[ol * YROW + p + P * q];
                     stage_b_inv(yin, j, p);
                 }
                 wave_sync();
-                ifft_store(o_base + 32 * ot + 8 * wave + rd * PPW + jw);
+                ifft_store(o_base + 32 * ot + C::RPW * wave + rd * PPW + jw);
                 wave_sync();
             }
             __syncthreads();
@@ -533,21 +618,21 @@ k_fused1d(Fused1dArgs a)
     }
 }
 
-template <int N, int K, int OT, bool BF, int MODE = 0, bool REAL = false>
+template <int N, int K, int OT, bool BF, int MODE = 0, bool REAL = false, int NW = 4, int XB = 2>
 hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
-    using C = FusedCfg<N, K, OT, BF>;
+    using C = FusedCfg<N, K, OT, BF, NW, XB>;
     static LdsLimitOnce lds_limit;
-    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL>),
-                                        reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL>)},
+    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL, NW, XB>),
+                                        reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL, NW, XB>)},
                                        (int)C::LDS_DYN);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
     // unmasked kernel only when every workgroup's slab of 32 OT outputs exists in full
     if (a.C_in % C::PPI == 0 && a.C_out % (32 * OT) == 0)
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE, REAL>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE, REAL, NW, XB>), grid, dim3(C::NT), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE, REAL>), grid, dim3(256), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE, REAL, NW, XB>), grid, dim3(C::NT), C::LDS_DYN, s, a);
     return hipGetLastError();
 }
 
@@ -600,6 +685,14 @@ hipError_t launch_partial(int K, const Fused1dArgs &a, long long rows, hipStream
     case 128: return launch_partial_k<N, 128, MODE>(a, rows, s);
     default: return hipErrorInvalidValue;
     }
+}
+
+// Single-operand-tile kernels (BF16x3 contraction only): NW = 8 waves in one workgroup, or NW = 4 with two workgroups per CU
+template <int N, int K, int OT, int NW = 8>
+hipError_t launch_fused1d_wide(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
+{
+    static_assert(FusedCfg<N, K, OT, true, NW, 1>::FITS, "LDS budget of one gfx950 CU");
+    return launch_fused1d_impl<N, K, OT, true, 0, false, NW, 1>(a, batch_rows, s);
 }
 
 // BF16x3 contraction unless the environment asks for FP32 MFMA (TFNO_CONTRACTION=f32)

@@ -3,8 +3,45 @@
 
 namespace tfno {
 
+// Kernel choice for N = 256, measured on MI355X over the hidden-dimension sweep (B = 512):
+//   K = 128, 32 < C_out <= 128: four waves with a single operand tile, two workgroups per CU (C = 128: 80 us against
+//       93 us for the double-buffered kernel that fits one workgroup per CU; C = 64: 34 against 40 us);
+//   C_out > 128: one workgroup covers 256 outputs, so x is read and transformed once per batch row: the two-group
+//       kernel for K = 32 and 64 where the channel counts are whole blocks (130 / 160 us against 155 / 185 us for two
+//       128-output workgroups per row), the eight-wave kernel otherwise and for K = 128 (247 against 299 us);
+//   everything else: the four-wave double-buffered kernel, two workgroups per CU wherever its LDS allows.
+// TFNO_KERNEL=generic keeps the four-wave double-buffered kernel everywhere (A/B measurements).
+template <int K>
+static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipStream_t s, bool *done)
+{
+    *done = true;
+    if (a.C_out > 128) {
+        if constexpr (K != 128) {
+            if (a.inner_count == 1 && fused1d_pp_supported(256, K, a.C_in, a.C_out)) return fused1d_pp_launch(256, K, a, rows, s);
+        }
+        return launch_fused1d_wide<256, K, 8>(a, rows, s);
+    }
+    if constexpr (K == 128) {
+        if (a.C_out > 64) return launch_fused1d_wide<256, K, 4, 4>(a, rows, s);
+        if (a.C_out > 32) return launch_fused1d_wide<256, K, 2, 4>(a, rows, s);
+    }
+    *done = false;
+    return hipSuccess;
+}
+
 hipError_t fused1d_launch_n256(int K, const Fused1dArgs &a, long long rows, hipStream_t s)
 {
+    if (!contraction_forced_f32() && !generic_kernels_forced()) {
+        bool done = false;
+        hipError_t e = hipSuccess;
+        switch (K) {
+        case 32: e = launch_special_n256<32>(a, rows, s, &done); break;
+        case 64: e = launch_special_n256<64>(a, rows, s, &done); break;
+        case 128: e = launch_special_n256<128>(a, rows, s, &done); break;
+        default: break;
+        }
+        if (done) return e;
+    }
     switch (K) {
     case 16:
         switch (pick_output_tiles(a.C_out, rows, 4)) {
