@@ -39,7 +39,8 @@ struct SymCfg {
     static constexpr int TPW = KT / 2;              // mode tiles per wave
     static constexpr int OPL = KH / 4;              // retained bins per lane after the quad reduction
     static constexpr int PATCH = 16 * 64;           // complex elements of one wave's transpose patch
-    static constexpr int XS_BUF = 3 * 2 * KT * 128; // dwords per operand buffer: [term][g][tile][n][d]
+    static constexpr int XT = K == 128 ? 144 : 160; // dwords between mode tiles of the operand buffer (128 + pad, see row_stage)
+    static constexpr int XS_BUF = 3 * 2 * KT * XT;  // dwords per operand buffer: [term][g][tile][d][n]
     static constexpr int YH_BUF = 8 * K;            // complex elements per spectrum buffer: [pencil][mode]
     static constexpr size_t LDS_PATCH = sizeof(c64) * NW * PATCH;
     static constexpr size_t LDS_XS = sizeof(unsigned) * 2 * XS_BUF;
@@ -82,7 +83,10 @@ k_fused1d_sym(Fused1dArgs a)
     c64 *patch = patch_all + wave * C::PATCH;
     const int p = lane;                                 // row-stage identity
     const int kl = lane >> 2, qa = lane & 3;            // column-stage identity: column k_lo, quad position
-    const int swz = 4 * (kl & 3);                       // patch entry (k_lo, p) lives at k_lo*64 + (p ^ 4(k_lo & 3))
+    // patch entry (k_lo, p) lives at k_lo*64 + (p ^ 4(k_lo & 7)): a half wave of the column stage reads rows k_lo = 0..7
+    // at positions qa + 4 p', which the swizzle spreads over all 32 eight-byte bank pairs (with k_lo & 3 rows k_lo and
+    // k_lo + 4 met in one pair)
+    const int swz = 4 * (kl & 7);
     const int g = lane >> 5, nn = lane & 31;            // MFMA identity
     const int slab = wave >> 1;                         // 32-output slab of this wave
     const int tile0 = (wave & 1) * TPW;                 // first mode tile of this wave
@@ -162,8 +166,8 @@ k_fused1d_sym(Fused1dArgs a)
                 const int c0 = 2 * k, c1 = 2 * k + 1;       // z[2k] = za[k], z[2k+1] = zo[k]
                 const c64 t0 = c0 == 0 ? za[0] : cmul(za[k], TW[c0 * 64 + p]);
                 const c64 t1 = cmul(zo[k], TW[c1 * 64 + p]);
-                patch[c0 * 64 + (p ^ (4 * (c0 & 3)))] = t0;
-                patch[c1 * 64 + (p ^ (4 * (c1 & 3)))] = t1;
+                patch[c0 * 64 + (p ^ (4 * (c0 & 7)))] = t0;
+                patch[c1 * 64 + (p ^ (4 * (c1 & 7)))] = t1;
             }
         }
         if constexpr (REFILL && DEEP) {
@@ -198,25 +202,32 @@ k_fused1d_sym(Fused1dArgs a)
                 O[i] = make_float2(mine.x + sym_quad_perm<0xB1>(send.x), mine.y + sym_quad_perm<0xB1>(send.y));
             }
         }
-        // bin k = k_lo + 16 (OPL qa + i)  ->  XS[buf][term][wave / 4][k / 32][k % 32][wave % 4]
-        unsigned *dst = XS + buf * C::XS_BUF + (wave >> 2) * (KT * 128) + (wave & 3);
+        // bin k = k_lo + 16 (OPL qa + i)  ->  XS[buf][term][wave / 4][k / 32][wave % 4][k % 32]
+        // Planar in the channel slot d = wave % 4: a wave stores ONE slot of every mode, so with the slot innermost
+        // ([n][d]) its 64 dword stores could reach 16 banks only.  Here lane (k_lo, qa) stores at position k_lo (+ 16)
+        // of tile qa (K = 128) or qa / 2 (K = 64); the tile stride of 128 + 16 (K = 128) or 128 + 32 (K = 64) dwords
+        // turns (k_lo, qa) into 64 different banks.
+        unsigned *dst = XS + buf * C::XS_BUF + (wave >> 2) * (KT * C::XT) + (wave & 3) * 32;
 #pragma unroll
         for (int i = 0; i < OPL; ++i) {
             const int k = kl + 16 * (OPL * qa + i);
             const Split3 re = split3(O[i].x), im = split3(O[i].y);
-            unsigned *d = dst + (k >> 5) * 128 + (k & 31) * 4;
-            d[0 * 2 * KT * 128] = pack_bf16(re.t0, im.t0);
-            d[1 * 2 * KT * 128] = pack_bf16(re.t1, im.t1);
-            d[2 * 2 * KT * 128] = pack_bf16(re.t2, im.t2);
+            unsigned *d = dst + (k >> 5) * C::XT + (k & 31);
+            d[0 * 2 * KT * C::XT] = pack_bf16(re.t0, im.t0);
+            d[1 * 2 * KT * C::XT] = pack_bf16(re.t1, im.t1);
+            d[2 * 2 * KT * C::XT] = pack_bf16(re.t2, im.t2);
         }
     };
     auto mfma_block = [&](int buf) __attribute__((always_inline)) {
-        const unsigned *src = XS + buf * C::XS_BUF + (g * KT + tile0) * 128 + nn * 4;
+        const unsigned *src = XS + buf * C::XS_BUF + (g * KT + tile0) * C::XT + nn;
         uintx4 b[TPW][3];
 #pragma unroll
         for (int i = 0; i < TPW; ++i)
 #pragma unroll
-            for (int t = 0; t < 3; ++t) b[i][t] = *reinterpret_cast<const uintx4 *>(src + t * 2 * KT * 128 + i * 128);
+            for (int t = 0; t < 3; ++t) {
+                const unsigned *q = src + t * 2 * KT * C::XT + i * C::XT;
+                b[i][t] = uintx4{q[0], q[32], q[64], q[96]};    // the four channel slots of mode nn
+            }
         // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
         constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
 #pragma unroll
@@ -313,7 +324,7 @@ k_fused1d_sym(Fused1dArgs a)
         c64 z[16], res[16];
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
-            c64 t = patch[c * 64 + (p ^ (4 * (c & 3)))];
+            c64 t = patch[c * 64 + (p ^ (4 * (c & 7)))];
             if (c != 0) {
                 const c64 w = TW[c * 64 + p];
                 t = cmul(t, make_float2(w.x, -w.y));
