@@ -4,8 +4,9 @@
 namespace tfno {
 
 // Kernel choice for N = 256, measured on MI355X over the hidden-dimension sweep (B = 512):
-//   K = 128, 32 < C_out <= 128: four waves with a single operand tile, two workgroups per CU (C = 128: 80 us against
-//       93 us for the double-buffered kernel that fits one workgroup per CU; C = 64: 34 against 40 us);
+//   K = 128, C_out <= 128, more batch rows than CUs: four waves with a single operand tile, two workgroups per CU
+//       (C = 128: 80 us against 93 us for the double-buffered kernel that fits one workgroup per CU; C = 64: 34
+//       against 40 us; C = 32: 16 against 21 us);
 //   C_out > 128: one workgroup covers 256 outputs, so x is read and transformed once per batch row: the two-group
 //       kernel for K = 32 and 64 where the channel counts are whole blocks (130 / 160 us against 155 / 185 us for two
 //       128-output workgroups per row), the eight-wave kernel otherwise and for K = 128 (247 against 299 us);
@@ -22,8 +23,13 @@ static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipS
         return launch_fused1d_wide<256, K, 8>(a, rows, s);
     }
     if constexpr (K == 128) {
-        if (a.C_out > 64) return launch_fused1d_wide<256, K, 4, 4>(a, rows, s);
-        if (a.C_out > 32) return launch_fused1d_wide<256, K, 2, 4>(a, rows, s);
+        // (two workgroups per CU need more batch rows than CUs; below that the double-buffered kernel's single
+        // barrier per block is the better deal)
+        if (rows > 256) {
+            if (a.C_out > 64) return launch_fused1d_wide<256, K, 4, 4>(a, rows, s);
+            if (a.C_out > 32) return launch_fused1d_wide<256, K, 2, 4>(a, rows, s);
+            return launch_fused1d_wide<256, K, 1, 4>(a, rows, s);
+        }
     }
     *done = false;
     return hipSuccess;

@@ -148,8 +148,9 @@ k_fused1d_sym(Fused1dArgs a)
     // registers (after the patch writes): two blocks of loads per wave, 128 KB per CU, are then in flight, which
     // the loaded HBM latency needs; one block (64 KB) leaves the k-loop waiting for memory.
     // REFILL, not DEEP: v is reloaded with the next block right after the first butterfly level.
-    auto row_stage = [&](c64 *v, int buf, auto refill, int refill_c0) __attribute__((always_inline)) {
+    auto row_stage = [&](c64 *v, int buf, auto refill, int refill_c0, auto &&hook) __attribute__((always_inline)) {
         constexpr bool REFILL = decltype(refill)::value;
+        hook(std::integral_constant<int, 0>{});
         {
             c64 ea[8], eb[8], za[8], zo[8];
             dif_first_level<16, -1>(v, ea, eb);
@@ -160,7 +161,9 @@ k_fused1d_sym(Fused1dArgs a)
             }
             RegFFT<8, -1, 1>::run(ea, za);
             RegFFT<8, -1, 1>::run(eb, zo);
+            hook(std::integral_constant<int, 10>{});
             wave_sync();                                    // the previous pencil's patch reads are done
+            hook(std::integral_constant<int, 1>{});
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int c0 = 2 * k, c1 = 2 * k + 1;       // z[2k] = za[k], z[2k+1] = zo[k]
@@ -170,12 +173,14 @@ k_fused1d_sym(Fused1dArgs a)
                 patch[c1 * 64 + (p ^ (4 * (c1 & 7)))] = t1;
             }
         }
+        hook(std::integral_constant<int, 11>{});
         if constexpr (REFILL && DEEP) {
             __builtin_amdgcn_sched_barrier(0);
             load_pencil(v, refill_c0);
             __builtin_amdgcn_sched_barrier(0);
         }
         wave_sync();
+        hook(std::integral_constant<int, 2>{});
         // lane (k_lo, qa): entries p = qa + 4 p', p' < 16, of column k_lo
         c64 P[KH];
         dft_prune_out<16, KH, -1>([&](auto ppc) __attribute__((always_inline)) {
@@ -217,6 +222,7 @@ k_fused1d_sym(Fused1dArgs a)
             d[1 * 2 * KT * C::XT] = pack_bf16(re.t1, im.t1);
             d[2 * 2 * KT * C::XT] = pack_bf16(re.t2, im.t2);
         }
+        hook(std::integral_constant<int, 12>{});
     };
     auto mfma_block = [&](int buf) __attribute__((always_inline)) {
         const unsigned *src = XS + buf * C::XS_BUF + (g * KT + tile0) * C::XT + nn;
@@ -239,14 +245,58 @@ k_fused1d_sym(Fused1dArgs a)
                 acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[i], 0, 0, 0);
             }
     };
-    // one k-loop iteration: contraction of block `it`, row stage of block it + 1 (held in v), W of block it + 1
+    // one k-loop iteration: contraction of block `it`, row stage of block it + 1 (held in v), W of block it + 1.
+    // The 12 TPW MFMAs of the block are spread over the three stretches of the row stage (between its wave-level LDS
+    // synchronisations) and interleaved with its vector instructions by an explicit pattern: a wave that issues the
+    // contraction and then the transforms pays the sum of both, and both waves of a SIMD reach the contraction
+    // together after the barrier, so without the pattern the matrix pipe runs while the vector ALU idles and vice
+    // versa.  (Contraction first: it does not depend on the loads in flight, so the row stage, which starts by
+    // waiting for them, still meets them as late as possible.)
+    auto no_hook = [](auto) __attribute__((always_inline)) {};
     auto body = [&](int it, c64 *v, auto refill) __attribute__((always_inline)) {
         load_w((it + 1) * PPI);
-        // contraction first in every wave: it does not depend on the loads in flight, so the row stage, which
-        // starts by waiting for them, comes as late as possible (alternating the order between the two waves of
-        // a SIMD, meant to overlap matrix and vector work, measured 4 % slower)
-        mfma_block(it & 1);
-        row_stage(v, (it + 1) & 1, refill, (it + (DEEP ? 3 : 2)) * PPI);
+        const unsigned *src = XS + (it & 1) * C::XS_BUF + (g * KT + tile0) * C::XT + nn;
+        uintx4 b[TPW][3];
+        constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};      // smallest products first
+        auto products = [&](int k0, int k1) __attribute__((always_inline)) {
+#pragma unroll
+            for (int k = k0; k < k1; ++k)
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const bf16x8 bb16 = __builtin_bit_cast(bf16x8, b[i][SB[k]]);
+                    acc_re[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb16, acc_re[i], 0, 0, 0);
+                    acc_im[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb16, acc_im[i], 0, 0, 0);
+                }
+        };
+        auto pattern = [&](auto mfmas, auto valu_per_mfma) __attribute__((always_inline)) {
+            static_for<0, decltype(mfmas)::value>([&](auto) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, decltype(valu_per_mfma)::value, 0);
+            });
+        };
+        row_stage(v, (it + 1) & 1, refill, (it + (DEEP ? 3 : 2)) * PPI, [&](auto rc) __attribute__((always_inline)) {
+            constexpr int R = decltype(rc)::value;
+            if constexpr (R == 0) {
+#pragma unroll
+                for (int i = 0; i < TPW; ++i)
+#pragma unroll
+                    for (int t = 0; t < 3; ++t) {
+                        const unsigned *q = src + t * 2 * KT * C::XT + i * C::XT;
+                        b[i][t] = uintx4{q[0], q[32], q[64], q[96]};        // the four channel slots of mode nn
+                    }
+                products(0, 2);
+            } else if constexpr (R == 10) {
+                pattern(std::integral_constant<int, 4 * TPW>{}, std::integral_constant<int, 20>{});
+            } else if constexpr (R == 1) {
+                products(2, 3);
+            } else if constexpr (R == 11) {
+                pattern(std::integral_constant<int, 2 * TPW>{}, std::integral_constant<int, 20>{});
+            } else if constexpr (R == 2) {
+                products(3, 6);
+            } else if constexpr (R == 12) {
+                pattern(std::integral_constant<int, 6 * TPW>{}, std::integral_constant<int, 18>{});
+            }
+        });
         split_w();
         __syncthreads();
     };
@@ -263,10 +313,10 @@ k_fused1d_sym(Fused1dArgs a)
     if (tid < 64) TW64[tid] = cis2pi(-(float)tid, 64.f);
     __syncthreads();                                        // twiddle tables are ready
     if constexpr (DEEP) {
-        row_stage(va, 0, yes, 2 * PPI);
+        row_stage(va, 0, yes, 2 * PPI, no_hook);
     } else {
-        if (n_it > 1) row_stage(va, 0, yes, PPI);
-        else row_stage(va, 0, no, 0);
+        if (n_it > 1) row_stage(va, 0, yes, PPI, no_hook);
+        else row_stage(va, 0, no, 0, no_hook);
     }
     split_w();
     __syncthreads();                                        // XS[0] holds block 0
