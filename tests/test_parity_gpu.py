@@ -778,6 +778,35 @@ def test_wide_output_slabs_with_ragged_channels(gpu, oracle_mod):
             close(got, wantr, "real layer")
 
 
+# N = 256 has three more fused kernels behind the dispatch: the single-operand-tile kernel (K = 128, more batch rows
+# than CUs; two workgroups per CU), the eight-wave kernel and the two-group kernel (C_out > 128: 256 outputs per
+# workgroup).  Shapes that reach each of them with whole and ragged channel blocks, absent output slabs and mode counts
+# between the built sizes.  (B, C_in, C_out, N, K)
+N256_SPECIAL = [
+    (300, 5, 70, 256, 128),      # single tile, masked, 128-output slab partly empty
+    (260, 20, 33, 256, 100),     # single tile, masked, 64-output slab, K rounded up to 128
+    (257, 9, 30, 256, 128),      # single tile, masked, 32-output slab
+    (258, 16, 64, 256, 128),     # single tile, whole blocks
+    (3, 64, 256, 256, 48),       # two-group kernel, K rounded up to 64
+    (2, 64, 160, 256, 64),       # two-group kernel, three of eight output slabs absent
+    (2, 96, 192, 256, 32),       # two-group kernel, six 16-channel blocks
+    (2, 128, 256, 256, 128),     # eight-wave kernel, whole blocks
+    (2, 70, 200, 256, 128),      # eight-wave kernel, masked
+    (2, 48, 136, 256, 32),       # eight-wave kernel (48 channels are not whole 32-channel blocks), masked
+]
+
+
+@pytest.mark.parametrize("shape", N256_SPECIAL, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
+def test_n256_dispatched_kernels(gpu, oracle_mod, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] N = 256 dispatch {shape}")
+    x = inputs.make_x(2400 + Ci + K, B, Ci, (N,))
+    W = inputs.make_W(2400 + Ci + K, Ci, Co)
+    want, _ = oracle_mod.spectral_conv1d(x, W, K)
+    check(run_gpu(gpu, "spectral_conv1d", x, W, K), want, "fused")
+    check(run_gpu(gpu, "spectral_conv1d_auto", x, W, K), want, "auto")
+
+
 def test_round_trip_identity_and_determinism(gpu):
     """K = N, W = I gives y = x; two runs give bitwise equal output."""
     torch, binding = gpu
