@@ -307,6 +307,29 @@ def cpu_baseline(w):
                       f"each on {int(used)} threads; layers/s scaled by {nb}/{w.B}"}
 
 
+def stream_copy_rate(torch, nbytes, steps=200):
+    """What the machine streams when it reads and writes at the same time, as the fused layer does: a plain
+    device-to-device copy of `nbytes` (torch's copy_, i.e. the runtime's copy kernel) through rotating buffer pairs
+    totalling at least 1 GiB, timed with events like the layers.  Context for roofline.frac, not part of the path."""
+    sets = max(2, -(-(1 << 30) // (2 * nbytes)))
+    src = [torch.ones(nbytes, dtype=torch.uint8, device="cuda") for _ in range(sets)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(sets)]
+    for i in range(20):
+        dst[i % sets].copy_(src[i % sets])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        dst[i % sets].copy_(src[i % sets])
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) / 1e3 / steps
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"kernel": "device-to-device copy (reads and writes at once)", "bytes_read": nbytes, "bytes_written": nbytes,
+            "us_per_copy": sec * 1e6, "GBps": 2 * nbytes / sec / 1e9, "frac_of_peak": 2 * nbytes / sec / 1e9 / HBM_PEAK_GBPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -406,8 +429,8 @@ def main():
             e["median_launch_ms"], e["min_launch_ms"] = stats["median_s"] * 1e3, stats["min_s"] * 1e3
         return e
 
-    kernel_1d = ("k_fused1d_sym (N = 1024, K in {64, 128}), k_fused1d_wide (N = 256, eight waves), k_fused1d_ws / "
-                 "k_fused1d otherwise")
+    kernel_1d = ("k_fused1d_sym (N = 1024, K in {64, 128}); N = 256: k_fused1d with four waves (one or two operand "
+                 "tiles) or eight waves, k_fused1d_pp for C_out > 128 and K <= 64; k_fused1d_ws / k_fused1d otherwise")
     out = {
         "metric": "fused_spectral_conv_layers_per_s",
         "value": layers_per_s,
@@ -434,6 +457,9 @@ def main():
     }
 
     if not args.no_extras:
+        out["stream_copy"] = stream_copy_rate(torch, alg_bytes // 2)
+        out["stream_copy"]["fused_time_over_copy_time"] = (
+            (wall / args.steps) / (alg_bytes / (out["stream_copy"]["GBps"] * 1e9)))
         s_steps = max(5, args.steps // 10)
         swall, sdev = measure(w, torch, binding, s_steps, 2, staged=True, ramp=args.ramp)
         out["staged"] = {"ms_per_step": swall / s_steps * 1e3, "layers_per_s": s_steps / swall,

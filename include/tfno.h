@@ -72,7 +72,9 @@ typedef enum {
  *
  *   y[b,o,:] = iFFT_N( pad_N( sum_c trunc_K( FFT_N(x[b,c,:]) ) * W[c,o] ) )
  *
- * One kernel launch; the spectra never leave the chip.  Needs no workspace.
+ * One kernel launch; the spectra never leave the chip.  Needs no workspace.  Which instantiation runs (workgroups of
+ * four or eight waves, 128 or 256 outputs per workgroup, one or two operand tiles) is chosen from the shape and does
+ * not change the result beyond the order of floating-point accumulation.
  * Built sizes of the fused kernel: K a power of two, 8..64 for N = 64, 16..128 for N = 128, 16..256 for N = 256,
  * 32..256 for N = 512 and N = 1024 (K = N allowed where listed); every smaller K runs on the next built size (see
  * "Mode counts" above).  Other valid shapes: TFNO_ERR_UNSUPPORTED (use the staged entry point or
@@ -251,9 +253,9 @@ tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y
 
 /*
  * Per-shape dispatch (variant "E" of Table 2, Sec. 5: the best of the variants for each shape), with the rule
- * measured on MI355X: the CGEMM + iFFT variant when C_out > 128 and that variant exists for (N, K) (the fully
- * fused kernel repeats the forward transform for every 128-output slab), else the fully fused kernel where one
- * exists, else the three pruned kernels of tfno_spectral_conv1d_pruned where they exist (N = 2048, 4096), else the
+ * measured on MI355X: the CGEMM + iFFT variant when C_out > 128, N != 256 and that variant exists for (N, K) (there
+ * the fully fused kernel repeats the forward transform for every 128-output slab; at N = 256 it covers 256 outputs
+ * per workgroup and is the fastest variant), else the fully fused kernel where one exists, else the three pruned kernels of tfno_spectral_conv1d_pruned where they exist (N = 2048, 4096), else the
  * staged path.  Accepts every valid 1-D shape; same contract and same result as
  * tfno_spectral_conv1d.  Workspace: tfno_workspace_bytes(1, 5, ...) bytes (0 when the fused kernel is chosen).
  */
