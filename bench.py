@@ -408,7 +408,10 @@ def main():
         if not os.path.exists(tpath):
             return None, None
         e = json.load(open(tpath)).get(name, {})
-        return e.get("hbm_bytes_per_launch"), e.get("source")
+        src = e.get("source")
+        if src and e.get("kernel"):
+            src += ", kernel " + e["kernel"]
+        return e.get("hbm_bytes_per_launch"), src
 
     def roofline_entry(wk, devk, kernel, stats=None):
         r = roofline_of(wk, devk)
