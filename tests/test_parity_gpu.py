@@ -317,7 +317,9 @@ def test_2d_rect_square_case_is_bitwise_the_square_entry_point(gpu):
 PERMODE_1D = [(4, 16, 16, 64, 16), (19, 5, 7, 64, 64), (9, 33, 40, 128, 32), (3, 9, 70, 128, 128), (17, 6, 18, 256, 256),
               (1, 1, 1, 256, 16), (2, 20, 30, 1024, 64), (11, 13, 17, 1024, 128), (8, 3, 2, 256, 128),
               # mode counts between the built sizes (weights hold exactly K matrices)
-              (3, 5, 7, 64, 12), (9, 9, 4, 256, 100), (4, 6, 6, 1024, 72), (2, 3, 3, 128, 1)]
+              (3, 5, 7, 64, 12), (9, 9, 4, 256, 100), (4, 6, 6, 1024, 72), (2, 3, 3, 128, 1),
+              # batches and output counts that fill 64 x 64 tiles per mode (ragged last tiles, channel mask, surplus modes)
+              (250, 16, 128, 256, 128), (256, 9, 120, 256, 100)]
 
 
 @pytest.mark.parametrize("shape", PERMODE_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
@@ -337,7 +339,8 @@ def test_1d_permode(gpu, oracle_mod, shape):
 
 # (B, C_in, C_out, N1, N2, K1, K2)
 PERMODE_2D = [(2, 3, 5, 64, 64, 16, 16), (9, 5, 33, 128, 64, 32, 16), (1, 4, 3, 256, 256, 64, 64), (10, 2, 2, 64, 256, 16, 64),
-              (3, 17, 9, 128, 128, 64, 32), (2, 3, 4, 64, 128, 12, 20), (9, 2, 3, 256, 64, 33, 5)]
+              (3, 17, 9, 128, 128, 64, 32), (2, 3, 4, 64, 128, 12, 20), (9, 2, 3, 256, 64, 33, 5),
+              (120, 20, 112, 64, 64, 16, 16)]
 
 
 @pytest.mark.parametrize("shape", PERMODE_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
