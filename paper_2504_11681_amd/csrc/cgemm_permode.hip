@@ -18,7 +18,13 @@ hipError_t cgemm_permode_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, 
     if (M % 128 == 0 && TPI == M / 128 && C_in >= 16 && C_out >= 16 && per >= 16 && !contraction_forced_f32() &&
         (per + 31) / 32 <= 65535 && (C_out + 31) / 32 <= 65535) {
         const dim3 grid((unsigned)(TPI * 16), (unsigned)((per + 31) / 32), (unsigned)((C_out + 31) / 32));
-        hipLaunchKernelGGL(k_cgemm_permode_mfma, grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale, K2p, K1a, K2a);
+        // without masks where every tile is full and the extents a workgroup addresses with 32-bit offsets (32 batch
+        // elements of Xh, all of W) stay below 2^31 bytes
+        const bool fits32 = 32LL * TPI * C_in * 1024 < (1LL << 31) && (long long)C_in * C_out * K1a * K2a * 8 < (1LL << 31);
+        if (per % 32 == 0 && C_out % 32 == 0 && C_in % 8 == 0 && fits32)
+            hipLaunchKernelGGL(k_cgemm_permode_mfma<true>, grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale, K2p, K1a, K2a);
+        else
+            hipLaunchKernelGGL(k_cgemm_permode_mfma<false>, grid, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, M, num_tiles, TPI, scale, K2p, K1a, K2a);
         return hipGetLastError();
     }
     constexpr int OT = 8;

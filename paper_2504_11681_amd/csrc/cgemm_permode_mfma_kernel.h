@@ -38,6 +38,9 @@ struct PermodeMfma {
     static_assert(16 * 32 * YROW * 2 <= 2 * TILE, "the epilogue tile aliases the operand tiles");
 };
 
+// FULL: 32 batch elements, 32 outputs and a multiple of 8 channels per workgroup -- no masks, and every row is
+// addressed as a uniform pointer plus one lane offset.
+template <bool FULL>
 __global__ void __launch_bounds__(256, 2)
 k_cgemm_permode_mfma(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh, int C_in, int C_out,
                      int M, long long num_tiles, int TPI, float scale, int K2p, int K1a, int K2a)
@@ -77,8 +80,9 @@ k_cgemm_permode_mfma(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 
     // W: pass p holds channel 4 ((4 p + wave) % 2) + wcq, output 2 ((4 p + wave) / 2) + wol.
     // Row pointers are set up once (rows outside the problem point at a valid row and are zeroed after the load);
     // a step adds a constant to them: per-load 64-bit address arithmetic was a third of the kernel's instructions.
-    uintx4 xr2[2][4];
-    c64 wr2[2][8];
+    constexpr int D = 2;                        // steps of values in flight (three measured no faster)
+    uintx4 xr2[D][4];
+    c64 wr2[D][8];
     const uintx4 *xrow[4];
     bool xok[4];
 #pragma unroll
@@ -98,18 +102,33 @@ k_cgemm_permode_mfma(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 
     }
     const long long wstep = (long long)C_out * Ma;      // one channel further in W
     const bool c_even = C_in % 8 == 0;                  // no channel masks needed
+    // FULL: batch 2 (4 p + wave) + xbl = 8 p + 2 wave + xbl; channel 4 (wave % 2) + wcq, output 4 p + 2 (wave / 2) + wol
+    const int bstride = TPI * C_in * 64;                                        // uintx4 between batch elements
+    const uintx4 *xbase = reinterpret_cast<const uintx4 *>(Xh + ((r + (long long)TPI * b0) * C_in) * 128 + i0) + 2 * wave * bstride;
+    const c64 *wbase = W + ((long long)(4 * (wave & 1)) * C_out + o0 + 2 * (wave >> 1)) * Ma;
+    const unsigned xlane = (unsigned)((xbl * TPI * C_in + 4 * xch + xcq) * 64 + xq);
+    const unsigned wlane = (unsigned)((wcq * C_out + wol) * Ma + w_mode);
     auto fetch = [&](uintx4 *xr, c64 *wr, int c0) __attribute__((always_inline)) {
-        const bool cx = c_even || c0 + 4 * xch + xcq < C_in;
+        if constexpr (FULL) {
+            const uintx4 *xs = xbase + c0 * 64;
+            const c64 *ws = wbase + (size_t)c0 * (size_t)wstep;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uintx4 v = xrow[p][cx ? (long long)c0 * 64 : 0];          // 64 uintx4 = 128 c64 per channel
-            xr[p] = (cx && xok[p]) ? v : uintx4{0u, 0u, 0u, 0u};
-        }
+            for (int p = 0; p < 4; ++p) xr[p] = xs[xlane + (unsigned)(8 * p * bstride)];
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const bool cw = c_even || c0 + 4 * ((4 * p + wave) & 1) + wcq < C_in;
-            const c64 v = wrow[p][cw ? c0 * wstep : 0];
-            wr[p] = (cw && wok[p]) ? v : make_float2(0.f, 0.f);
+            for (int p = 0; p < 8; ++p) wr[p] = ws[wlane + (unsigned)(4 * p * Ma)];
+        } else {
+            const bool cx = c_even || c0 + 4 * xch + xcq < C_in;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uintx4 v = xrow[p][cx ? (long long)c0 * 64 : 0];          // 64 uintx4 = 128 c64 per channel
+                xr[p] = (cx && xok[p]) ? v : uintx4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const bool cw = c_even || c0 + 4 * ((4 * p + wave) & 1) + wcq < C_in;
+                const c64 v = wrow[p][cw ? c0 * wstep : 0];
+                wr[p] = (cw && wok[p]) ? v : make_float2(0.f, 0.f);
+            }
         }
     };
     auto put3 = [&](unsigned *d, float re_, float im_) __attribute__((always_inline)) {
@@ -140,18 +159,18 @@ k_cgemm_permode_mfma(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 
         for (int k = 0; k < 16; ++k) { acc_re[i][k] = 0.f; acc_im[i][k] = 0.f; }
 
     const int n_steps = (C_in + 7) / 8;
-    fetch(xr2[0], wr2[0], 0);
-    fetch(xr2[1], wr2[1], n_steps > 1 ? 8 : 0);
+#pragma unroll
+    for (int e = 0; e < D; ++e) fetch(xr2[e], wr2[e], 8 * (e < n_steps ? e : n_steps - 1));
     // (steps in pairs so that the register set of a step is a compile-time choice; past the end a fetch repeats the
     // last step and is dropped)
-    for (int s2 = 0; s2 < n_steps; s2 += 2) {
+    for (int s2 = 0; s2 < n_steps; s2 += D) {
 #pragma unroll
-      for (int e = 0; e < 2; ++e) {
+      for (int e = 0; e < D; ++e) {
         const int s = s2 + e;
         if (s >= n_steps) break;
         stage(xr2[e], wr2[e]);
         __builtin_amdgcn_sched_barrier(0);
-        fetch(xr2[e], wr2[e], 8 * (s + 2 < n_steps ? s + 2 : n_steps - 1));
+        fetch(xr2[e], wr2[e], 8 * (s + D < n_steps ? s + D : n_steps - 1));
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         const unsigned *xa = XS + (lane >> 5) * HS + (lane & 31) * 4, *wb = WS + (lane >> 5) * HS + (lane & 31) * 4;
