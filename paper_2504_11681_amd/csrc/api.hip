@@ -423,9 +423,14 @@ bool fused1d_real_supported(int N, int K)
     }
 }
 
+static int kernel_choice();
+
 hipError_t fused1d_real_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s)
 {
     if (!fused1d_real_supported(N, K)) return hipErrorInvalidValue;
+    // N = 1024: the symmetric-wave kernel where it exists and no bins are masked (it has no mode mask)
+    if (fused1d_sym_supported(N, K) && a.K_keep == K && kernel_choice() == 0 && !contraction_forced_f32())
+        return fused1d_sym_real_launch(N, K, a, rows, s);
     switch (N) {
     case 64: return fused1d_real_launch_n64(K, a, rows, s);
     case 128: return fused1d_real_launch_n128(K, a, rows, s);

@@ -42,6 +42,7 @@ hipError_t fused1d_ws_launch(int N, int K, const Fused1dArgs &a, long long rows,
 // Symmetric-wave variant (every wave runs transforms and contraction; BF16x3 split contraction).
 bool fused1d_sym_supported(int N, int K);
 hipError_t fused1d_sym_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
+hipError_t fused1d_sym_real_launch(int N, int K, const Fused1dArgs &a, long long rows, hipStream_t s);
 
 // Two-group variant for N = 256 (eight waves, the groups alternate between transforms and contraction; 256 outputs
 // per workgroup): whole 32-channel blocks only, 128 < C_out, K in {32, 64}.

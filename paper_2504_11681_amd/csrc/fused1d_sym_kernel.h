@@ -58,7 +58,11 @@ __device__ __forceinline__ float sym_quad_perm(float v)
 
 // EVEN: C_in is a multiple of 8 and C_out a multiple of 128 (no masks).  DEEP: the number of 8-channel blocks
 // is even and at least four; the k-loop then keeps two blocks of loads in flight per wave.
-template <int K, bool EVEN, bool DEEP>
+// REAL: the real-valued layer.  a.x and a.y point to float32 tensors (strides in floats); the forward transform of
+// a real pencil is the complex one with a zero imaginary part, whose first K bins are the R2C bins; the C2R inverse of
+// the zero-padded half spectrum is (2/N) Re( sum_k Y'[k] e^(+2 pi i k n / N) ) with Y'[0] = Y[0]/2, so bin 0 is halved
+// on its way into the operand tile, the caller passes scale = 2/N, and only real parts are stored.
+template <int K, bool EVEN, bool DEEP, bool REAL = false>
 __global__ void __launch_bounds__(512)
 k_fused1d_sym(Fused1dArgs a)
 {
@@ -79,6 +83,8 @@ k_fused1d_sym(Fused1dArgs a)
     const long long bo = bb / a.inner_count, bi = bb % a.inner_count;
     const c64 *__restrict__ xb = a.x + bo * a.x_outer_stride + bi * a.x_inner_stride;
     c64 *__restrict__ yb = a.y + bo * a.y_outer_stride + bi * a.y_inner_stride;
+    const float *__restrict__ xbr = reinterpret_cast<const float *>(a.x) + bo * a.x_outer_stride + bi * a.x_inner_stride;
+    float *__restrict__ ybr = reinterpret_cast<float *>(a.y) + bo * a.y_outer_stride + bi * a.y_inner_stride;
     const int n_it = (a.C_in + PPI - 1) / PPI;
     c64 *patch = patch_all + wave * C::PATCH;
     const int p = lane;                                 // row-stage identity
@@ -104,7 +110,15 @@ k_fused1d_sym(Fused1dArgs a)
 
     auto load_pencil = [&](c64 *v, int c0) __attribute__((always_inline)) {
         const int c = c0 + wave;
-        if constexpr (EVEN) {
+        if constexpr (REAL) {
+            const bool ok = EVEN || c < a.C_in;
+            const float *src = xbr + (long long)(ok ? c : 0) * a.x_chan_stride + p;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const float val = __builtin_nontemporal_load(src + 64 * j);
+                v[j] = make_float2(ok ? val : 0.f, 0.f);
+            }
+        } else if constexpr (EVEN) {
             const c64 *src = xb + (long long)c * a.x_chan_stride + p;
 #pragma unroll
             for (int j = 0; j < 16; ++j) v[j] = load_nt(src + 64 * j);
@@ -213,6 +227,9 @@ k_fused1d_sym(Fused1dArgs a)
         // of tile qa (K = 128) or qa / 2 (K = 64); the tile stride of 128 + 16 (K = 128) or 128 + 32 (K = 64) dwords
         // turns (k_lo, qa) into 64 different banks.
         unsigned *dst = XS + buf * C::XS_BUF + (wave >> 2) * (KT * C::XT) + (wave & 3) * 32;
+        if constexpr (REAL) {
+            if (lane == 0) O[0] = make_float2(0.5f * O[0].x, 0.5f * O[0].y);    // bin 0 (k_lo = 0, qa = 0, i = 0)
+        }
 #pragma unroll
         for (int i = 0; i < OPL; ++i) {
             const int k = kl + 16 * (OPL * qa + i);
@@ -384,32 +401,38 @@ k_fused1d_sym(Fused1dArgs a)
         RegFFT<16, +1, 1>::run(z, res);
         const int o = o_base + 32 * (wave >> 1) + 8 * (r / 4) + 4 * (wave & 1) + (r % 4);
         if (EVEN || o < a.C_out) {
-            c64 *dst = yb + (long long)o * a.y_chan_stride + p;
+            if constexpr (REAL) {
+                float *dst = ybr + (long long)o * a.y_chan_stride + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) store_nt(dst + 64 * j, res[j]);
+                for (int j = 0; j < 16; ++j) __builtin_nontemporal_store(res[j].x, dst + 64 * j);
+            } else {
+                c64 *dst = yb + (long long)o * a.y_chan_stride + p;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) store_nt(dst + 64 * j, res[j]);
+            }
         }
     }
 }
 
-template <int K>
+template <int K, bool REAL = false>
 hipError_t launch_fused1d_sym(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
     using C = SymCfg<K>;
     static LdsLimitOnce lds_limit;
-    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d_sym<K, true, true>),
-                                        reinterpret_cast<const void *>(&k_fused1d_sym<K, true, false>),
-                                        reinterpret_cast<const void *>(&k_fused1d_sym<K, false, false>)},
+    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d_sym<K, true, true, REAL>),
+                                        reinterpret_cast<const void *>(&k_fused1d_sym<K, true, false, REAL>),
+                                        reinterpret_cast<const void *>(&k_fused1d_sym<K, false, false, REAL>)},
                                        (int)C::LDS_DYN);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 127) / 128));
     const bool even = a.C_in % C::PPI == 0 && a.C_out % 128 == 0;
     const int n_it = (a.C_in + C::PPI - 1) / C::PPI;
     if (even && n_it % 2 == 0 && n_it >= 4)
-        hipLaunchKernelGGL((k_fused1d_sym<K, true, true>), grid, dim3(512), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d_sym<K, true, true, REAL>), grid, dim3(512), C::LDS_DYN, s, a);
     else if (even)
-        hipLaunchKernelGGL((k_fused1d_sym<K, true, false>), grid, dim3(512), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d_sym<K, true, false, REAL>), grid, dim3(512), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d_sym<K, false, false>), grid, dim3(512), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d_sym<K, false, false, REAL>), grid, dim3(512), C::LDS_DYN, s, a);
     return hipGetLastError();
 }
 

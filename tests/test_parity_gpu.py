@@ -445,7 +445,10 @@ def test_entry_points_replay_from_a_hip_graph(gpu):
 REAL_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 8), (2, 33, 40, 64, 32), (3, 9, 70, 128, 32), (2, 37, 17, 128, 64),
            (64, 64, 64, 256, 64), (5, 19, 130, 256, 32), (2, 40, 33, 256, 16), (3, 24, 96, 256, 128), (2, 17, 9, 512, 32),
            (2, 8, 40, 512, 256), (3, 13, 129, 1024, 128), (1, 1, 1, 1024, 64), (2, 20, 30, 1024, 32), (2, 16, 64, 1024, 256),
-           (2, 128, 128, 1024, 128)]
+           (2, 128, 128, 1024, 128),
+           # N = 1024 on the symmetric-wave kernel: whole blocks without the deep pipeline, K = 64 deep, and a mode
+           # count between the built sizes (stays on the four-wave kernel, which masks bins)
+           (2, 16, 128, 1024, 64), (2, 64, 256, 1024, 64), (2, 9, 11, 1024, 100)]
 
 
 @pytest.mark.parametrize("shape", REAL_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
