@@ -109,11 +109,13 @@ k_fwd1d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C, long long npenci
         if constexpr (REAL) {
             const float *src = reinterpret_cast<const float *>(x) + q * N + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] = make_float2(src[LPR * j], 0.f);
+            for (int j = 0; j < 16; ++j) v[j] = make_float2(LPR >= 16 ? __builtin_nontemporal_load(src + LPR * j) : src[LPR * j], 0.f);
         } else {
+            // (x is read once; non-temporal where the lanes of a pencil cover whole lines, so that the stream does not
+            // evict the spectra the contraction reads next)
             const c64 *src = x + q * N + p;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] = src[LPR * j];
+            for (int j = 0; j < 16; ++j) v[j] = LPR >= 16 ? load_nt(src + LPR * j) : src[LPR * j];
         }
     };
     auto stage = [&](long long sweep, auto refill, long long next_sweep) __attribute__((always_inline)) {
@@ -288,11 +290,18 @@ k_inv1d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C, long long npenci
             if constexpr (REAL) {
                 float *dst = reinterpret_cast<float *>(y) + q * N + p;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) dst[LPR * j] = res[j].x;
+                for (int j = 0; j < 16; ++j) {
+                    if constexpr (LPR >= 32) __builtin_nontemporal_store(res[j].x, dst + LPR * j);
+                    else dst[LPR * j] = res[j].x;
+                }
             } else {
+                // (non-temporal only where the lanes of a pencil write whole 128-byte lines)
                 c64 *dst = y + q * N + p;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) store_nt(dst + LPR * j, res[j]);
+                for (int j = 0; j < 16; ++j) {
+                    if constexpr (LPR >= 16) store_nt(dst + LPR * j, res[j]);
+                    else dst[LPR * j] = res[j];
+                }
             }
         }
     };
