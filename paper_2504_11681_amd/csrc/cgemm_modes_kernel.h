@@ -242,6 +242,141 @@ k_cgemm_modes(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__rest
     }
 }
 
+// The same contraction with ALL of W resident in LDS, for 64 < C_in <= 128 (96 KB as three BF16 terms): the looped
+// kernel above restages a 64-channel block of W twice per mode tile, with the L2 round trip of its loads and four
+// barriers exposed every time, which is half of its run time at C_in = 128.  Here eight waves share one copy of W,
+// staged once; after that no wave meets a barrier: wave w walks the 32 modes 32 (w % 4) of tiles tile0 + 2 t + w / 4,
+// its loads four 8-channel steps ahead across tile boundaries.
+__global__ void __launch_bounds__(512)
+k_cgemm_modes_resident(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *__restrict__ Yh,
+                       int C_in, int C_out, float scale, long long num_tiles, int pairs_per_wg)
+{
+    extern __shared__ __align__(16) unsigned Wres[];        // [channel / 4][term][output][channel % 4], c_pad channels
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int o0 = blockIdx.y * 64;
+    const long long tile0 = (long long)blockIdx.x * 2 * pairs_per_wg;
+    const int c_pad = (C_in + 31) / 32 * 32;
+    // tiles of this wave: tile0 + 2 t + wave / 4, t < nt_w
+    const long long first = tile0 + (wave >> 2);
+    const int nt_w = first >= num_tiles ? 0 : (int)((num_tiles - first + 1) / 2 < pairs_per_wg ? (num_tiles - first + 1) / 2 : pairs_per_wg);
+
+    const int rot = 8 * (int)(blockIdx.x & 7);              // see the looped kernel: spreads the memory channels
+    auto rotated = [&](int c_lin) __attribute__((always_inline)) {
+        const int cb = c_lin & ~63, left = C_in - cb, lim = left >= 64 ? 64 : (left + 31) / 32 * 32;
+        return cb + ((c_lin - cb + rot) & (lim - 1));
+    };
+    int nt = 0, nc = 0;
+    auto load_next = [&](c64 *xv) __attribute__((always_inline)) {
+        // (past this wave's last tile the first one is read again and never used; a wave without tiles reads tile 0)
+        const long long ti = nt_w > 0 ? first + 2 * (nt < nt_w ? nt : 0) : 0;
+        const c64 *src = Xh + ti * C_in * 128 + 32 * (wave & 3) + col;
+        const int c0 = rotated(nc);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int c = c0 + 4 * g + d;
+            xv[d] = src[(c < C_in ? c : 0) * 128];
+        }
+        nc += 8;
+        if (nc >= c_pad) { nc = 0; ++nt; }
+    };
+    c64 xq[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_next(xq[i]);           // in flight while W is staged
+
+    {
+        c64 wq[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int idx = i * 512 + tid, c = idx / 64, o = o0 + idx % 64;
+            const bool ok = c < C_in && o < C_out;
+            const c64 w = W[ok ? (long long)c * C_out + o : 0];
+            wq[i] = ok ? w : make_float2(0.f, 0.f);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int idx = i * 512 + tid, cl = idx / 64, ol = idx % 64;
+            if (cl < c_pad) {
+                const Split3 re = split3(wq[i].x * scale), im = split3(wq[i].y * scale);
+                unsigned *dst = Wres + (((cl >> 2) * 3) * 64 + ol) * 4 + (cl & 3);
+                dst[0 * 64 * 4] = pack_bf16(re.t0, im.t0);
+                dst[1 * 64 * 4] = pack_bf16(re.t1, im.t1);
+                dst[2 * 64 * 4] = pack_bf16(re.t2, im.t2);
+            }
+        }
+    }
+    __syncthreads();                                        // the only barrier: W is resident
+
+    // W operands of a step: [output half][term], read one step ahead of their MFMAs (the LDS round trip of six
+    // 16-byte reads would otherwise sit between every step's split and its MFMAs)
+    const int nsteps = c_pad / 8;
+    uintx4 wbuf[2][2][3];
+    auto read_w = [&](uintx4 (*w)[3], int step) __attribute__((always_inline)) {
+        const int c0 = rotated(8 * step);
+        const unsigned *wsrc = Wres + (((c0 >> 2) + g) * 3 * 64 + col) * 4;
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+            for (int tm = 0; tm < 3; ++tm) w[sl][tm] = *reinterpret_cast<const uintx4 *>(wsrc + (tm * 64 + 32 * sl) * 4);
+    };
+    read_w(wbuf[0], 0);
+
+    floatx16 acc_re[2], acc_im[2];
+    for (int t = 0; t < nt_w; ++t) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc_re[i][r] = 0.f; acc_im[i][r] = 0.f; }
+#pragma unroll 1
+        for (int s4 = 0; s4 < nsteps; s4 += 4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uintx4 b[3];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const Split3 re = split3(xq[i][d].x), im = split3(xq[i][d].y);
+                    b[0][d] = pack_bf16(re.t0, im.t0);
+                    b[1][d] = pack_bf16(re.t1, im.t1);
+                    b[2][d] = pack_bf16(re.t2, im.t2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                load_next(xq[i]);                           // four steps ahead
+                read_w(wbuf[(i + 1) & 1], s4 + i + 1 < nsteps ? s4 + i + 1 : 0);
+                __builtin_amdgcn_sched_barrier(0);
+                constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};   // smallest products first
+#pragma unroll
+                for (int sl = 0; sl < 2; ++sl) {
+                    uintx4 a_re[3], a_im[3];
+#pragma unroll
+                    for (int tm = 0; tm < 3; ++tm)
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const unsigned w = wbuf[i & 1][sl][tm][d];
+                            a_re[tm][d] = w ^ 0x80000000u;
+                            a_im[tm][d] = __builtin_amdgcn_alignbit(w, w, 16);
+                        }
+#pragma unroll
+                    for (int k = 0; k < 6; ++k) {
+                        const bf16x8 bb = __builtin_bit_cast(bf16x8, b[SB[k]]);
+                        acc_re[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_re[SA[k]]), bb, acc_re[sl], 0, 0, 0);
+                        acc_im[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_im[SA[k]]), bb, acc_im[sl], 0, 0, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        c64 *__restrict__ Yb = Yh + (first + 2 * t) * C_out * 128 + 32 * (wave & 3) + col;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int o = o0 + 32 * i + 8 * (r / 4) + 4 * g + (r % 4);
+                if (o < C_out) Yb[o * 128] = make_float2(acc_re[i][r], acc_im[i][r]);
+            }
+    }
+}
+
 // The same contraction for C_in <= 8 NSTEP <= 64 (one block of W), two mode tiles per workgroup, written as
 // straight-line code: all NSTEP steps of a tile live in registers (16 KB per wave), every step's registers are
 // refilled with the next tile right after their operand split, and without a loop back-edge the compiler waits for

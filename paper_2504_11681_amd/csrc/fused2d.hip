@@ -29,6 +29,19 @@ hipError_t cgemm_modes_launch(const c64 *Xh, const c64 *W, c64 *Yh, int C_in, in
             hipLaunchKernelGGL(k_cgemm_modes_small<8>, g2, dim3(256), 0, s, Xh, W, Yh, C_in, C_out, scale, tiles);
         return hipGetLastError();
     }
+    if (!contraction_forced_f32() && C_in <= 128) {
+        // all of W resident in LDS, eight waves, two mode tiles at a time; about one workgroup per CU
+        const int c_pad = (C_in + 31) / 32 * 32, lds = c_pad * 3 * 64 * 4;
+        static LdsLimitOnce lds_limit;
+        const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_cgemm_modes_resident)}, 128 * 3 * 64 * 4);
+        if (e != hipSuccess) return e;
+        const long long pairs = (tiles + 1) / 2, gy = (C_out + 63) / 64;
+        long long ppw = pairs * gy / 256;
+        ppw = ppw < 1 ? 1 : ppw > 16 ? 16 : ppw;
+        const dim3 gr((unsigned)((pairs + ppw - 1) / ppw), (unsigned)gy);
+        hipLaunchKernelGGL(k_cgemm_modes_resident, gr, dim3(512), lds, s, Xh, W, Yh, C_in, C_out, scale, tiles, (int)ppw);
+        return hipGetLastError();
+    }
     // about two workgroups per CU, each walking several mode tiles
     const int tpw = tiles >= 1024 ? (int)(tiles / 512 > 16 ? 16 : tiles / 512) : 1;
     const dim3 ggrid((unsigned)((tiles + tpw - 1) / tpw), (unsigned)((C_out + 63) / 64));

@@ -106,6 +106,9 @@ PRUNED_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 64), (2, 33, 40, 64, 32), (3, 9,
              (2, 5, 3, 128, 16), (64, 64, 64, 256, 64), (5, 19, 130, 256, 32), (2, 40, 33, 256, 16), (3, 24, 96, 256, 128),
              (2, 20, 40, 256, 256), (3, 13, 129, 1024, 128), (1, 1, 1, 1024, 64), (2, 20, 30, 1024, 64),
              (7, 3, 2, 256, 16),
+             # 64 < C_in <= 128: the contraction with all of W resident in LDS (ragged channels and outputs, an odd
+             # number of mode tiles, several tile pairs per workgroup, whole blocks)
+             (5, 70, 65, 256, 64), (3, 97, 130, 1024, 128), (600, 128, 128, 256, 128), (9, 128, 64, 256, 128), (2, 100, 20, 128, 64),
              # long pencils (N1 x 256 decomposition): odd pencil counts, K / N1 from 16 to 256, no truncation
              (2, 5, 7, 2048, 128), (3, 3, 5, 2048, 256), (1, 1, 1, 2048, 2048), (2, 8, 8, 2048, 1024),
              (2, 6, 9, 4096, 256), (1, 3, 2, 4096, 1024), (1, 2, 2, 4096, 4096), (2, 33, 70, 4096, 512),
