@@ -281,10 +281,8 @@ k_cgemm_modes_resident(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c6
         if (nc >= c_pad) { nc = 0; ++nt; }
     };
     c64 xq[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) load_next(xq[i]);           // in flight while W is staged
-
     {
+        // W first: its staging is on every wave's critical path, the first steps of X are not
         c64 wq[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -293,6 +291,9 @@ k_cgemm_modes_resident(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c6
             const c64 w = W[ok ? (long long)c * C_out + o : 0];
             wq[i] = ok ? w : make_float2(0.f, 0.f);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_next(xq[i]);       // in flight while W is staged
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -406,10 +407,8 @@ k_cgemm_modes_small(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *
             xq[i][d] = src[(c < C_in ? c : 0) * 128];
         }
     };
-#pragma unroll
-    for (int i = 0; i < NSTEP; ++i) load_step(0, i);        // in flight while W is staged
-
     {
+        // W first: its staging is on every wave's critical path, the first tile of X is not
         c64 wq[2 * NSTEP];
 #pragma unroll
         for (int i = 0; i < 2 * NSTEP; ++i) {
@@ -418,6 +417,9 @@ k_cgemm_modes_small(const c64 *__restrict__ Xh, const c64 *__restrict__ W, c64 *
             const c64 w = W[ok ? (long long)c * C_out + o : 0];
             wq[i] = ok ? w : make_float2(0.f, 0.f);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) load_step(0, i);    // in flight while W is staged
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2 * NSTEP; ++i) {
