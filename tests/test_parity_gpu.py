@@ -846,6 +846,28 @@ def test_empty_batch_and_error_paths(gpu):
     torch.cuda.synchronize()
 
 
+# Scaling the input or the weights by a power of two only changes exponents, so every entry point must return the
+# scaled result bit for bit: the transforms multiply by twiddles and add, and the contraction splits each operand into
+# three BF16 terms whose exponent range is that of float32.  A split that lost low-order terms to underflow, or a
+# path that mixed scaled and unscaled quantities, would show here.
+@pytest.mark.parametrize("entry,shape", [("spectral_conv1d", (3, 24, 40, 1024, 128)), ("spectral_conv1d", (5, 32, 64, 256, 128)),
+                                         ("spectral_conv1d", (4, 64, 256, 256, 64)), ("spectral_conv1d_pruned", (3, 70, 65, 256, 64)),
+                                         ("spectral_conv2d", (2, 8, 8, 64, 16))],
+                         ids=lambda v: v if isinstance(v, str) else "x".join(map(str, v)))
+def test_power_of_two_scaling_is_exact(gpu, entry, shape):
+    B, Ci, Co, N, K = shape
+    say(f"[case] scaling {entry} {shape}")
+    dims = (N, N) if entry.endswith("2d") else (N,)
+    x = inputs.make_x(4242, B, Ci, dims)
+    W = inputs.make_W(4242, Ci, Co)
+    base = run_gpu(gpu, entry, x, W, K)
+    assert np.isfinite(base.view(np.float32)).all()
+    for ex, ew in ((30, 0), (-30, 0), (0, 25), (-20, -20), (40, -45)):
+        got = run_gpu(gpu, entry, x * np.float32(2.0 ** ex), W * np.float32(2.0 ** ew), K)
+        want = base * np.float32(2.0 ** (ex + ew))
+        assert np.array_equal(got.view(np.float32), want.view(np.float32)), (entry, shape, ex, ew)
+
+
 def test_workspace_growth_does_not_disturb_earlier_work_on_another_stream(gpu, oracle_mod):
     """A call that uses the workspace is enqueued on a side stream behind a long queue of other launches; a call
     with a larger workspace need follows on the default stream at once.  The binding synchronises the device before
