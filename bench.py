@@ -185,6 +185,26 @@ def measure(w, torch, binding, steps, warmup, staged=False, pruned=False, ramp=R
     return wall, dev
 
 
+def measure_strips(w, torch, binding, steps, warmup, ramp):
+    """Device seconds per layer of the paper's own 2-D pipeline (tfno_spectral_conv2d_strips: first-axis FFT with
+    truncation, fused 1-D kernel on the retained rows, first-axis iFFT with padding) on the 2-D workload w."""
+    xd, Wd, yd = device_inputs(w, torch)
+    sets = [(xd, yd), (xd.clone(), torch.zeros_like(yd))]
+    binding.ensure_workspace(binding.workspace_bytes_2d(7, w.B, w.C_in, w.C_out, w.N, w.N, w.K, w.K), xd.device)
+    stream = torch.cuda.current_stream().cuda_stream
+    turn = [0]
+
+    def call():
+        xi, yi = sets[turn[0] % 2]
+        turn[0] += 1
+        binding.spectral_conv2d_strips(xi, Wd, yi, w.K, w.K, stream)
+
+    _, dev = time_calls(torch, call, steps, warmup, ramp)
+    del xd, Wd, yd, sets
+    torch.cuda.empty_cache()
+    return dev
+
+
 def measure_rect(torch, binding, B, C, N1, N2, K1, K2, steps, warmup, ramp):
     """Device seconds per layer of the non-square 2-D entry point on seeded inputs of the usual recipe."""
     from paper_2504_11681_amd import inputs
@@ -490,6 +510,17 @@ def main():
                               "roofline": roofline_entry(w4, dev4, "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)")}
             # Everything below widens the report beyond the headline workloads; a failure there is recorded, not fatal
             # to the line (the headline figures above are already measured).
+            try:
+                # the 2-D ablation: the paper's own pipeline (strips of K retained rows through HBM around the fused
+                # 1-D kernel) against the image kernels above
+                sdev = measure_strips(w4, torch, binding, max(5, steps4 // 25), 2, args.ramp / 3)
+                out["cfg4_2d"]["paper_2d_pipeline"] = {
+                    "entry_point": "tfno_spectral_conv2d_strips", "us_per_layer": sdev * 1e6,
+                    "structure": "first-axis FFT with truncation, fused FFT-CGEMM-iFFT along the last axis on the K "
+                                 "retained rows, first-axis iFFT with padding; two [B, C, K, N] strips cross HBM",
+                    "image_kernels_speedup": sdev / dev4}
+            except Exception as exc:                                    # pragma: no cover
+                out["cfg4_2d"]["paper_2d_pipeline"] = {"error": repr(exc)}
             try:
                 # the remaining configurations: the two small 1-D shapes on the fused entry point and the twelve cells
                 # of the hidden-dimension sweep on the per-shape dispatch (all variants of the sweep: --sweep)

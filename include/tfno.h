@@ -151,6 +151,19 @@ tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void 
                                              int N1, int N2, int K1, int K2, void *stream);
 
 /*
+ * The paper's own 2-D pipeline (Sec. 3.2, Sec. 3.3 and the fully fused 2-D variant of Sec. 5.2) on request, for
+ * every shape including those that tfno_spectral_conv2d_rect runs on the image kernels: truncated forward FFT along
+ * the first axis (writes the K1 retained rows), the fully fused 1-D kernel along the last axis on those rows,
+ * zero-padded inverse FFT along the first axis; the two [B, C, K1, N2] strips go through the workspace
+ * (tfno_workspace_bytes_2d(7, ...) = 8 B K1 N2 (C_in + C_out) bytes).  Same arguments, contract and result as
+ * tfno_spectral_conv2d_rect.  It exists for comparison (the 2-D ablation of the paper): on this machine the image
+ * kernels, which keep both axes of an image on chip, are several times faster.  Shapes: N1 a power of two in
+ * [2, 4096] with any K1 <= N1, (N2, K2) a shape of the fused 1-D kernel; others TFNO_ERR_UNSUPPORTED.
+ */
+tfno_status tfno_spectral_conv2d_strips(const void *x, const void *W, void *y, int B, int C_in, int C_out,
+                                        int N1, int N2, int K1, int K2, void *stream);
+
+/*
  * Spectral convolution with an own weight matrix per retained mode -- the Fourier layer as the FNO model defines
  * it (Sec. 1, Sec. 2.1 step 3: a learned linear transformation in the frequency domain); the entry points above
  * take the single shared matrix of the paper's GEMM formulation (Sec. 3.1), which is the special case of equal
@@ -266,7 +279,8 @@ tfno_status tfno_spectral_conv1d_auto(const void *x, const void *W, void *y,
  * Workspace (device memory for intermediates) that an entry point needs for a
  * shape: dims = 1 or 2, variant = 0 (fused entry point), 1 (staged twin), 2
  * (tfno_spectral_conv1d_pruned), 3 (tfno_spectral_conv1d_fft_gemm), 4 (tfno_spectral_conv1d_gemm_ifft), 5
- * (tfno_spectral_conv1d_auto) or 6 (tfno_spectral_conv1d_permode).  Returns 0 when none is needed or the arguments are invalid.
+ * (tfno_spectral_conv1d_auto), 6 (tfno_spectral_conv1d_permode) or 7 (tfno_spectral_conv2d_strips, dims = 2 only).
+ * Returns 0 when none is needed or the arguments are invalid.
  */
 size_t tfno_workspace_bytes(int dims, int variant, int B, int C_in, int C_out, int N, int K);
 /* The same for the 2-D entry points that take N1, N2, K1, K2: variant = 0 (tfno_spectral_conv2d_rect), 1 (its

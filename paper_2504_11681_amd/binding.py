@@ -33,6 +33,7 @@ EXPORTS = (
     "tfno_fno1d_real",
     "tfno_fno1d_real_workspace_bytes",
     "tfno_spectral_conv2d_noalloc",
+    "tfno_spectral_conv2d_strips",
     "tfno_workspace_bytes",
     "tfno_workspace_bytes_2d",
     "tfno_set_workspace",
@@ -67,7 +68,7 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
-        for name in RECT_EXPORTS:
+        for name in RECT_EXPORTS + ("tfno_spectral_conv2d_strips",):
             fn = getattr(L, name)
             fn.restype = ci
             fn.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
@@ -244,6 +245,11 @@ def spectral_conv2d_rect(x, W, y, K1: int, K2: int, stream=None):
 
 def spectral_conv2d_rect_staged(x, W, y, K1: int, K2: int, stream=None):
     return _call_rect("tfno_spectral_conv2d_rect_staged", True, x, W, y, K1, K2, stream)
+
+
+def spectral_conv2d_strips(x, W, y, K1: int, K2: int, stream=None):
+    """The paper's 2-D pipeline on request (first-axis FFT, fused 1-D kernel on the retained rows, first-axis iFFT)."""
+    return _call_rect("tfno_spectral_conv2d_strips", 7, x, W, y, K1, K2, stream)
 
 
 def _call_permode(name: str, dims: int, x, W, y, stream):

@@ -124,6 +124,11 @@ bool kernel_shape(const Shape &req, int variant, Shape *ks)
         ks->K2 = k;
         return k != 0;
     }
+    if (variant == 7) {                                     // the strip pipeline on request: the first axis takes any K1
+        const int k = round_modes(req.N2, req.K2, fused1d_supported);
+        ks->K2 = k;
+        return k != 0;
+    }
     if (variant != 0 && variant != 6) return false;
     const int k1 = round_modes(req.N1, req.K1, image_modes), k2 = round_modes(req.N2, req.K2, image_modes);
     if (k1 && k2 && fused2d_supported(req.N1, req.N2, k1, k2)) {
@@ -149,7 +154,7 @@ tfno_status check_workspace(size_t need, const void *x, size_t xb, const void *W
     return TFNO_OK;
 }
 
-enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2, FFT_GEMM = 3, GEMM_IFFT = 4 };
+enum Variant { FUSED = 0, STAGED = 1, PRUNED = 2, FFT_GEMM = 3, GEMM_IFFT = 4, STRIPS = 7 };
 
 // own_scratch: the intermediates go to the library's static scratch array instead of the registered workspace
 tfno_status run(const Shape &req, Variant variant, const void *x, const void *W, void *y, int B, int C_in, int C_out,
@@ -212,7 +217,7 @@ tfno_status run(const Shape &req, Variant variant, const void *x, const void *W,
         a.scale = 1.0f / (float)N;
         a.K_keep = keep2;
         e = fused1d_launch(N, K, a, B, s);
-    } else if (sh.image_kernels()) {
+    } else if (variant != STRIPS && sh.image_kernels()) {
         // image kernels: only the truncated K1 x K2 spectra cross global memory
         e = fused2d_launch(xc, Wc, yc, B, C_in, C_out, sh.N1, sh.N2, sh.K1, sh.K2, keep1, keep2, (c64 *)ws, s);
     } else {
@@ -511,7 +516,8 @@ size_t workspace_for(const Shape &req, int variant, int B, int C_in, int C_out)
         variant = (int)choose_variant(req.N2, req.K2, C_out);
     }
     if (B < 1 || !sizes_ok(req, B, C_in, C_out, variant == 1)) return 0;
-    if (variant < 0 || variant > 6 || variant == 5 || (variant >= 2 && variant <= 4 && req.dims != 1)) return 0;
+    if (variant < 0 || variant > 7 || variant == 5 || (variant >= 2 && variant <= 4 && req.dims != 1)) return 0;
+    if (variant == 7 && req.dims != 2) return 0;
     Shape sh;                                               // the kernels' shape (K rounded up to a built size)
     if (!kernel_shape(req, variant, &sh)) return 0;
     if (variant == 6)       // per-mode weights: the truncated spectra of input and output
@@ -521,8 +527,8 @@ size_t workspace_for(const Shape &req, int variant, int B, int C_in, int C_out)
     if (variant == 3 || variant == 4) return sizeof(c64) * pruned1d_spectrum_elems(B, variant == 3 ? C_out : C_in, sh.K2);
     if (variant == 1) return staged_workspace_bytes(B, C_in, C_out, req.N1, req.N2, req.K1, req.K2);
     if (sh.dims == 1) return 0;
-    return sh.image_kernels() ? fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2)
-                              : strip2d_workspace_bytes(B, C_in, C_out, sh.N2, sh.K1);
+    return variant != 7 && sh.image_kernels() ? fused2d_workspace_bytes(B, C_in, C_out, sh.K1, sh.K2)
+                                              : strip2d_workspace_bytes(B, C_in, C_out, sh.N2, sh.K1);
 }
 
 }  // namespace
@@ -587,6 +593,12 @@ tfno_status tfno_spectral_conv2d_rect(const void *x, const void *W, void *y, int
                                       int N2, int K1, int K2, void *stream)
 {
     return run(shape2d(N1, N2, K1, K2), FUSED, x, W, y, B, C_in, C_out, stream);
+}
+
+tfno_status tfno_spectral_conv2d_strips(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1,
+                                        int N2, int K1, int K2, void *stream)
+{
+    return run(shape2d(N1, N2, K1, K2), STRIPS, x, W, y, B, C_in, C_out, stream);
 }
 
 tfno_status tfno_spectral_conv2d_rect_staged(const void *x, const void *W, void *y, int B, int C_in, int C_out, int N1,

@@ -65,7 +65,7 @@ def test_argument_errors_are_caught_on_the_host(L, name):
     assert call(L, name, None, None, None, 0, 4, 4, 64, 16) == binding.OK
 
 
-@pytest.mark.parametrize("name", binding.RECT_EXPORTS)
+@pytest.mark.parametrize("name", binding.RECT_EXPORTS + ("tfno_spectral_conv2d_strips",))
 def test_rect_argument_errors_are_caught_on_the_host(L, name):
     x, W, y = FAKE, FAKE + (1 << 26), FAKE + (2 << 26)
     fn = getattr(L, name)
@@ -103,6 +103,13 @@ def test_rect_workspace_and_unsupported_shapes(L):
     # last axis not covered by the fused 1-D kernel and not an image-kernel shape
     assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 2048, 16, 32, None) == binding.ERR_UNSUPPORTED
     assert L.tfno_spectral_conv2d_rect(x, W, y, 2, 4, 4, 64, 32, 16, 8, None) == binding.ERR_UNSUPPORTED
+    # the strip pipeline on request: strips also for a shape that the other entry point runs on the image kernels
+    assert binding.workspace_bytes_2d(7, 2, 3, 5, 64, 256, 16, 64) == 8 * 2 * 16 * 256 * (3 + 5)
+    assert binding.workspace_bytes_2d(7, 2, 3, 5, 32, 256, 5, 40) == 8 * 2 * 5 * 256 * (3 + 5)
+    assert binding.workspace_bytes_2d(7, 2, 3, 5, 64, 2048, 16, 32) == 0
+    assert binding.workspace_bytes(1, 7, 2, 3, 5, 256, 64) == 0                # 2-D only
+    assert L.tfno_spectral_conv2d_strips(x, W, y, 2, 4, 4, 64, 128, 16, 32, None) == binding.ERR_WORKSPACE
+    assert L.tfno_spectral_conv2d_strips(x, W, y, 2, 4, 4, 64, 2048, 16, 32, None) == binding.ERR_UNSUPPORTED
 
 
 def test_real_layer_argument_checks(L):

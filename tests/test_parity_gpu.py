@@ -294,6 +294,22 @@ def test_2d_rect_mixed(gpu, oracle_mod, fn, shape):
     check(run_gpu_rect(gpu, fn, x, W, K1, K2), want, fn)
 
 
+# the paper's 2-D pipeline on request: image-kernel shapes (where the default entry point takes the other path), shapes
+# it serves anyway, modes between the built sizes on both axes
+STRIPS_2D = [(3, 7, 70, 64, 256, 16, 64), (2, 33, 5, 256, 64, 64, 16), (2, 8, 8, 64, 64, 16, 16), (2, 3, 4, 32, 256, 8, 64),
+             (1, 5, 3, 128, 128, 20, 12), (2, 16, 16, 256, 256, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", STRIPS_2D, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
+def test_2d_strip_pipeline_on_request(gpu, oracle_mod, shape):
+    B, Ci, Co, N1, N2, K1, K2 = shape
+    say(f"[case] spectral_conv2d_strips {shape}")
+    x = inputs.make_x(450 + N1 + K2, B, Ci, (N1, N2))
+    W = inputs.make_W(450 + N1 + K2, Ci, Co)
+    want, _ = oracle_mod.spectral_conv2d_rect(x, W, K1, K2)
+    check(run_gpu_rect(gpu, "spectral_conv2d_strips", x, W, K1, K2), want, "strips")
+
+
 @pytest.mark.parametrize("shape", RECT_STAGED_ONLY, ids=lambda s: "B%d_Ci%d_Co%d_N%dx%d_K%dx%d" % s)
 def test_2d_rect_staged_general_shapes(gpu, oracle_mod, shape):
     torch, binding = gpu
