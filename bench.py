@@ -110,6 +110,16 @@ def flops_of(w):
     return 8.0 * w.B * (w.K ** w.dims) * w.C_in * w.C_out
 
 
+def transform_flops_of(w):
+    """Estimate of the real flops of the pruned transforms: per pencil N/K sub-transforms of length K plus one pruned
+    radix-N/K combine, 5 N log2 K + 8 K (N/K - 1), for the B (C_in + C_out) pencils of the last axis and, in 2-D, N
+    pencils per image on the first-axis pass of the forward side and K on the other (mirrored on the inverse side)."""
+    import math
+    per_pencil = 5.0 * w.N * math.log2(w.K) + 8.0 * w.K * (w.N / w.K - 1)
+    images = w.B * (w.C_in + w.C_out)
+    return images * per_pencil * (1 if w.dims == 1 else (w.N + w.K))
+
+
 def buffer_sets(w):
     """Number of (x, y) buffer pairs the timed launches rotate through: enough that one round of the pool is
     at least 1 GiB, four times the 256 MB last-level cache, so that no launch finds its input or the lines of
@@ -476,6 +486,10 @@ def main():
         "effective_hbm_GBps": alg_bytes / (wall / args.steps) / 1e9,
         "effective_hbm_frac_of_peak": alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "contraction_TFLOPs": flops_of(w) / dev / 1e12,
+        # secondary check: the butterflies against the FP32 vector rate this pool allows (packed FP32 is switched
+        # off, so a CU array issues 78.6 TFLOP/s of FMAs, half the published 157.3)
+        "transform_TFLOPs": transform_flops_of(w) / dev / 1e12,
+        "transform_frac_of_unpacked_fp32_vector_peak": transform_flops_of(w) / dev / 1e12 / 78.6,
         "roofline": roofline_entry(w, dev, kernel_1d if w.dims == 1 else "tfno_spectral_conv2d (k_fwd2d, k_cgemm_modes, k_inv2d)", st),
     }
 
