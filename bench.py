@@ -372,6 +372,10 @@ def main():
                     help="seconds of untimed calls before the warm-up steps that bring the engine clock from idle to "
                          "its sustained value (0 for counter-collection runs, where every launch is slow)")
     ap.add_argument("--no-extras", action="store_true", help="skip the staged, 2-D and CPU-baseline legs")
+    ap.add_argument("--only", default=None, choices=["per_mode_weights", "real_1d"],
+                    help="time just this layer on --config and print a short JSON line (for profiler runs of the "
+                         "kernels behind the widened entry points): per_mode_weights = tfno_spectral_conv{1,2}d_permode, "
+                         "real_1d = tfno_spectral_conv1d_real")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of one workload, time every cell of the hidden-dimension sweep (B=512, N=256, C in "
                          "{32,64,128,256}, K in {32,64,128}) with the fused kernel (the paper's variant D), the two "
@@ -424,6 +428,13 @@ def main():
         return
 
     w = pick_config(args.config)
+    if args.only:
+        fn = measure_permode if args.only == "per_mode_weights" else measure_real
+        devo, nbo = fn(torch, binding, w, args.steps, args.warmup, args.ramp)
+        print(json.dumps({"metric": args.only, "workload": w.name, "us_per_layer": devo * 1e6, "steps": args.steps,
+                          "warmup": args.warmup, "bytes_per_layer": nbo, "hbm_frac": nbo / devo / 1e9 / HBM_PEAK_GBPS,
+                          "dtype": "f32", "data": "synthetic", "n_gpus": 1}), flush=True)
+        return
     vid = ["fused", "staged", "pruned", "fft_gemm", "gemm_ifft", "auto"].index(args.variant)
     st = {}
     wall, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp, variant=vid, stats=st)
