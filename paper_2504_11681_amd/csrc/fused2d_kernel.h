@@ -38,11 +38,15 @@ namespace tfno {
 // RP16: 16-row passes with two tile buffers (one barrier per pass) instead of 32-row passes with one buffer
 template <int N1, int N2, int K1, int K2, bool RP16>
 struct Cfg2d {
-    static constexpr int NT = 256;
     static constexpr int LPR = N2 / 16;                         // lanes per row
     static constexpr int RP = RP16 ? 16 : 32;                   // rows per pass
-    static constexpr int RPS = (NT / LPR) < RP ? NT / LPR : RP; // rows per sweep of the workgroup
+    static constexpr int RPS = (256 / LPR) < RP ? 256 / LPR : RP; // rows per sweep of the workgroup
     static constexpr int ACTIVE = RPS * LPR;                    // threads that take part in the row stage
+    // Workgroup size: the larger of the row stage's threads and the column stage's (four lanes per column k2).  Rows
+    // of 64 points keep 128 threads busy in the row stage; with 256 threads per workgroup half of every workgroup's
+    // registers belonged to waves that only met the barriers, and half as many images were in flight per CU.
+    static constexpr int NT = ACTIVE > 4 * K2 ? ACTIVE : 4 * K2;
+    static constexpr int WG_PER_CU = 768 / NT;                  // twelve waves per CU whatever the workgroup size
     static constexpr int S = N1 / RP;                           // passes
     static constexpr int SWEEPS = RP / RPS;
     static constexpr int NSWEEP = S * SWEEPS;
@@ -123,7 +127,7 @@ __device__ __forceinline__ long long spec_index(long long b, int c, int C, int m
 // real row is the complex one with zero imaginary part, and the C2R inverse equals twice the real part of the
 // zero-padded complex inverse once the k2 = 0 column is halved (done here, at the spectrum store).
 template <int N1, int N2, int K1, int K2, bool FNO = false>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__((Cfg2d<N1, N2, K1, K2, N2 == 256>::NT), (Cfg2d<N1, N2, K1, K2, N2 == 256>::WG_PER_CU))
 k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, int K2_keep, int h1)
 {
     using C = Cfg2d<N1, N2, K1, K2, N2 == 256>;
@@ -282,7 +286,7 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, 
 
 // ------------------------------------------------------------------------------------------------ inverse
 template <int N1, int N2, int K1, int K2, bool FNO = false>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__((Cfg2d<N1, N2, K1, K2, false>::NT), (Cfg2d<N1, N2, K1, K2, false>::WG_PER_CU))
 k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out, int h1)
 {
     using C = Cfg2d<N1, N2, K1, K2, false>;
