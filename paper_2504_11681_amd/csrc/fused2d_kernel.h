@@ -162,13 +162,20 @@ k_fwd2d(const c64 *__restrict__ x, c64 *__restrict__ Xh, int C_in, int K1_keep, 
         const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
         const XT *src = img + (long long)(r + S * s) * N2 + p;
         if (row_on) {
+            if constexpr (FNO) {
+                // (real rows; fetching pairs of floats and swapping halves between neighbouring lanes, as the inverse
+                // kernel's stores do, measured 2 - 6 % slower here: the loads are not the limit)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                // (quarter-line pieces per row and instruction, LPR = 4, measured 13 % faster through the cache)
-                // (non-temporal where measured to help: 256-point rows, 312 -> 267 us on the 256 x 256 layer)
-                if constexpr (FNO) v[j] = make_float2(LPR >= 16 ? __builtin_nontemporal_load(src + LPR * j) : src[LPR * j], 0.f);
-                else if constexpr (LPR >= 8) v[j] = load_nt(src + LPR * j);
-                else v[j] = src[LPR * j];
+                for (int j = 0; j < 16; ++j)
+                    v[j] = make_float2(LPR >= 16 ? __builtin_nontemporal_load(src + LPR * j) : src[LPR * j], 0.f);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    // (quarter-line pieces per row and instruction, LPR = 4, measured 13 % faster through the cache)
+                    // (non-temporal where measured to help: 256-point rows, 312 -> 267 us on the 256 x 256 layer)
+                    if constexpr (LPR >= 8) v[j] = load_nt(src + LPR * j);
+                    else v[j] = src[LPR * j];
+                }
             }
         }
     };
@@ -382,14 +389,34 @@ k_inv2d(const c64 *__restrict__ Yh, c64 *__restrict__ y, int C_out, int h1)
         if (!row_on) return;
         const int r = (sweep / SWEEPS + r_rot) & (S - 1), s = (sweep % SWEEPS) * RPS + g;
         XT *dst = img + (long long)(r + S * s) * N2 + p;
+        if constexpr (FNO) {
+            // The C2R result: the real part (the scale 2 / (N1 N2) is in W).  Lane p owns the floats p + LPR j; stored one
+            // by one, the LPR lanes of a row write LPR * 4 bytes per instruction (16-byte pieces for 64-point rows).
+            // Instead an even lane writes the pair (p, p + 1) of segment 2u and its odd neighbour the pair of segment
+            // 2u + 1, after the two have swapped the halves that belong to each other: twice the bytes per piece, whole
+            // lines for 256-point rows (64 x 64 fields: inverse kernel 99 -> 84 us).
+            const int odd = p & 1;
+            XT *pair = dst - odd;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            // non-temporal only where the LPR lanes of a row write whole 128-byte lines: with narrower rows every
-            // store instruction leaves half or quarter lines, which cost up to 40 % of the kernel time when they
-            // bypass the cache that would have merged them
-            if constexpr (FNO) dst[LPR * j] = out[j].x;    // the C2R result: the real part (the scale 2 / (N1 N2) is in W)
-            else if constexpr (LPR >= 16) store_nt(dst + LPR * j, out[j]);
-            else dst[LPR * j] = out[j];
+            for (int u = 0; u < 8; ++u) {
+                const float recv = quad_perm<QP_XOR1>(odd ? out[2 * u].x : out[2 * u + 1].x);
+                tfno_vf2 q;
+                q.x = odd ? recv : out[2 * u].x;
+                q.y = odd ? out[2 * u + 1].x : recv;
+                tfno_vf2 *q2 = reinterpret_cast<tfno_vf2 *>(pair + LPR * (2 * u + odd));
+                if constexpr (LPR >= 16) __builtin_nontemporal_store(q, q2);       // whole 128-byte lines
+                else *q2 = q;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                // non-temporal only where the LPR lanes of a row write whole 128-byte lines: with narrower rows every
+                // store instruction leaves half or quarter lines, which cost up to 40 % of the kernel time when they
+                // bypass the cache that would have merged them.  (Pairing complex elements between neighbouring
+                // lanes as above, 16 bytes per lane, measured no faster for 64- and 128-point rows.)
+                if constexpr (LPR >= 16) store_nt(dst + LPR * j, out[j]);
+                else dst[LPR * j] = out[j];
+            }
         }
     };
 
