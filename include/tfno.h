@@ -44,8 +44,9 @@
  *    every stream has passed the calls that used it (a captured HIP graph keeps the address it was captured with).
  *  - Two environment variables, read once per process, select alternative kernels for A/B measurements and tests:
  *    TFNO_CONTRACTION=f32 (FP32-MFMA contractions instead of the exact-split BF16 ones) and, for N = 1024,
- *    TFNO_KERNEL=ws | generic (the wave-specialised or the four-wave kernel instead of the default).  Results stay
- *    within the same tolerance; production callers leave both unset.
+ *    TFNO_KERNEL=ws | generic | sym (the wave-specialised, the four-wave or the symmetric-wave kernel whatever the
+ *    batch size, instead of the per-shape default).  Results stay within the same tolerance; production callers
+ *    leave both unset.
  */
 #ifndef TFNO_H
 #define TFNO_H

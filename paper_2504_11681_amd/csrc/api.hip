@@ -434,7 +434,9 @@ hipError_t fused1d_real_launch(int N, int K, const Fused1dArgs &a, long long row
 {
     if (!fused1d_real_supported(N, K)) return hipErrorInvalidValue;
     // N = 1024: the symmetric-wave kernel where it exists and no bins are masked (it has no mode mask)
-    if (fused1d_sym_supported(N, K) && a.K_keep == K && kernel_choice() == 0 && !contraction_forced_f32())
+    // (fewer than half a chip of workgroups: the four-wave kernel's narrower slabs, unless TFNO_KERNEL=sym)
+    const bool sym_fills = (kernel_choice() == 0 && rows * ((a.C_out + 127) / 128) >= 128) || kernel_choice() == 3;
+    if (fused1d_sym_supported(N, K) && a.K_keep == K && sym_fills && !contraction_forced_f32())
         return fused1d_sym_real_launch(N, K, a, rows, s);
     switch (N) {
     case 64: return fused1d_real_launch_n64(K, a, rows, s);
@@ -468,13 +470,14 @@ bool contraction_forced_f32()
     return forced;
 }
 
-// TFNO_KERNEL (read once): 0 default, 1 "ws", 2 "generic"
+// TFNO_KERNEL (read once): 0 default, 1 "ws", 2 "generic", 3 "sym"
 static int kernel_choice()
 {
     static const int which = [] {
         const char *e = getenv("TFNO_KERNEL");
         if (e && e[0] == 'w' && e[1] == 's' && e[2] == 0) return 1;
         if (e && e[0] == 'g' && e[1] == 'e' && e[2] == 'n') return 2;
+        if (e && e[0] == 's' && e[1] == 'y' && e[2] == 'm' && e[3] == 0) return 3;
         return 0;
     }();
     return which;
@@ -492,8 +495,13 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
         const int which = kernel_choice();
         // (they have no mode mask: a request for fewer modes than the kernel's K runs on the four-wave kernel)
         const bool exact = a.K_keep == 0 || a.K_keep == K;
-        if (exact && which == 0 && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
-        if (exact && which != 2 && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
+        // (and one workgroup per batch row and 128 outputs: below half a chip of such workgroups the four-wave kernel
+        // with its narrower output slabs puts the idle CUs to work -- B = 64, C = 128: 70 against 83 us; B = 64, C = 64:
+        // 41 against 62 us; from B = 128 on the symmetric kernel is level or ahead)
+        // TFNO_KERNEL=sym keeps the symmetric kernel for every batch size.
+        const bool fills = rows * ((a.C_out + 127) / 128) >= 128;
+        if (exact && ((which == 0 && fills) || which == 3) && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
+        if (exact && (which == 1 || (which == 0 && fills)) && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
     }
     switch (N) {
     case 64: return fused1d_launch_n64(K, a, rows, s);

@@ -86,6 +86,8 @@ SMALL_1D = [
     (2, 32, 128, 1024, 128),
     (1, 48, 256, 1024, 64),
     (2, 16, 128, 1024, 128),
+    (128, 16, 128, 1024, 64),   # half a chip of workgroups: the symmetric-wave kernel by default (below: the four-wave one)
+    (70, 9, 130, 1024, 128),    # ... with masks (70 rows x 2 slabs)
 ]
 
 
@@ -467,7 +469,9 @@ REAL_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 8), (2, 33, 40, 64, 32), (3, 9, 70
            (2, 128, 128, 1024, 128),
            # N = 1024 on the symmetric-wave kernel: whole blocks without the deep pipeline, K = 64 deep, and a mode
            # count between the built sizes (stays on the four-wave kernel, which masks bins)
-           (2, 16, 128, 1024, 64), (2, 64, 256, 1024, 64), (2, 9, 11, 1024, 100)]
+           (2, 16, 128, 1024, 64), (2, 64, 256, 1024, 64), (2, 9, 11, 1024, 100),
+           # enough workgroups for the symmetric-wave kernel by default (smaller batches run the four-wave kernel)
+           (128, 16, 128, 1024, 64), (70, 9, 130, 1024, 128)]
 
 
 @pytest.mark.parametrize("shape", REAL_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
@@ -1004,10 +1008,12 @@ SYM_1D = [(2, 32, 128, 1024, 128),   # two blocks of loads in flight (even block
           (1, 1, 1, 1024, 64)]
 
 
-@pytest.mark.parametrize("kernel", ["ws", "generic"])
+@pytest.mark.parametrize("kernel", ["ws", "generic", "sym"])
 def test_alternative_n1024_kernels_in_a_child_process(gpu, oracle_mod, tmp_path, kernel):
-    """N = 1024 runs the symmetric-wave kernel by default (K in {64, 128}); TFNO_KERNEL (read once per process)
-    selects the wave-specialised kernel (ws) or the generic four-wave kernel (generic) instead."""
+    """N = 1024 runs the symmetric-wave kernel by default when the grid fills half the chip (K in {64, 128}) and the
+    four-wave kernel below that; TFNO_KERNEL (read once per process) selects the wave-specialised kernel (ws), the
+    four-wave kernel (generic) or the symmetric-wave kernel (sym) for every batch size.  The real-valued layer follows
+    the same switch."""
     import os
     import subprocess
     import textwrap
@@ -1023,6 +1029,11 @@ def test_alternative_n1024_kernels_in_a_child_process(gpu, oracle_mod, tmp_path,
             binding.spectral_conv1d(torch.from_numpy(x).cuda(), torch.from_numpy(W).cuda(), y, K)
             torch.cuda.synchronize()
             res['y%d' % i] = y.cpu().numpy()
+            if K <= N // 2:
+                yr = torch.empty((B, Co, N), dtype=torch.float32, device='cuda')
+                binding.spectral_conv1d_real(torch.from_numpy(np.ascontiguousarray(x.real)).cuda(), torch.from_numpy(W).cuda(), yr, K)
+                torch.cuda.synchronize()
+                res['r%d' % i] = yr.cpu().numpy()
         np.savez({out!r}, **res)
     """)
     env = dict(os.environ, TFNO_KERNEL=kernel)
@@ -1032,6 +1043,10 @@ def test_alternative_n1024_kernels_in_a_child_process(gpu, oracle_mod, tmp_path,
     for i, (B, Ci, Co, N, K) in enumerate(SYM_1D):
         x = inputs.make_x(40 + i, B, Ci, (N,)); W = inputs.make_W(40 + i, Ci, Co)
         check(got["y%d" % i], oracle_mod.spectral_conv1d(x, W, K)[0], f"{kernel} {(B, Ci, Co, N, K)}")
+        wantr = oracle_mod.spectral_conv1d_real(np.ascontiguousarray(x.real), W, K)[0]
+        gotr = got["r%d" % i].astype(np.float64)
+        assert np.linalg.norm((gotr - wantr).ravel()) <= 1e-5 * np.linalg.norm(wantr.ravel()), (kernel, "real", i)
+        assert np.abs(gotr - wantr).max() <= 1e-4 * np.abs(wantr).max(), (kernel, "real", i)
 
 
 def test_fp32_contraction_kernels_in_a_child_process(gpu, oracle_mod, tmp_path):
