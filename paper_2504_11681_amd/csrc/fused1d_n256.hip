@@ -10,13 +10,17 @@ namespace tfno {
 //   C_out > 128: one workgroup covers 256 outputs, so x is read and transformed once per batch row: the two-group
 //       kernel for K = 32 and 64 where the channel counts are whole blocks (130 / 160 us against 155 / 185 us for two
 //       128-output workgroups per row), the eight-wave kernel otherwise and for K = 128 (247 against 299 us);
-//   everything else: the four-wave double-buffered kernel, two workgroups per CU wherever its LDS allows.
+//   everything else (and batches too small to give the special kernels a workgroup per CU): the four-wave
+//       double-buffered kernel, two workgroups per CU wherever its LDS allows.
 // TFNO_KERNEL=generic keeps the four-wave double-buffered kernel everywhere (A/B measurements).
 template <int K>
 static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipStream_t s, bool *done)
 {
     *done = true;
-    if (a.C_out > 128) {
+    // (a 256-output workgroup per batch row needs about as many rows as CUs: B = 128, C = 256: 59 / 94 us at K = 64 / 128
+    // against 53 / 74 us for the four-wave kernel's 128-output slabs, B = 64: 58 / 93 against 43 / 51 us; B = 256:
+    // 80 / 117 against 89 / 148 us)
+    if (a.C_out > 128 && rows >= 192) {
         if constexpr (K != 128) {
             if (a.inner_count == 1 && fused1d_pp_supported(256, K, a.C_in, a.C_out)) return fused1d_pp_launch(256, K, a, rows, s);
         }

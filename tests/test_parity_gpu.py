@@ -816,12 +816,14 @@ N256_SPECIAL = [
     (260, 20, 33, 256, 100),     # single tile, masked, 64-output slab, K rounded up to 128
     (257, 9, 30, 256, 128),      # single tile, masked, 32-output slab
     (258, 16, 64, 256, 128),     # single tile, whole blocks
-    (3, 64, 256, 256, 48),       # two-group kernel, K rounded up to 64
-    (2, 64, 160, 256, 64),       # two-group kernel, three of eight output slabs absent
-    (2, 96, 192, 256, 32),       # two-group kernel, six 16-channel blocks
-    (2, 128, 256, 256, 128),     # eight-wave kernel, whole blocks
-    (2, 70, 200, 256, 128),      # eight-wave kernel, masked
-    (2, 48, 136, 256, 32),       # eight-wave kernel (48 channels are not whole 32-channel blocks), masked
+    # (the 256-output kernels take over from 192 batch rows on)
+    (193, 64, 256, 256, 48),     # two-group kernel, K rounded up to 64
+    (192, 64, 160, 256, 64),     # two-group kernel, three of eight output slabs absent
+    (200, 96, 192, 256, 32),     # two-group kernel, six 16-channel blocks
+    (192, 128, 256, 256, 128),   # eight-wave kernel, whole blocks
+    (195, 70, 200, 256, 128),    # eight-wave kernel, masked
+    (200, 48, 136, 256, 32),     # eight-wave kernel (48 channels are not whole 32-channel blocks), masked
+    (191, 64, 256, 256, 64),     # one row short of the rule: the four-wave kernel, two 128-output slabs per row
 ]
 
 
