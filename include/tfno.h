@@ -267,9 +267,9 @@ tfno_status tfno_spectral_conv1d_gemm_ifft(const void *x, const void *W, void *y
 
 /*
  * Per-shape dispatch (variant "E" of Table 2, Sec. 5: the best of the variants for each shape), with the rule
- * measured on MI355X: the CGEMM + iFFT variant when C_out > 128, N != 256 and that variant exists for (N, K) (there
- * the fully fused kernel repeats the forward transform for every 128-output slab; at N = 256 it covers 256 outputs
- * per workgroup and is the fastest variant), else the fully fused kernel where one exists, else the three pruned kernels of tfno_spectral_conv1d_pruned where they exist (N = 2048, 4096), else the
+ * measured on MI355X: the CGEMM + iFFT variant when C_out > 128, N = 128 and K <= 32 (the fully fused kernel
+ * repeats the forward transform for every 128-output slab, which only there costs more than the detour of the
+ * truncated spectrum; at N = 256 it covers 256 outputs per workgroup), else the fully fused kernel where one exists, else the three pruned kernels of tfno_spectral_conv1d_pruned where they exist (N = 2048, 4096), else the
  * staged path.  Accepts every valid 1-D shape; same contract and same result as
  * tfno_spectral_conv1d.  Workspace: tfno_workspace_bytes(1, 5, ...) bytes (0 when the fused kernel is chosen).
  */

@@ -391,8 +391,10 @@ tfno_status run_fno1d(const void *x, const void *W, void *y, int B, int C_in, in
 // batch row, and the CGEMM + iFFT variant, which transforms once and re-reads only the truncated spectrum, wins.
 Variant choose_variant(int N, int K, int C_out)
 {
-    // (N = 256 has fused kernels that cover 256 outputs per workgroup and beat the CGEMM + iFFT variant there)
-    if (C_out > 128 && N != 256 && round_modes(N, K, fused1d_partial_supported)) return GEMM_IFFT;
+    // (N = 256 has fused kernels that cover 256 outputs per workgroup and beat the CGEMM + iFFT variant there; at
+    // N = 128 the fused kernel wins from K = 64 on -- C 256: 258 against 296 us, K = 128: 447 against 495 us -- and
+    // loses by 3 % at K = 32)
+    if (C_out > 128 && N == 128 && round_modes(N, K, fused1d_partial_supported) == 32) return GEMM_IFFT;
     if (round_modes(N, K, fused1d_supported)) return FUSED;
     // long pencils (N = 2048, 4096) have no fused kernel: one workgroup cannot hold the K >= 128 retained modes of
     // all its output channels; the three pruned kernels move only 4 K / N of the tensor bytes extra

@@ -207,7 +207,9 @@ def test_workspace_contract(L):
     # per-shape dispatch: the workspace of the variant it picks
     assert binding.workspace_bytes(1, 5, 4, 16, 48, 256, 64) == 0                         # fused
     assert binding.workspace_bytes(1, 5, 4, 16, 200, 256, 64) == 0                        # fused (256 outputs per workgroup)
-    assert binding.workspace_bytes(1, 5, 4, 16, 200, 128, 64) == 8 * 2 * 128 * 16         # N = 128: CGEMM + iFFT
+    assert binding.workspace_bytes(1, 5, 4, 16, 200, 128, 64) == 0                        # N = 128, K = 64: fused
+    assert binding.workspace_bytes(1, 5, 4, 16, 200, 128, 32) == 8 * 128 * 16             # N = 128, K = 32: CGEMM + iFFT
+    assert binding.workspace_bytes(1, 5, 4, 16, 200, 128, 20) == 8 * 128 * 16             # ... also for K rounded up to 32
     assert binding.workspace_bytes(1, 5, 2, 3, 4, 2048, 100) == binding.workspace_bytes(1, 2, 2, 3, 4, 2048, 128)  # pruned, K' = 128
     assert binding.workspace_bytes(1, 5, 2, 3, 4, 32, 5) == binding.workspace_bytes(1, 1, 2, 3, 4, 32, 5)          # staged
     assert binding.workspace_bytes(1, 5, 2, 3, 4, 4096, 512) == binding.workspace_bytes(1, 2, 2, 3, 4, 4096, 512)  # pruned

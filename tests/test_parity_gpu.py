@@ -824,6 +824,10 @@ N256_SPECIAL = [
     (195, 70, 200, 256, 128),    # eight-wave kernel, masked
     (200, 48, 136, 256, 32),     # eight-wave kernel (48 channels are not whole 32-channel blocks), masked
     (191, 64, 256, 256, 64),     # one row short of the rule: the four-wave kernel, two 128-output slabs per row
+    # N = 128, K = 64 with more batch rows than CUs: the single-operand-tile kernel (two workgroups per CU)
+    (300, 20, 70, 128, 64), (260, 32, 33, 128, 50), (258, 64, 128, 128, 64), (257, 5, 9, 128, 64),
+    (300, 16, 200, 128, 64),     # ... two slabs per row; the dispatch keeps the fused kernel here
+    (300, 16, 200, 128, 32),     # ... and takes the CGEMM + iFFT variant at K = 32
 ]
 
 
