@@ -10,8 +10,8 @@ namespace tfno {
 //   C_out > 128: one workgroup covers 256 outputs, so x is read and transformed once per batch row: the two-group
 //       kernel for K = 32 and 64 where the channel counts are whole blocks (130 / 160 us against 155 / 185 us for two
 //       128-output workgroups per row), the eight-wave kernel otherwise and for K = 128 (247 against 299 us);
-//   everything else (and batches too small to give the special kernels a workgroup per CU): the four-wave
-//       double-buffered kernel, two workgroups per CU wherever its LDS allows.
+//   at most 256 workgroups of 32 (K <= 64: or 64) outputs: the eight-wave kernel with those slabs;
+//   everything else: the four-wave double-buffered kernel, two workgroups per CU wherever its LDS allows.
 // TFNO_KERNEL=generic keeps the four-wave double-buffered kernel everywhere (A/B measurements).
 template <int K>
 static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipStream_t s, bool *done)
@@ -25,6 +25,15 @@ static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipS
             if (a.inner_count == 1 && fused1d_pp_supported(256, K, a.C_in, a.C_out)) return fused1d_pp_launch(256, K, a, rows, s);
         }
         return launch_fused1d_wide<256, K, 8>(a, rows, s);
+    }
+    // Batches that give at most one workgroup per CU are bound by the latency of one workgroup: eight waves with
+    // 32-output slabs halve the pencil blocks each wave transforms (B = 64, C = 64: 14.6 -> 12.3 us at K = 64,
+    // 13.6 -> 11.7 at K = 32, 14.7 -> 13.2 at K = 128; B = 64, C = 128: 23.2 -> 20.0 us); with 64-output slabs they
+    // still win at K <= 64 (B = 64, C = 256: 42.7 -> 36.9 us; B = 128, C = 128: 25.4 -> 23.9 us).  With more
+    // workgroups than CUs the four-wave kernel's two workgroups per CU are faster (B = 256, C = 64: 17.9 against 26.2 us).
+    if (rows * ((a.C_out + 31) / 32) <= 256) return launch_fused1d_wide<256, K, 1, 8>(a, rows, s);
+    if constexpr (K != 128) {
+        if (rows * ((a.C_out + 63) / 64) <= 256) return launch_fused1d_wide<256, K, 2, 8>(a, rows, s);
     }
     if constexpr (K == 128) {
         // (two workgroups per CU need more batch rows than CUs; below that the double-buffered kernel's single

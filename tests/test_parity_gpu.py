@@ -808,8 +808,8 @@ def test_wide_output_slabs_with_ragged_channels(gpu, oracle_mod):
 
 
 # N = 256 has three more fused kernels behind the dispatch: the single-operand-tile kernel (K = 128, more batch rows
-# than CUs; two workgroups per CU), the eight-wave kernel and the two-group kernel (C_out > 128: 256 outputs per
-# workgroup).  Shapes that reach each of them with whole and ragged channel blocks, absent output slabs and mode counts
+# than CUs; two workgroups per CU), the eight-wave kernel (256 outputs per workgroup for C_out > 128, and 32 or 64 for
+# batches of at most 256 workgroups) and the two-group kernel (C_out > 128: 256 outputs per workgroup).  Shapes that reach each of them with whole and ragged channel blocks, absent output slabs and mode counts
 # between the built sizes.  (B, C_in, C_out, N, K)
 N256_SPECIAL = [
     (300, 5, 70, 256, 128),      # single tile, masked, 128-output slab partly empty
@@ -824,6 +824,14 @@ N256_SPECIAL = [
     (195, 70, 200, 256, 128),    # eight-wave kernel, masked
     (200, 48, 136, 256, 32),     # eight-wave kernel (48 channels are not whole 32-channel blocks), masked
     (191, 64, 256, 256, 64),     # one row short of the rule: the four-wave kernel, two 128-output slabs per row
+    # at most 256 workgroups of 32 (K <= 64: or 64) outputs: eight waves with those slabs
+    (64, 20, 33, 256, 64),       # 32-output slabs, masked, the second slab holds one channel
+    (8, 64, 256, 256, 128),      # 32-output slabs, exactly 256 workgroups, whole blocks
+    (100, 33, 100, 256, 48),     # 64-output slabs (400 workgroups of 32 outputs would be too many), K rounded up
+    (256, 8, 64, 256, 32),       # 64-output slabs, exactly 256 workgroups
+    (257, 5, 64, 256, 32),       # one row more: the four-wave kernel
+    (150, 33, 100, 256, 64),     # 300 workgroups of 64 outputs: the four-wave kernel
+    (100, 7, 100, 256, 128),     # K = 128 has no 64-output eight-wave kernel: the four-wave kernel
     # N = 128, K = 64 with more batch rows than CUs: the single-operand-tile kernel (two workgroups per CU)
     (300, 20, 70, 128, 64), (260, 32, 33, 128, 50), (258, 64, 128, 128, 64), (257, 5, 9, 128, 64),
     (300, 16, 200, 128, 64),     # ... two slabs per row; the dispatch keeps the fused kernel here
