@@ -27,6 +27,8 @@
  *  - Ownership: the caller owns every buffer (including the workspace) and must
  *    keep it alive and unmodified until the stream has passed the call.
  *  - y must not overlap x or W (checked on address ranges: TFNO_ERR_ALIAS).
+ *  - x, W and y must be aligned to 8 bytes (TFNO_ERR_ALIGN), the float32 tensors of the real-valued entry points
+ *    included: complex64 elements move as 8-byte words and the real-valued kernels move pairs of floats.
  *  - Argument errors are detected on the host before anything is launched, so a
  *    failed call has no effect on y.  B == 0 is a valid empty call (TFNO_OK,
  *    nothing launched, pointers may be NULL).
@@ -64,7 +66,8 @@ typedef enum {
     TFNO_ERR_UNSUPPORTED = 3, /* valid shape, but this entry point has no kernel for it   */
     TFNO_ERR_ALIAS = 4,       /* y overlaps x or W                                        */
     TFNO_ERR_WORKSPACE = 5,   /* workspace missing or smaller than tfno_workspace_bytes() */
-    TFNO_ERR_HIP = 6          /* the HIP runtime reported a launch error                  */
+    TFNO_ERR_HIP = 6,         /* the HIP runtime reported a launch error                  */
+    TFNO_ERR_ALIGN = 7        /* x, W or y is not aligned to 8 bytes                      */
 } tfno_status;
 
 /*

@@ -68,6 +68,12 @@ bool sizes_ok(const Shape &sh, int B, int C_in, int C_out, bool any_n = false)
            (sh.dims == 1 || axis_ok(sh.N1, sh.K1, any_n));
 }
 
+// complex64 elements are read and written as 8-byte words, and the real-valued kernels move pairs of floats
+bool aligned8(const void *a, const void *b, const void *c)
+{
+    return (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c) & 7u) == 0;
+}
+
 // Everything that can be decided on the host.  *empty is set for a valid call with nothing to do.
 tfno_status validate(const Shape &sh, const void *x, const void *W, const void *y, int B, int C_in, int C_out,
                      bool *empty, bool per_mode = false, bool any_n = false)
@@ -87,6 +93,7 @@ tfno_status validate(const Shape &sh, const void *x, const void *W, const void *
     const size_t xb = sizeof(c64) * (size_t)B * C_in * pts, yb = sizeof(c64) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out * (per_mode ? sh.kpts() : 1);
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!aligned8(x, W, y)) return TFNO_ERR_ALIGN;
     return TFNO_OK;
 }
 
@@ -296,6 +303,7 @@ tfno_status run_real1d(const void *x, const void *W, void *y, int B, int C_in, i
     const size_t xb = sizeof(float) * (size_t)B * C_in * N, yb = sizeof(float) * (size_t)B * C_out * N;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out;
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!aligned8(x, W, y)) return TFNO_ERR_ALIGN;
     const int Kk = round_modes(N, K, fused1d_real_supported);       // the kernel's K; bins K .. Kk-1 are zeroed
     if (!Kk) return TFNO_ERR_UNSUPPORTED;
     Fused1dArgs a{};
@@ -333,6 +341,7 @@ tfno_status run_fno2d(const void *x, const void *W, void *y, int B, int C_in, in
     const size_t xb = sizeof(float) * (size_t)B * C_in * pts, yb = sizeof(float) * (size_t)B * C_out * pts;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out * 2 * M1 * M2;
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!aligned8(x, W, y)) return TFNO_ERR_ALIGN;
     if (!have) return TFNO_ERR_UNSUPPORTED;
     void *wsp = nullptr;
     tfno_status st = check_workspace(fused2d_workspace_bytes(B, C_in, C_out, K1, K2), x, xb, W, wb, y, yb, &wsp);
@@ -369,6 +378,7 @@ tfno_status run_fno1d(const void *x, const void *W, void *y, int B, int C_in, in
     const size_t xb = sizeof(float) * (size_t)B * C_in * N, yb = sizeof(float) * (size_t)B * C_out * N;
     const size_t wb = sizeof(c64) * (size_t)C_in * C_out * M;
     if (overlaps(y, yb, x, xb) || overlaps(y, yb, W, wb)) return TFNO_ERR_ALIAS;
+    if (!aligned8(x, W, y)) return TFNO_ERR_ALIGN;
     if (!K) return TFNO_ERR_UNSUPPORTED;
     void *wsp = nullptr;
     tfno_status st = check_workspace(pruned1d_workspace_bytes(B, C_in, C_out, K), x, xb, W, wb, y, yb, &wsp);
@@ -692,6 +702,7 @@ const char *tfno_status_string(tfno_status s)
     case TFNO_ERR_ALIAS: return "y or the workspace overlaps another buffer";
     case TFNO_ERR_WORKSPACE: return "workspace missing or too small (see tfno_workspace_bytes), or the shape needs more than the built-in scratch";
     case TFNO_ERR_HIP: return "the HIP runtime reported an error at launch";
+    case TFNO_ERR_ALIGN: return "x, W or y is not aligned to 8 bytes";
     default: return "unknown status";
     }
 }

@@ -34,8 +34,8 @@ def test_every_declared_symbol_is_exported(L):
 
 def test_version_and_status_strings(L):
     assert binding.version() >= 100
-    seen = {binding.status_string(s) for s in range(7)}
-    assert len(seen) == 7 and all(seen)
+    seen = {binding.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and all(seen)
 
 
 FAKE = 0x10000000  # never dereferenced: all of these calls fail validation before any launch
@@ -61,6 +61,9 @@ def test_argument_errors_are_caught_on_the_host(L, name):
     assert call(L, name, x, W, x, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
     assert call(L, name, x, W, x + 8, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
     assert call(L, name, x, W, W, 2, 4, 4, 64, 16) == binding.ERR_ALIAS
+    # complex64 elements move as 8-byte words
+    for (dx, dw, dy) in ((4, 0, 0), (0, 4, 0), (0, 0, 4), (1, 0, 0)):
+        assert call(L, name, x + dx, W + dw, y + dy, 2, 4, 4, 64, 16) == binding.ERR_ALIGN
     # empty batch: valid, nothing to do, pointers may be NULL
     assert call(L, name, None, None, None, 0, 4, 4, 64, 16) == binding.OK
 
@@ -126,6 +129,9 @@ def test_real_layer_argument_checks(L):
     # float tensors: y right behind x (4 B per element) does not overlap, y inside x does
     assert f(x, W, x + 4 * 2 * 4 * 64 - 4, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
     assert f(x, W, W, 2, 4, 4, 64, 16, None) == binding.ERR_ALIAS
+    # the real-valued kernels move pairs of floats
+    assert f(x + 4, W, y, 2, 4, 4, 64, 16, None) == binding.ERR_ALIGN
+    assert f(x, W, y + 4, 2, 4, 4, 64, 16, None) == binding.ERR_ALIGN
     assert f(None, None, None, 0, 4, 4, 64, 16, None) == binding.OK
 
 
@@ -140,6 +146,7 @@ def test_fno2d_argument_checks_and_workspace(L):
     assert f(x, W, y, 2, 4, 4, 512, 64, 12, 12, None) == binding.ERR_UNSUPPORTED
     assert f(x, W, y, 2, 4, 4, 256, 256, 40, 12, None) == binding.ERR_UNSUPPORTED   # 2 M1 > 64
     assert f(x, W, x, 2, 4, 4, 64, 64, 12, 12, None) == binding.ERR_ALIAS
+    assert f(x, W, y + 4, 2, 4, 4, 64, 64, 12, 12, None) == binding.ERR_ALIGN
     assert f(x, W, y, 2, 4, 4, 64, 64, 12, 12, None) == binding.ERR_WORKSPACE
     assert f(None, None, None, 0, 4, 4, 64, 64, 12, 12, None) == binding.OK
     wsb = L.tfno_fno2d_real_workspace_bytes
@@ -158,6 +165,7 @@ def test_fno1d_argument_checks_and_workspace(L):
     assert f(x, W, y, 2, 4, 4, 512, 16, None) == binding.ERR_UNSUPPORTED
     assert f(x, W, y, 2, 4, 4, 1024, 200, None) == binding.ERR_UNSUPPORTED
     assert f(x, W, x, 2, 4, 4, 64, 12, None) == binding.ERR_ALIAS
+    assert f(x + 4, W, y, 2, 4, 4, 64, 12, None) == binding.ERR_ALIGN
     assert f(x, W, y, 2, 4, 4, 64, 12, None) == binding.ERR_WORKSPACE
     assert f(None, None, None, 0, 4, 4, 64, 12, None) == binding.OK
     assert L.tfno_fno1d_real_workspace_bytes(4, 16, 16, 64, 12) == binding.workspace_bytes(1, 2, 4, 16, 16, 64, 16)
