@@ -55,7 +55,11 @@ template <> struct Decomp<1024> { static constexpr int P = 32, T = 32; };
 //               prologue and epilogue hide under the other's work (with one wave per SIMD nothing else hides them).
 //   NW 8, XB 1: two waves per SIMD in one workgroup; a block is twice as many channels; carries the 256-output slab
 //               (OT = 8) at K = 128, whose accumulators alone are half of the CU's register file.
-template <int N, int K, int OT, bool BF = false, int NW_ = 4, int XB_ = 2>
+// KS: (NW 8, XB 1 only) the 8-channel steps of a block are dealt out to KS waves per 32 x 32 tile, each with its own
+//     partial accumulator; the partial sums meet in the epilogue's LDS tile.  For narrow slabs (one or two tiles) this
+//     puts the contraction on all eight waves instead of one or two, which is what a workgroup that has the CU to
+//     itself (small batches) is waiting for.
+template <int N, int K, int OT, bool BF = false, int NW_ = 4, int XB_ = 2, int KS_ = 1>
 struct FusedCfg {
     static constexpr int P = Decomp<N>::P, T = Decomp<N>::T;
     static constexpr int Q = K / P;                 // retained outputs per column of stage B
@@ -70,18 +74,19 @@ struct FusedCfg {
     static constexpr int KT = (K + 31) / 32;        // 32-mode MFMA tiles
     static constexpr int KPAD = KT * 32;
     static constexpr int TILES = OT * KT;
-    static constexpr int TPW = (TILES + NW - 1) / NW;   // 32x32 complex tiles per wave
-    static constexpr bool ALLT = TILES % NW == 0;       // every wave owns exactly TPW tiles
-    static constexpr bool DIRECT = P == 32 && OT == NW && TPW == KT;   // wave w owns output slab w entirely
+    static constexpr int KS = KS_;                      // waves that share one tile's channel steps
+    static constexpr int TPW = KS > 1 ? 1 : (TILES + NW - 1) / NW;     // 32x32 complex tiles per wave
+    static constexpr bool ALLT = KS > 1 ? TILES * KS == NW : TILES % NW == 0;   // every wave owns exactly TPW tiles
+    static constexpr bool DIRECT = KS == 1 && P == 32 && OT == NW && TPW == KT;   // wave w owns output slab w entirely
     static constexpr int RPA = 32 / T;              // direct epilogue: stage-B' rounds per stage-A' round
     static constexpr int ZROW = T + 1;
     static constexpr int ZS = P * ZROW + (T == 8 ? 8 - (P * ZROW) % 16 + ((P * ZROW) % 16 > 8 ? 16 : 0) : 0);
     static constexpr int YROW = K + 1;
     static constexpr int XH_BUF = BF ? 3 * (PPI / 4) * KT * 128 : PPI * 2 * KPAD;   // 4-byte words per XH buffer
-    static constexpr int NWV = BF ? PPI / 2 : PPI;  // W values a lane holds per iteration
+    static constexpr int NWV = BF ? PPI / 2 / KS : PPI;  // W values a lane holds per iteration
     static constexpr size_t LDS_Z = sizeof(c64) * NW * PPW * ZS;
     static constexpr size_t LDS_XH = sizeof(float) * XB * XH_BUF;
-    static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * 32 * YROW;
+    static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * KS * 32 * YROW;
     static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [t][p] (static)
     static constexpr size_t LDS_DYN = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH);   // dynamic part
     static constexpr size_t LDS_BYTES = LDS_DYN + LDS_TW;
@@ -91,6 +96,8 @@ struct FusedCfg {
     static_assert(PPI % 8 == 0, "an iteration is a whole number of 8-channel MFMA steps");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
     static_assert(TPW * 32 <= 128, "accumulators must fit the register file");
+    static_assert(KS == 1 || (XB == 1 && NW == 8 && BF && TILES * KS <= NW && (PPI / 8) % KS == 0),
+                  "the channel steps of a block are split over the waves of the eight-wave kernel only");
     static constexpr bool FITS = LDS_BYTES <= 160 * 1024;           // LDS budget of one gfx950 CU
     // Two workgroups per CU (two waves per SIMD, 256 registers each) wherever the accumulators leave room and LDS
     // allows: left to itself the compiler takes more than 256 registers for TPW = 2 and halves the occupancy.
@@ -112,11 +119,11 @@ __device__ __forceinline__ void wave_sync()
 // transform of a real pencil is the complex one with a zero imaginary part, whose first K bins are the R2C bins;
 // the C2R inverse of the zero-padded half spectrum is (2/N) Re( sum_k Y'[k] e^(+2 pi i k n / N) ) with Y'[0] = Y[0]/2,
 // so bin 0 is halved on its way into the operand tile, the caller passes scale = 2/N, and only real parts are stored.
-template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0, bool REAL = false, int NW = 4, int XB = 2>
-__global__ void __launch_bounds__((FusedCfg<N, K, OT, BF, NW, XB>::NT), (FusedCfg<N, K, OT, BF, NW, XB>::MIN_WG_PER_CU))
+template <int N, int K, int OT, bool EVEN, bool BF, int MODE = 0, bool REAL = false, int NW = 4, int XB = 2, int KS = 1>
+__global__ void __launch_bounds__((FusedCfg<N, K, OT, BF, NW, XB, KS>::NT), (FusedCfg<N, K, OT, BF, NW, XB, KS>::MIN_WG_PER_CU))
 k_fused1d(Fused1dArgs a)
 {
-    using C = FusedCfg<N, K, OT, BF, NW, XB>;
+    using C = FusedCfg<N, K, OT, BF, NW, XB, KS>;
     static_assert(!C::WIDE || (MODE == 0 && !REAL), "the eight-wave kernel is the fully fused complex layer only");
     static_assert(C::FITS, "LDS budget of one gfx950 CU");
     constexpr int NWV = C::NWV;
@@ -158,11 +165,17 @@ k_fused1d(Fused1dArgs a)
     const int jw = lane / T, t = lane % T;
     const int ja = wave * PPW + jw;
     c64 *Zw = Zl + wave * (PPW * ZS);
-    for (int i = tid; i < N; i += NT) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
-    __syncthreads();
+    // (called once the first loads are on their way: the table is built while they are in flight)
+    auto build_twiddles = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        for (int i = tid; i < N; i += NT) TW[i] = cis2pi(-(float)((i / P) * (i % P)), (float)N);
+        __syncthreads();
+    };
 
-    // MFMA tile identity of this wave: tiles tile0 .. tile0+TPW-1, all in output slab `ot_w`
-    const int tile0 = wave * TPW;
+    // MFMA tile identity of this wave: tiles tile0 .. tile0+TPW-1, all in output slab `ot_w`; with KS > 1 one tile,
+    // shared with KS - 1 other waves, of which this one takes the 8-channel steps s KS + part
+    const int tile0 = KS > 1 ? wave / KS : wave * TPW;
+    const int part = KS > 1 ? wave % KS : 0;
     const bool has_tiles = ALLT || tile0 < C::TILES;
     const int ot_w = tile0 / KT, kt0 = tile0 % KT;
     floatx16 acc_re[TPW], acc_im[TPW];
@@ -180,7 +193,7 @@ k_fused1d(Fused1dArgs a)
     // the BF16 path, the four channels 8 s + 4 (lane / 32) + d of every 8-channel step s, at index 4 s + d
     c64 wv[NWV];
     auto wv_channel = [&](int i) __attribute__((always_inline)) {
-        return BF ? 8 * (i / 4) + 4 * (lane >> 5) + (i % 4) : i;
+        return BF ? 8 * ((i / 4) * KS + part) + 4 * (lane >> 5) + (i % 4) : i;
     };
 
     auto load_pencil = [&](int c0) __attribute__((always_inline)) {
@@ -343,12 +356,12 @@ k_fused1d(Fused1dArgs a)
         auto read_b = [&](uintx4 *b, int n) __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < 3; ++t)
-                b[t] = *reinterpret_cast<const uintx4 *>(XS + ((t * (PPI / 4) + 2 * (n / TPW)) * KT + n % TPW) * 128);
+                b[t] = *reinterpret_cast<const uintx4 *>(XS + ((t * (PPI / 4) + 2 * ((n / TPW) * KS + part)) * KT + n % TPW) * 128);
         };
         uintx4 b[2][3];
         read_b(b[0], 0);
 #pragma unroll
-        for (int s = 0; s < PPI / 8; ++s) {
+        for (int s = 0; s < PPI / 8 / KS; ++s) {
             uintx4 a_re[3], a_im[3];
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -364,7 +377,7 @@ k_fused1d(Fused1dArgs a)
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
                 const int n = s * TPW + i;
-                if (n + 1 < (PPI / 8) * TPW) read_b(b[(n + 1) & 1], n + 1);
+                if (n + 1 < (PPI / 8 / KS) * TPW) read_b(b[(n + 1) & 1], n + 1);
 #pragma unroll
                 for (int k = 0; k < 6; ++k) {
                     const bf16x8 bb16 = __builtin_bit_cast(bf16x8, b[n & 1][SB[k]]);
@@ -420,6 +433,7 @@ k_fused1d(Fused1dArgs a)
     // ------------------------------------------------------------------ k-loop over input channels
     if constexpr (C::WIDE) {
         load_pencil(0);
+        build_twiddles();
         stage_a();
         wave_sync();
         if (n_it > 1) load_pencil(PPI);
@@ -430,6 +444,7 @@ k_fused1d(Fused1dArgs a)
     } else if constexpr (MODE != 2) {
         load_pencil(0);
         load_w(wv, 0);
+        build_twiddles();
         stage_a();
         wave_sync();
         if (n_it > 1) load_pencil(PPI);
@@ -495,6 +510,7 @@ k_fused1d(Fused1dArgs a)
         };
         load_spec(0);
         load_w(wv, 0);
+        build_twiddles();
         put_spec(0);
         if (n_it > 1) load_spec(PPI);
         __syncthreads();
@@ -591,7 +607,7 @@ k_fused1d(Fused1dArgs a)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int ol = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                            YH[ol * YROW + k] = make_float2(acc_re[i][r], acc_im[i][r]);
+                            YH[(part * 32 + ol) * YROW + k] = make_float2(acc_re[i][r], acc_im[i][r]);
                         }
                     }
                 }
@@ -606,7 +622,11 @@ k_fused1d(Fused1dArgs a)
                     const int ol = C::RPW * wave + rd * PPW + j;
                     c64 yin[Q];
 #pragma unroll
-                    for (int q = 0; q < Q; ++q) yin[q] = YH[ol * YROW + p + P * q];
+                    for (int q = 0; q < Q; ++q) {
+                        yin[q] = YH[ol * YROW + p + P * q];
+#pragma unroll
+                        for (int ks = 1; ks < KS; ++ks) yin[q] = cadd(yin[q], YH[(ks * 32 + ol) * YROW + p + P * q]);
+                    }
                     stage_b_inv(yin, j, p);
                 }
                 wave_sync();
@@ -618,21 +638,21 @@ k_fused1d(Fused1dArgs a)
     }
 }
 
-template <int N, int K, int OT, bool BF, int MODE = 0, bool REAL = false, int NW = 4, int XB = 2>
+template <int N, int K, int OT, bool BF, int MODE = 0, bool REAL = false, int NW = 4, int XB = 2, int KS = 1>
 hipError_t launch_fused1d_impl(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
-    using C = FusedCfg<N, K, OT, BF, NW, XB>;
+    using C = FusedCfg<N, K, OT, BF, NW, XB, KS>;
     static LdsLimitOnce lds_limit;
-    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL, NW, XB>),
-                                        reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL, NW, XB>)},
+    const hipError_t e = lds_limit.set({reinterpret_cast<const void *>(&k_fused1d<N, K, OT, true, BF, MODE, REAL, NW, XB, KS>),
+                                        reinterpret_cast<const void *>(&k_fused1d<N, K, OT, false, BF, MODE, REAL, NW, XB, KS>)},
                                        (int)C::LDS_DYN);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)batch_rows, (unsigned)((a.C_out + 32 * OT - 1) / (32 * OT)));
     // unmasked kernel only when every workgroup's slab of 32 OT outputs exists in full
     if (a.C_in % C::PPI == 0 && a.C_out % (32 * OT) == 0)
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE, REAL, NW, XB>), grid, dim3(C::NT), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, true, BF, MODE, REAL, NW, XB, KS>), grid, dim3(C::NT), C::LDS_DYN, s, a);
     else
-        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE, REAL, NW, XB>), grid, dim3(C::NT), C::LDS_DYN, s, a);
+        hipLaunchKernelGGL((k_fused1d<N, K, OT, false, BF, MODE, REAL, NW, XB, KS>), grid, dim3(C::NT), C::LDS_DYN, s, a);
     return hipGetLastError();
 }
 
@@ -688,11 +708,11 @@ hipError_t launch_partial(int K, const Fused1dArgs &a, long long rows, hipStream
 }
 
 // Single-operand-tile kernels (BF16x3 contraction only): NW = 8 waves in one workgroup, or NW = 4 with two workgroups per CU
-template <int N, int K, int OT, int NW = 8>
+template <int N, int K, int OT, int NW = 8, int KS = 1>
 hipError_t launch_fused1d_wide(const Fused1dArgs &a, long long batch_rows, hipStream_t s)
 {
-    static_assert(FusedCfg<N, K, OT, true, NW, 1>::FITS, "LDS budget of one gfx950 CU");
-    return launch_fused1d_impl<N, K, OT, true, 0, false, NW, 1>(a, batch_rows, s);
+    static_assert(FusedCfg<N, K, OT, true, NW, 1, KS>::FITS, "LDS budget of one gfx950 CU");
+    return launch_fused1d_impl<N, K, OT, true, 0, false, NW, 1, KS>(a, batch_rows, s);
 }
 
 // BF16x3 contraction unless the environment asks for FP32 MFMA (TFNO_CONTRACTION=f32)

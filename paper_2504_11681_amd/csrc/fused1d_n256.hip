@@ -31,9 +31,14 @@ static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipS
     // 13.6 -> 11.7 at K = 32, 14.7 -> 13.2 at K = 128; B = 64, C = 128: 23.2 -> 20.0 us); with 64-output slabs they
     // still win at K <= 64 (B = 64, C = 256: 42.7 -> 36.9 us; B = 128, C = 128: 25.4 -> 23.9 us).  With more
     // workgroups than CUs the four-wave kernel's two workgroups per CU are faster (B = 256, C = 64: 17.9 against 26.2 us).
-    if (rows * ((a.C_out + 31) / 32) <= 256) return launch_fused1d_wide<256, K, 1, 8>(a, rows, s);
+    // One or two 32-output slabs are only KT or 2 KT tiles: the 8-channel steps of a block are dealt out to the waves
+    // that would otherwise wait for the one or two waves holding tiles (cfg2: 12.9 -> 11.4 us in the same run;
+    // B = 64, C = 256: 38.0 -> 34.9 us).
+    constexpr int KT = K / 32;
+    constexpr int KS1 = 8 / KT > 4 ? 4 : 8 / KT, KS2 = 8 / (2 * KT) > 4 ? 4 : 8 / (2 * KT);
+    if (rows * ((a.C_out + 31) / 32) <= 256) return launch_fused1d_wide<256, K, 1, 8, KS1>(a, rows, s);
     if constexpr (K != 128) {
-        if (rows * ((a.C_out + 63) / 64) <= 256) return launch_fused1d_wide<256, K, 2, 8>(a, rows, s);
+        if (rows * ((a.C_out + 63) / 64) <= 256) return launch_fused1d_wide<256, K, 2, 8, KS2>(a, rows, s);
     }
     if constexpr (K == 128) {
         // (two workgroups per CU need more batch rows than CUs; below that the double-buffered kernel's single
