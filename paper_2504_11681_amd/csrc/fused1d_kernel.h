@@ -55,10 +55,9 @@ template <> struct Decomp<1024> { static constexpr int P = 32, T = 32; };
 //               prologue and epilogue hide under the other's work (with one wave per SIMD nothing else hides them).
 //   NW 8, XB 1: two waves per SIMD in one workgroup; a block is twice as many channels; carries the 256-output slab
 //               (OT = 8) at K = 128, whose accumulators alone are half of the CU's register file.
-// KS: (NW 8, XB 1 only) the 8-channel steps of a block are dealt out to KS waves per 32 x 32 tile, each with its own
-//     partial accumulator; the partial sums meet in the epilogue's LDS tile.  For narrow slabs (one or two tiles) this
-//     puts the contraction on all eight waves instead of one or two, which is what a workgroup that has the CU to
-//     itself (small batches) is waiting for.
+// KS: (BF16 contraction only) the 8-channel steps of a block are dealt out to KS waves per 32 x 32 tile, each with its
+//     own partial accumulator; the partial sums meet in the epilogue's LDS tile.  For narrow slabs (fewer tiles than
+//     waves) this puts the contraction on all waves instead of one or two that the others wait for at the barrier.
 template <int N, int K, int OT, bool BF = false, int NW_ = 4, int XB_ = 2, int KS_ = 1>
 struct FusedCfg {
     static constexpr int P = Decomp<N>::P, T = Decomp<N>::T;
@@ -96,13 +95,25 @@ struct FusedCfg {
     static_assert(PPI % 8 == 0, "an iteration is a whole number of 8-channel MFMA steps");
     static_assert(TPW <= KT && KT % TPW == 0, "a wave's tiles share one 32-output slab");
     static_assert(TPW * 32 <= 128, "accumulators must fit the register file");
-    static_assert(KS == 1 || (XB == 1 && NW == 8 && BF && TILES * KS <= NW && (PPI / 8) % KS == 0),
-                  "the channel steps of a block are split over the waves of the eight-wave kernel only");
+    static_assert(KS == 1 || (BF && TILES * KS <= NW && (PPI / 8) % KS == 0),
+                  "the channel steps of a block are split over waves that would otherwise hold no tile");
     static constexpr bool FITS = LDS_BYTES <= 160 * 1024;           // LDS budget of one gfx950 CU
     // Two workgroups per CU (two waves per SIMD, 256 registers each) wherever the accumulators leave room and LDS
     // allows: left to itself the compiler takes more than 256 registers for TPW = 2 and halves the occupancy.
     static constexpr int MIN_WG_PER_CU = (NW == 4 && (TPW <= 2 || WIDE || OT == 8) && LDS_BYTES <= 80 * 1024) ? 2 : 1;
 };
+
+// KS for a slab with fewer tiles than the workgroup has waves: as many waves per tile as there are spare waves and
+// 8-channel steps in a block (1 = every wave has a tile of its own anyway).  Measured on MI355X, unsplit -> split:
+// B 4096, C 64, N 128, K 32: 151 -> 118 us; B 8192, C 64, N 64, K 16: 196 -> 139 us; B 8192, C 32, N 64: 97 -> 58 us;
+// B 512, C 32, N 256, K 64: 15.5 -> 13.9 us; B 2048, C 32, N 512, K 64: 140 -> 131 us.
+template <int N, int K, int OT, int NW = 4>
+constexpr int split_steps_over_waves()
+{
+    using C1 = FusedCfg<N, K, OT, true, NW, NW == 8 ? 1 : 2>;
+    constexpr int steps = C1::PPI / 8, spare = C1::TILES < NW ? NW / C1::TILES : 1;
+    return spare < steps ? spare : steps;
+}
 
 // Orders this wave's LDS traffic (all lanes) without a workgroup barrier.
 __device__ __forceinline__ void wave_sync()
@@ -125,6 +136,7 @@ k_fused1d(Fused1dArgs a)
 {
     using C = FusedCfg<N, K, OT, BF, NW, XB, KS>;
     static_assert(!C::WIDE || (MODE == 0 && !REAL), "the eight-wave kernel is the fully fused complex layer only");
+    static_assert(KS == 1 || MODE != 1, "partial accumulators meet in the inverse transform's LDS tile");
     static_assert(C::FITS, "LDS budget of one gfx950 CU");
     constexpr int NWV = C::NWV;
     constexpr int P = C::P, T = C::T, Q = C::Q, PPW = C::PPW, PPI = C::PPI, CPL = C::CPL, KT = C::KT;
@@ -302,7 +314,7 @@ k_fused1d(Fused1dArgs a)
             // accumulators of the wave's tiles are interleaved (a dependent MFMA issues about four slots later).
             const unsigned *XS = reinterpret_cast<const unsigned *>(XHb) + (hi ? 1 : 0) * (KT * 128) + kt0 * 128 + (lane & 31) * 4;
 #pragma unroll
-            for (int s = 0; s < PPI / 8; ++s) {
+            for (int s = 0; s < PPI / 8 / KS; ++s) {
                 uintx4 a_re[3], a_im[3];
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
@@ -319,7 +331,7 @@ k_fused1d(Fused1dArgs a)
                 for (int i = 0; i < TPW; ++i)
 #pragma unroll
                     for (int t = 0; t < 3; ++t)
-                        b[i][t] = *reinterpret_cast<const uintx4 *>(XS + ((t * (PPI / 4) + 2 * s) * KT + i) * 128);
+                        b[i][t] = *reinterpret_cast<const uintx4 *>(XS + ((t * (PPI / 4) + 2 * (s * KS + part)) * KT + i) * 128);
                 // smallest products first: (2,0) (0,2) (1,1) (1,0) (0,1) (0,0)
                 constexpr int SA[6] = {2, 0, 1, 1, 0, 0}, SB[6] = {0, 2, 1, 0, 1, 0};
 #pragma unroll
@@ -673,7 +685,11 @@ template <int N, int K, int OT>
 hipError_t launch_fused1d_real_ot(const Fused1dArgs &a, long long rows, hipStream_t s)
 {
     if constexpr (FusedCfg<N, K, OT, true>::FITS) {
-        if (!contraction_forced_f32()) return launch_fused1d_impl<N, K, OT, true, 0, true>(a, rows, s);
+        constexpr int KS = split_steps_over_waves<N, K, OT>();
+        if (!contraction_forced_f32()) {
+            if constexpr (FusedCfg<N, K, OT, true, 4, 2, KS>::FITS) return launch_fused1d_impl<N, K, OT, true, 0, true, 4, 2, KS>(a, rows, s);
+            else return launch_fused1d_impl<N, K, OT, true, 0, true>(a, rows, s);
+        }
     }
     return launch_fused1d_impl<N, K, OT, false, 0, true>(a, rows, s);
 }
@@ -692,9 +708,11 @@ hipError_t launch_fused1d_real(const Fused1dArgs &a, long long rows, hipStream_t
 template <int N, int K, int MODE>
 hipError_t launch_partial_k(const Fused1dArgs &a, long long rows, hipStream_t s)
 {
+    // (the FFT + CGEMM kernel writes its accumulators straight to the spectrum: no split there)
+    constexpr int KS2 = MODE == 2 ? split_steps_over_waves<N, K, 2>() : 1, KS1 = MODE == 2 ? split_steps_over_waves<N, K, 1>() : 1;
     if (a.C_out > 64) return launch_fused1d_impl<N, K, 4, true, MODE>(a, rows, s);
-    if (a.C_out > 32) return launch_fused1d_impl<N, K, 2, true, MODE>(a, rows, s);
-    return launch_fused1d_impl<N, K, 1, true, MODE>(a, rows, s);
+    if (a.C_out > 32) return launch_fused1d_impl<N, K, 2, true, MODE, false, 4, 2, KS2>(a, rows, s);
+    return launch_fused1d_impl<N, K, 1, true, MODE, false, 4, 2, KS1>(a, rows, s);
 }
 template <int N, int MODE>
 hipError_t launch_partial(int K, const Fused1dArgs &a, long long rows, hipStream_t s)
@@ -721,7 +739,11 @@ hipError_t launch_fused1d(const Fused1dArgs &a, long long batch_rows, hipStream_
 {
     // (the packed three-term operand tile is 1.5x the FP32 one; the largest shapes only fit with FP32 operands)
     if constexpr (FusedCfg<N, K, OT, true>::FITS) {
-        if (!contraction_forced_f32()) return launch_fused1d_impl<N, K, OT, true>(a, batch_rows, s);
+        constexpr int KS = split_steps_over_waves<N, K, OT>();
+        if (!contraction_forced_f32()) {
+            if constexpr (FusedCfg<N, K, OT, true, 4, 2, KS>::FITS) return launch_fused1d_impl<N, K, OT, true, 0, false, 4, 2, KS>(a, batch_rows, s);
+            else return launch_fused1d_impl<N, K, OT, true>(a, batch_rows, s);
+        }
     }
     return launch_fused1d_impl<N, K, OT, false>(a, batch_rows, s);
 }

@@ -12,7 +12,7 @@ hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipS
         if (K == 64) {
             if (a.C_out > 64) return launch_fused1d_wide<128, 64, 4, 4>(a, rows, s);
             if (a.C_out > 32) return launch_fused1d_wide<128, 64, 2, 4>(a, rows, s);
-            return launch_fused1d_wide<128, 64, 1, 4>(a, rows, s);
+            return launch_fused1d_wide<128, 64, 1, 4, split_steps_over_waves<128, 64, 1>()>(a, rows, s);
         }
     }
     switch (K) {

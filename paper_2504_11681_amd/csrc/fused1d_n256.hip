@@ -34,8 +34,7 @@ static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipS
     // One or two 32-output slabs are only KT or 2 KT tiles: the 8-channel steps of a block are dealt out to the waves
     // that would otherwise wait for the one or two waves holding tiles (cfg2: 12.9 -> 11.4 us in the same run;
     // B = 64, C = 256: 38.0 -> 34.9 us).
-    constexpr int KT = K / 32;
-    constexpr int KS1 = 8 / KT > 4 ? 4 : 8 / KT, KS2 = 8 / (2 * KT) > 4 ? 4 : 8 / (2 * KT);
+    constexpr int KS1 = split_steps_over_waves<256, K, 1, 8>(), KS2 = split_steps_over_waves<256, K, 2, 8>();
     if (rows * ((a.C_out + 31) / 32) <= 256) return launch_fused1d_wide<256, K, 1, 8, KS1>(a, rows, s);
     if constexpr (K != 128) {
         if (rows * ((a.C_out + 63) / 64) <= 256) return launch_fused1d_wide<256, K, 2, 8, KS2>(a, rows, s);
