@@ -376,6 +376,10 @@ def main():
                     help="time just this layer on --config and print a short JSON line (for profiler runs of the "
                          "kernels behind the widened entry points): per_mode_weights = tfno_spectral_conv{1,2}d_permode, "
                          "real_1d = tfno_spectral_conv1d_real")
+    ap.add_argument("--shape", default=None, metavar="B,C,N,K",
+                    help="time the 1-D entry point chosen by --variant on this shape (C_in = C_out = C) instead of a named "
+                         "configuration and print a short JSON line (for the short-pencil and small-batch shapes of the "
+                         "profiles)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of one workload, time every cell of the hidden-dimension sweep (B=512, N=256, C in "
                          "{32,64,128,256}, K in {32,64,128}) with the fused kernel (the paper's variant D), the two "
@@ -427,6 +431,16 @@ def main():
                           "cells": cells}), flush=True)
         return
 
+    if args.shape:
+        from paper_2504_11681_amd import inputs
+        B, C, N, K = (int(v) for v in args.shape.split(","))
+        w = inputs.Workload(f"shape_1d_B{B}_C{C}_N{N}_K{K}", 1, B, C, C, N, K, 0)
+        vid = ["fused", "staged", "pruned", "fft_gemm", "gemm_ifft", "auto"].index(args.variant)
+        _, dev = measure(w, torch, binding, args.steps, args.warmup, ramp=args.ramp, variant=vid)
+        print(json.dumps({"metric": "us_per_layer", "workload": w.name, "entry_point": "tfno_spectral_conv1d" + VARIANT_SUFFIX[vid],
+                          "us_per_layer": dev * 1e6, "steps": args.steps, "warmup": args.warmup,
+                          "roofline": roofline_of(w, dev), "dtype": "f32", "data": "synthetic", "n_gpus": 1}), flush=True)
+        return
     w = pick_config(args.config)
     if args.only:
         fn = measure_permode if args.only == "per_mode_weights" else measure_real
