@@ -85,7 +85,17 @@ struct FusedCfg {
     static constexpr int NWV = BF ? PPI / 2 / KS : PPI;  // W values a lane holds per iteration
     static constexpr size_t LDS_Z = sizeof(c64) * NW * PPW * ZS;
     static constexpr size_t LDS_XH = sizeof(float) * XB * XH_BUF;
-    static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * KS * 32 * YROW;
+    // Partial sums of a split contraction: KS copies of the epilogue tile that the inverse transform adds up as it
+    // reads them, or, where only that lets a third workgroup fit the CU's LDS, ONE copy that the KS waves of a tile add
+    // to in turn (a barrier per turn).
+    static constexpr size_t lds_with_copies(int c)
+    {
+        const size_t yh = sizeof(c64) * c * 32 * YROW, xh = sizeof(float) * XB * XH_BUF;
+        return sizeof(c64) * NW * PPW * ZS + (xh > yh ? xh : yh) + sizeof(c64) * N;
+    }
+    static constexpr bool YH_TURNS = KS > 1 && NW == 4 && lds_with_copies(KS) > 53 * 1024 && lds_with_copies(1) <= 53 * 1024;
+    static constexpr int YH_COPIES = YH_TURNS ? 1 : KS;
+    static constexpr size_t LDS_YH = DIRECT ? 0 : sizeof(c64) * YH_COPIES * 32 * YROW;
     static constexpr size_t LDS_TW = sizeof(c64) * N;               // twiddles w_N^(t p), laid out [t][p] (static)
     static constexpr size_t LDS_DYN = LDS_Z + (LDS_XH > LDS_YH ? LDS_XH : LDS_YH);   // dynamic part
     static constexpr size_t LDS_BYTES = LDS_DYN + LDS_TW;
@@ -102,7 +112,7 @@ struct FusedCfg {
     // allows: left to itself the compiler takes more than 256 registers for TPW = 2 and halves the occupancy.
     // Three for N = 64 where LDS allows it and the split contraction has shrunk the weight registers (K <= 32: 174
     // registers without the bound, no spills with it; the 16-point slices of N = 256 spill about 100 bytes).
-    static constexpr int MIN_WG_PER_CU = (NW == 4 && KS > 1 && P <= 8 && LDS_BYTES <= 53 * 1024) ? 3
+    static constexpr int MIN_WG_PER_CU = (NW == 4 && ((KS > 1 && P <= 8) || XB == 1) && LDS_BYTES <= 53 * 1024) ? 3
                                          : (NW == 4 && (TPW <= 2 || WIDE || OT == 8) && LDS_BYTES <= 80 * 1024) ? 2 : 1;
 };
 
@@ -612,22 +622,43 @@ k_fused1d(Fused1dArgs a)
     } else {
         __syncthreads();   // every wave is done reading XH, which YH aliases
         for (int ot = 0; ot < OT; ++ot) {
-            if (has_tiles && ot == ot_w) {
-                // accumulator layout of the 32x32 MFMA: register r of lane l holds
-                //   row (output)  8*(r/4) + 4*(l/32) + r%4,   column (mode) l%32
+            // accumulator layout of the 32x32 MFMA: register r of lane l holds
+            //   row (output)  8*(r/4) + 4*(l/32) + r%4,   column (mode) l%32
+            if constexpr (C::YH_TURNS) {
+                for (int turn = 0; turn < KS; ++turn) {
+                    if (has_tiles && ot == ot_w && part == turn) {
 #pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    const int k = 32 * (kt0 + i) + (lane & 31);
-                    if (k < K) {
+                        for (int i = 0; i < TPW; ++i) {
+                            const int k = 32 * (kt0 + i) + (lane & 31);
+                            if (k < K) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int ol = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                            YH[(part * 32 + ol) * YROW + k] = make_float2(acc_re[i][r], acc_im[i][r]);
+                                for (int r = 0; r < 16; ++r) {
+                                    const int ol = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                                    c64 v2 = make_float2(acc_re[i][r], acc_im[i][r]);
+                                    if (turn != 0) v2 = cadd(v2, YH[ol * YROW + k]);
+                                    YH[ol * YROW + k] = v2;
+                                }
+                            }
+                        }
+                    }
+                    __syncthreads();
+                }
+            } else {
+                if (has_tiles && ot == ot_w) {
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) {
+                        const int k = 32 * (kt0 + i) + (lane & 31);
+                        if (k < K) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int ol = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                                YH[(part * 32 + ol) * YROW + k] = make_float2(acc_re[i][r], acc_im[i][r]);
+                            }
                         }
                     }
                 }
+                __syncthreads();
             }
-            __syncthreads();
             // wave w inverts rows RPW w .. RPW w + RPW - 1 of the slab, PPW pencils per round, in its private Z tile
             for (int rd = 0; rd < C::RPW / PPW; ++rd) {
 #pragma unroll
@@ -640,7 +671,7 @@ k_fused1d(Fused1dArgs a)
                     for (int q = 0; q < Q; ++q) {
                         yin[q] = YH[ol * YROW + p + P * q];
 #pragma unroll
-                        for (int ks = 1; ks < KS; ++ks) yin[q] = cadd(yin[q], YH[(ks * 32 + ol) * YROW + p + P * q]);
+                        for (int ks = 1; ks < C::YH_COPIES; ++ks) yin[q] = cadd(yin[q], YH[(ks * 32 + ol) * YROW + p + P * q]);
                     }
                     stage_b_inv(yin, j, p);
                 }

@@ -15,6 +15,15 @@ hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipS
             return launch_fused1d_wide<128, 64, 1, 4, split_steps_over_waves<128, 64, 1>()>(a, rows, s);
         }
     }
+    // K <= 32, 33 .. 64 outputs, more than two batch rows per CU: the single operand tile again, here because it lets
+    // THREE workgroups share a CU: 52 KB of LDS once the two partial sums of the split contraction are added in turns
+    // into one epilogue tile, 156 registers.  B 4096, C 64: 117 -> 110 us (K = 32), 116 -> 106 us (K = 16); C 48:
+    // 102 -> 92 us.  With 32 outputs (four partial sums, three extra barriers) it measured slower (54 -> 59 us), and
+    // at B = 512 there is no third workgroup to place (16.3 -> 17.0 us).
+    if (rows > 512 && a.C_out > 32 && a.C_out <= 64 && !contraction_forced_f32() && !generic_kernels_forced()) {
+        if (K == 32) return launch_fused1d_wide<128, 32, 2, 4, split_steps_over_waves<128, 32, 2>()>(a, rows, s);
+        if (K == 16) return launch_fused1d_wide<128, 16, 2, 4, split_steps_over_waves<128, 16, 2>()>(a, rows, s);
+    }
     switch (K) {
     case 16:
         switch (pick_output_tiles(a.C_out, rows, 4)) {

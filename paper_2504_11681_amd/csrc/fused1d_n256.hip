@@ -39,6 +39,18 @@ static hipError_t launch_special_n256(const Fused1dArgs &a, long long rows, hipS
     if constexpr (K != 128) {
         if (rows * ((a.C_out + 63) / 64) <= 256) return launch_fused1d_wide<256, K, 2, 8, KS2>(a, rows, s);
     }
+    // K <= 64 with more than four batch rows per CU: the single operand tile leaves room for THREE workgroups per CU
+    // (49 KB of LDS, 163 - 168 registers) where the instantiation does not spill: whole channel blocks, and at
+    // K = 64 at most 64 outputs (B 2048: C 64 / 128 at K = 32 106 -> 100 / 208 -> 200 us, C 32 / 64 at K = 64
+    // 58 -> 53 / 110 -> 108 us; with spills, C 128 at K = 64 236 -> 282 us and masked C 48 91 -> 99 us, not used).
+    if constexpr (K != 128) {
+        const int ot = a.C_out > 64 ? 4 : a.C_out > 32 ? 2 : 1;
+        if (rows > 1024 && a.C_in % 16 == 0 && a.C_out % (32 * ot) == 0 && (K == 32 || ot <= 2)) {
+            if (ot == 4) return launch_fused1d_wide<256, K, 4, 4, split_steps_over_waves<256, K, 4>()>(a, rows, s);
+            if (ot == 2) return launch_fused1d_wide<256, K, 2, 4, split_steps_over_waves<256, K, 2>()>(a, rows, s);
+            return launch_fused1d_wide<256, K, 1, 4, split_steps_over_waves<256, K, 1>()>(a, rows, s);
+        }
+    }
     if constexpr (K == 128) {
         // (two workgroups per CU need more batch rows than CUs; below that the double-buffered kernel's single
         // barrier per block is the better deal)

@@ -836,6 +836,15 @@ N256_SPECIAL = [
     (300, 20, 70, 128, 64), (260, 32, 33, 128, 50), (258, 64, 128, 128, 64), (257, 5, 9, 128, 64),
     (300, 16, 200, 128, 64),     # ... two slabs per row; the dispatch keeps the fused kernel here
     (300, 16, 200, 128, 32),     # ... and takes the CGEMM + iFFT variant at K = 32
+    # N = 128, K <= 32, 33 .. 64 outputs, more than two batch rows per CU: single operand tile, the partial sums of the
+    # split contraction added in turns into one epilogue tile (three workgroups per CU)
+    (600, 20, 40, 128, 32), (520, 32, 64, 128, 32), (513, 5, 40, 128, 16), (600, 64, 33, 128, 20), (530, 32, 64, 128, 16),
+    (512, 32, 64, 128, 32),      # one row short of the rule: the double-buffered kernel
+    (600, 32, 32, 128, 32),      # 32 outputs: the double-buffered kernel, four partial sums side by side
+    # N = 256, K <= 64, more than four batch rows per CU, whole channel blocks: single operand tile, three workgroups per CU
+    (1025, 16, 32, 256, 32), (1100, 32, 64, 256, 64), (1030, 16, 128, 256, 32), (1026, 32, 64, 256, 20),
+    (1030, 16, 128, 256, 64),    # K = 64 with 128 outputs would spill there: the double-buffered kernel
+    (1030, 24, 64, 256, 32),     # 24 channels are not whole blocks: the double-buffered kernel
 ]
 
 
