@@ -447,7 +447,7 @@ hipError_t fused1d_real_launch(int N, int K, const Fused1dArgs &a, long long row
     if (!fused1d_real_supported(N, K)) return hipErrorInvalidValue;
     // N = 1024: the symmetric-wave kernel where it exists and no bins are masked (it has no mode mask)
     // (fewer than half a chip of workgroups: the four-wave kernel's narrower slabs, unless TFNO_KERNEL=sym)
-    const bool sym_fills = (kernel_choice() == 0 && rows * ((a.C_out + 127) / 128) >= 128) || kernel_choice() == 3;
+    const bool sym_fills = (kernel_choice() == 0 && rows * ((a.C_out + 127) / 128) >= 128 && a.C_out > 64) || kernel_choice() == 3;
     if (fused1d_sym_supported(N, K) && a.K_keep == K && sym_fills && !contraction_forced_f32())
         return fused1d_sym_real_launch(N, K, a, rows, s);
     switch (N) {
@@ -511,7 +511,10 @@ hipError_t fused1d_launch(int N, int K, const Fused1dArgs &a, long long rows, hi
         // with its narrower output slabs puts the idle CUs to work -- B = 64, C = 128: 70 against 83 us; B = 64, C = 64:
         // 41 against 62 us; from B = 128 on the symmetric kernel is level or ahead)
         // TFNO_KERNEL=sym keeps the symmetric kernel for every batch size.
-        const bool fills = rows * ((a.C_out + 127) / 128) >= 128;
+        // (and more than 64 outputs: both kernels contract and invert whole 128-output slabs, so for narrower layers
+        // the four-wave kernel with a 32- or 64-output slab is ahead -- B = 1024, C = 32: 127 against 180 us at
+        // K = 128, 121 against 163 us at K = 64; B = 512, C = 64: 126 against 138 us and 124 against 130 us)
+        const bool fills = rows * ((a.C_out + 127) / 128) >= 128 && a.C_out > 64;
         if (exact && ((which == 0 && fills) || which == 3) && fused1d_sym_supported(N, K)) return fused1d_sym_launch(N, K, a, rows, s);
         if (exact && (which == 1 || (which == 0 && fills)) && fused1d_ws_supported(N, K)) return fused1d_ws_launch(N, K, a, rows, s);
     }

@@ -88,6 +88,8 @@ SMALL_1D = [
     (2, 16, 128, 1024, 128),
     (128, 16, 128, 1024, 64),   # half a chip of workgroups: the symmetric-wave kernel by default (below: the four-wave one)
     (70, 9, 130, 1024, 128),    # ... with masks (70 rows x 2 slabs)
+    (130, 16, 64, 1024, 64),    # at most 64 outputs: the four-wave kernel whatever the batch
+    (130, 16, 65, 1024, 64),    # one output more: the symmetric-wave kernel, slab half empty
 ]
 
 
@@ -471,7 +473,9 @@ REAL_1D = [(4, 16, 16, 64, 16), (3, 5, 7, 64, 8), (2, 33, 40, 64, 32), (3, 9, 70
            # count between the built sizes (stays on the four-wave kernel, which masks bins)
            (2, 16, 128, 1024, 64), (2, 64, 256, 1024, 64), (2, 9, 11, 1024, 100),
            # enough workgroups for the symmetric-wave kernel by default (smaller batches run the four-wave kernel)
-           (128, 16, 128, 1024, 64), (70, 9, 130, 1024, 128)]
+           (128, 16, 128, 1024, 64), (70, 9, 130, 1024, 128),
+           # at most 64 outputs: the four-wave kernel whatever the batch; one more: the symmetric-wave kernel
+           (130, 16, 64, 1024, 64), (130, 16, 65, 1024, 64)]
 
 
 @pytest.mark.parametrize("shape", REAL_1D, ids=lambda s: "B%d_Ci%d_Co%d_N%d_K%d" % s)
