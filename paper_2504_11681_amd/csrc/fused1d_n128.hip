@@ -24,6 +24,12 @@ hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipS
         if (K == 32) return launch_fused1d_wide<128, 32, 2, 4, split_steps_over_waves<128, 32, 2>()>(a, rows, s);
         if (K == 16) return launch_fused1d_wide<128, 16, 2, 4, split_steps_over_waves<128, 16, 2>()>(a, rows, s);
     }
+    // ... and with more than 64 outputs and whole channel blocks (159 registers; the masked instantiation spills):
+    // B 2048, C 128: 131 -> 124 us (K = 32), 128 -> 122 us (K = 16); B 1024, C 256: 197 -> 187 us.
+    if (rows > 512 && a.C_out > 64 && a.C_in % 32 == 0 && a.C_out % 128 == 0 && !contraction_forced_f32() && !generic_kernels_forced()) {
+        if (K == 16) return launch_fused1d_wide<128, 16, 4, 4>(a, rows, s);
+        if (K == 32) return launch_fused1d_wide<128, 32, 4, 4>(a, rows, s);
+    }
     switch (K) {
     case 16:
         switch (pick_output_tiles(a.C_out, rows, 4)) {

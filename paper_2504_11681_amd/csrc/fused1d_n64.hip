@@ -5,6 +5,15 @@ namespace tfno {
 
 hipError_t fused1d_launch_n64(int K, const Fused1dArgs &a, long long rows, hipStream_t s)
 {
+    // More than 64 outputs, K <= 32, more than two batch rows per CU: the single-operand-tile form takes 145 - 149
+    // registers against 202 for the double-buffered one, so three workgroups share a CU (B 4096, C 128: 167 -> 163 us;
+    // C 96: 139 -> 125 us).  (With at most 64 outputs the split contraction already gets the double-buffered form
+    // there.)
+    if (rows > 512 && a.C_out > 64 && !contraction_forced_f32() && !generic_kernels_forced()) {
+        if (K == 8) return launch_fused1d_wide<64, 8, 4, 4>(a, rows, s);
+        if (K == 16) return launch_fused1d_wide<64, 16, 4, 4>(a, rows, s);
+        if (K == 32) return launch_fused1d_wide<64, 32, 4, 4>(a, rows, s);
+    }
     switch (K) {
     case 8:
         switch (pick_output_tiles(a.C_out, rows, 4)) {

@@ -845,6 +845,9 @@ N256_SPECIAL = [
     (600, 20, 40, 128, 32), (520, 32, 64, 128, 32), (513, 5, 40, 128, 16), (600, 64, 33, 128, 20), (530, 32, 64, 128, 16),
     (512, 32, 64, 128, 32),      # one row short of the rule: the double-buffered kernel
     (600, 32, 32, 128, 32),      # 32 outputs: the double-buffered kernel, four partial sums side by side
+    # ... and the same form with four output tiles: N = 128 (whole channel blocks only), N = 64 (any channel count)
+    (520, 32, 128, 128, 32), (513, 64, 256, 128, 16), (520, 32, 130, 128, 32), (520, 20, 128, 128, 32),
+    (600, 32, 128, 64, 16), (520, 20, 96, 64, 32), (513, 9, 70, 64, 8), (512, 32, 128, 64, 16),
     # N = 256, K <= 64, more than four batch rows per CU, whole channel blocks: single operand tile, three workgroups per CU
     (1025, 16, 32, 256, 32), (1100, 32, 64, 256, 64), (1030, 16, 128, 256, 32), (1026, 32, 64, 256, 20),
     (1030, 16, 128, 256, 64),    # K = 64 with 128 outputs would spill there: the double-buffered kernel
