@@ -110,9 +110,11 @@ struct FusedCfg {
     static constexpr bool FITS = LDS_BYTES <= 160 * 1024;           // LDS budget of one gfx950 CU
     // Two workgroups per CU (two waves per SIMD, 256 registers each) wherever the accumulators leave room and LDS
     // allows: left to itself the compiler takes more than 256 registers for TPW = 2 and halves the occupancy.
+    // Four for the single-operand-tile form of N = 64 with one output tile (118 registers).
     // Three for N = 64 where LDS allows it and the split contraction has shrunk the weight registers (K <= 32: 174
     // registers without the bound, no spills with it; the 16-point slices of N = 256 spill about 100 bytes).
-    static constexpr int MIN_WG_PER_CU = (NW == 4 && ((KS > 1 && P <= 8) || XB == 1) && LDS_BYTES <= 53 * 1024) ? 3
+    static constexpr int MIN_WG_PER_CU = (NW == 4 && XB == 1 && P <= 8 && OT == 1 && LDS_BYTES <= 40 * 1024) ? 4
+                                         : (NW == 4 && ((KS > 1 && P <= 8) || XB == 1) && LDS_BYTES <= 53 * 1024) ? 3
                                          : (NW == 4 && (TPW <= 2 || WIDE || OT == 8) && LDS_BYTES <= 80 * 1024) ? 2 : 1;
 };
 

@@ -20,6 +20,11 @@ hipError_t fused1d_launch_n128(int K, const Fused1dArgs &a, long long rows, hipS
     // into one epilogue tile, 156 registers.  B 4096, C 64: 117 -> 110 us (K = 32), 116 -> 106 us (K = 16); C 48:
     // 102 -> 92 us.  With 32 outputs (four partial sums, three extra barriers) it measured slower (54 -> 59 us), and
     // at B = 512 there is no third workgroup to place (16.3 -> 17.0 us).
+    // (... except for a single, half-empty block of input channels: B 8192, C 16: 90 -> 78 us)
+    if (rows > 512 && a.C_out <= 32 && a.C_in <= 16 && !contraction_forced_f32() && !generic_kernels_forced()) {
+        if (K == 32) return launch_fused1d_wide<128, 32, 1, 4, split_steps_over_waves<128, 32, 1>()>(a, rows, s);
+        if (K == 16) return launch_fused1d_wide<128, 16, 1, 4, split_steps_over_waves<128, 16, 1>()>(a, rows, s);
+    }
     if (rows > 512 && a.C_out > 32 && a.C_out <= 64 && !contraction_forced_f32() && !generic_kernels_forced()) {
         if (K == 32) return launch_fused1d_wide<128, 32, 2, 4, split_steps_over_waves<128, 32, 2>()>(a, rows, s);
         if (K == 16) return launch_fused1d_wide<128, 16, 2, 4, split_steps_over_waves<128, 16, 2>()>(a, rows, s);

@@ -14,6 +14,15 @@ hipError_t fused1d_launch_n64(int K, const Fused1dArgs &a, long long rows, hipSt
         if (K == 16) return launch_fused1d_wide<64, 16, 4, 4>(a, rows, s);
         if (K == 32) return launch_fused1d_wide<64, 32, 4, 4>(a, rows, s);
     }
+    // At most 32 outputs, K <= 32, more than three batch rows per CU: the single-operand-tile form with the split
+    // contraction takes 118 registers and 31 KB of LDS, so FOUR workgroups share a CU (B 8192, C 32: 57 -> 55 us;
+    // B 16384, C 16: 89 -> 76 us).  With 33 - 64 outputs it gains 1 - 3 % on whole channel blocks and loses as much on
+    // masked ones, and stays on the double-buffered form.
+    if (rows > 768 && a.C_out <= 32 && !contraction_forced_f32() && !generic_kernels_forced()) {
+        if (K == 8) return launch_fused1d_wide<64, 8, 1, 4, split_steps_over_waves<64, 8, 1>()>(a, rows, s);
+        if (K == 16) return launch_fused1d_wide<64, 16, 1, 4, split_steps_over_waves<64, 16, 1>()>(a, rows, s);
+        if (K == 32) return launch_fused1d_wide<64, 32, 1, 4, split_steps_over_waves<64, 32, 1>()>(a, rows, s);
+    }
     switch (K) {
     case 8:
         switch (pick_output_tiles(a.C_out, rows, 4)) {

@@ -848,6 +848,10 @@ N256_SPECIAL = [
     # ... and the same form with four output tiles: N = 128 (whole channel blocks only), N = 64 (any channel count)
     (520, 32, 128, 128, 32), (513, 64, 256, 128, 16), (520, 32, 130, 128, 32), (520, 20, 128, 128, 32),
     (600, 32, 128, 64, 16), (520, 20, 96, 64, 32), (513, 9, 70, 64, 8), (512, 32, 128, 64, 16),
+    # N = 64, at most 32 outputs, more than three batch rows per CU: single operand tile, four workgroups per CU;
+    # N = 128 likewise for a single half-empty block of input channels
+    (800, 32, 32, 64, 16), (770, 16, 20, 64, 32), (769, 5, 9, 64, 8), (768, 32, 32, 64, 16),
+    (600, 16, 16, 128, 32), (520, 9, 30, 128, 16), (600, 17, 16, 128, 32),
     # N = 256, K <= 64, more than four batch rows per CU, whole channel blocks: single operand tile, three workgroups per CU
     (1025, 16, 32, 256, 32), (1100, 32, 64, 256, 64), (1030, 16, 128, 256, 32), (1026, 32, 64, 256, 20),
     (1030, 16, 128, 256, 64),    # K = 64 with 128 outputs would spill there: the double-buffered kernel
